@@ -1,0 +1,184 @@
+/*
+ * sparse_conv.h -- C ABI of the MI355X (gfx950) direct sparse convolution library.
+ *
+ * The operation is the one defined in the paper's section "Convolution operation using a sparse
+ * operation on GPGPU": a dense NCHW activation tensor is convolved (cross-correlation, zero
+ * padding, no bias) with an unstructured-pruned weight tensor stored per output channel in CSR
+ * form (rowptr RP, column index Lambda, values theta).  Every row is padded to the same stored
+ * count N_nz (the paper's "standardised sparse level"), which makes the layout a fixed-width
+ * ELL-like table, and the column indices are "pre-stretched" once into flat offsets into the
+ * padded input so the kernel (the paper's Algorithm 3) only gathers, multiplies and accumulates:
+ *
+ *     Y[b,d,p,q] = sum_{j < N_nz} theta[d,j] * Xp[b, p*s_h*Wp + q*s_w + lambda[d,j]]
+ *
+ * with Xp the zero-padded input of one sample (C planes of Hp x Wp), Hp = H + 2*pad_h,
+ * Wp = W + 2*pad_w, P = (Hp - R)/s_h + 1, Q = (Wp - S)/s_w + 1.
+ *
+ * Conventions
+ *   - All functions return sc_status_t; SC_OK is 0.  No exception crosses this boundary.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the
+ *     current device.  `stream` is a hipStream_t passed as an opaque pointer (NULL = the null stream).
+ *   - Host arrays given to the create calls are borrowed for the duration of the call and copied.
+ *   - The plan owns its device tables (weights, offsets, scales, codebook) until
+ *     sparse_conv_plan_destroy.  x, y and workspace are borrowed and never retained or freed.
+ *   - sparse_conv_forward is asynchronous on `stream`, never synchronises and never allocates.
+ *     A plan is immutable between create / set_tuning / autotune calls, so forward may be issued
+ *     concurrently on several streams as long as each uses its own workspace.
+ *   - Inputs must be finite: the zero-valued filler entries of padded rows are multiplied like any
+ *     other entry.
+ *   - Argument validation happens on the host before the first HIP call, so every error below
+ *     except SC_ERR_HIP / SC_ERR_OOM can be produced (and tested) without a GPU.
+ */
+#ifndef SPARSE_CONV_H
+#define SPARSE_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sparse_conv_plan sparse_conv_plan_t; /* opaque, library-owned */
+
+typedef enum {
+    SC_OK = 0,
+    SC_ERR_NULL = 1,        /* a required pointer is NULL */
+    SC_ERR_SHAPE = 2,       /* non-positive dimension, empty output, N <= 0 */
+    SC_ERR_CSR = 3,         /* rowptr not starting at 0 / not monotone, column outside [0, C*R*S),
+                               codebook index > 15 */
+    SC_ERR_UNSUPPORTED = 4, /* unknown dtype, missing scales/codebook for a quantised dtype,
+                               tuning that does not fit this layer */
+    SC_ERR_RANGE = 5,       /* one padded sample or one output sample has >= 2^31 elements */
+    SC_ERR_OOM = 6,         /* device or host allocation failed */
+    SC_ERR_WORKSPACE = 7,   /* workspace NULL or smaller than sparse_conv_workspace_size */
+    SC_ERR_HIP = 8          /* a HIP runtime call or kernel launch failed */
+} sc_status_t;
+
+/* Storage / arithmetic variants (weights x activations -> accumulator -> output):
+ *   SC_F32     f32 x f32 -> f32 -> f32
+ *   SC_F16     f16 x f16 -> f32 -> f16 (one rounding at the store)
+ *   SC_I8      i8  x i8  -> i32 -> i32 (exact; the per-channel scales are carried, not applied)
+ *   SC_CB4_I8  4-bit index into a 16-entry i8 codebook x i8 -> i32 -> i32 (the paper's non-linear,
+ *              cluster-based quantisation: each stored weight is a centroid index) */
+typedef enum { SC_F32 = 0, SC_F16 = 1, SC_I8 = 2, SC_CB4_I8 = 3 } sc_dtype_t;
+
+/* Layer geometry.  Weights are D rows (output channels) by K = C*R*S columns, a column being the
+ * filter tap (c, r, s) flattened as (c*R + r)*S + s (PyTorch's weight.view(D, -1)). */
+typedef struct {
+    int32_t C, D, H, W, R, S, stride_h, stride_w, pad_h, pad_w;
+} sc_layer_t;
+
+/* Kernel families (sc_tuning_t.variant). */
+enum {
+    SC_VARIANT_AUTO = 0,   /* let the library pick by heuristic */
+    SC_VARIANT_GATHER = 1, /* Algorithm-3 shape: one workgroup = one output channel x a pixel tile x
+                              sub_batch samples; (theta, lambda) row in LDS; input gathered from
+                              global memory (a padded copy in the workspace when pad > 0) */
+    SC_VARIANT_SLAB = 2    /* one workgroup = one sample x an output tile x all output channels;
+                              the input tile (all C channels, halo and zero padding included) is
+                              staged once in LDS and every row of (theta, lambda) is streamed over it */
+};
+
+/* Launch shape of sparse_conv_forward; the analogue of the paper's per-layer choice of the
+ * sub-batch size sb_S that fixes the number of thread blocks N_B = b_S * D / sb_S.
+ * Fields that do not apply to a variant are ignored.  All-zero = SC_VARIANT_AUTO. */
+typedef struct {
+    int32_t variant;    /* SC_VARIANT_* */
+    int32_t wg_threads; /* workgroup size: 64..1024, multiple of 64 */
+    int32_t sub_batch;  /* GATHER: samples per workgroup (sb_S), 1, 2, 4 or 8 */
+    int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
+    int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
+    int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
+    int32_t wsrc;       /* SLAB: how a wave gets (theta, lambda): 0 = LDS broadcast read,
+                           1 = scalar loads from global memory */
+    int32_t reserved[5];
+} sc_tuning_t;
+
+typedef struct {
+    int32_t n;                     /* unified stored entries per output channel (N_nz) */
+    int32_t P, Q;                  /* output height and width */
+    int64_t X_size;                /* elements of one padded input sample, C*Hp*Wp */
+    int64_t true_nnz;              /* stored entries before row padding (sum of CSR row lengths) */
+    int64_t macs_per_sample;       /* D*P*Q*n: multiply-accumulates executed per sample */
+    int64_t useful_macs_per_sample;/* P*Q*true_nnz: those that involve a caller-supplied entry */
+    int64_t act_bytes_per_sample;  /* C*H*W*e_x + D*P*Q*e_y */
+    int64_t weight_bytes;          /* D*n*(e_w + 4) (+ scales, codebook): read once per launch */
+    int32_t lds_bytes;             /* LDS per workgroup of the current tuning */
+    int32_t grid_size;             /* workgroups per launch for the N last used by set_tuning /
+                                      autotune (0 if unknown) */
+    sc_tuning_t tuning;            /* current tuning, heuristic defaults resolved */
+} sc_plan_info_t;
+
+/* Build a plan from CSR weights (host arrays).
+ *   rowptr  [D+1]  rowptr[0] = 0, non-decreasing; nnz = rowptr[D]
+ *   colidx  [nnz]  each in [0, C*R*S); any order within a row; duplicates add up
+ *   values  [nnz]  f32 (SC_F32), IEEE half bits (SC_F16), i8 (SC_I8), u8 index < 16 (SC_CB4_I8)
+ *   scales  [D]    per-output-channel dequantisation scale, required for SC_I8 / SC_CB4_I8, else NULL
+ *   codebook[16]   i8 centroids, required for SC_CB4_I8, else NULL
+ * Rows are padded to n = max row length with zero-valued entries that repeat the row's last column
+ * (column 0 for an empty row); then a device pass stretches every column to its input offset.
+ * Errors: SC_ERR_NULL, SC_ERR_SHAPE, SC_ERR_CSR, SC_ERR_UNSUPPORTED, SC_ERR_RANGE, SC_ERR_OOM, SC_ERR_HIP.
+ * On error *out is NULL. */
+sc_status_t sparse_conv_plan_create_csr(const sc_layer_t* layer, sc_dtype_t dtype,
+                                        const int32_t* rowptr, const int32_t* colidx,
+                                        const void* values, const float* scales,
+                                        const void* codebook, void* stream,
+                                        sparse_conv_plan_t** out);
+
+/* Same, from an already unified table: colidx / values are [D][n] row-major (n >= 0). */
+sc_status_t sparse_conv_plan_create_ell(const sc_layer_t* layer, sc_dtype_t dtype, int32_t n,
+                                        const int32_t* colidx, const void* values,
+                                        const float* scales, const void* codebook, void* stream,
+                                        sparse_conv_plan_t** out);
+
+void sparse_conv_plan_destroy(sparse_conv_plan_t* plan); /* NULL is allowed */
+
+/* Geometry, traffic model and current tuning of a plan. */
+sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t* info);
+
+/* Test hook for the stretch pass: copies the device-built canonical offsets
+ * lambda[d][j] = c*Hp*Wp + r*Wp + s (elements, relative to one padded sample) to host_out [D*n].
+ * Synchronises the device. */
+sc_status_t sparse_conv_plan_debug_offsets(const sparse_conv_plan_t* plan, int32_t* host_out);
+
+/* Replace the launch shape.  Fields left 0 are filled by heuristic.  SC_ERR_UNSUPPORTED if the
+ * shape does not fit the layer (e.g. the slab does not fit in LDS); the previous tuning stays.
+ * Rebuilds the variant-specific offset table on `stream` and waits for it. */
+sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tuning_t* tuning,
+                                        void* stream);
+sc_status_t sparse_conv_plan_get_tuning(const sparse_conv_plan_t* plan, sc_tuning_t* tuning);
+
+/* Bytes of device workspace sparse_conv_forward needs for batch N with the current tuning
+ * (0 unless the GATHER variant has to materialise a padded input). */
+sc_status_t sparse_conv_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
+
+/* Upper bound of sparse_conv_workspace_size over every tuning autotune may try. */
+sc_status_t sparse_conv_workspace_size_max(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
+
+/* Y = conv(X): x_dev [N,C,H,W] unpadded, y_dev [N,D,P,Q], both contiguous device memory in the
+ * plan's storage types.  Errors: SC_ERR_NULL, SC_ERR_SHAPE (N <= 0), SC_ERR_WORKSPACE, SC_ERR_HIP. */
+sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
+                                int32_t N, void* workspace_dev, size_t workspace_bytes,
+                                void* stream);
+
+/* Per-layer launch-shape search (the gfx950 counterpart of the paper's empirical tuning of sb_S):
+ * times every candidate tuning that fits the layer on the caller's buffers (y_dev is overwritten)
+ * with HIP events on `stream`, keeps the fastest, and leaves it installed.  Synchronises.
+ * workspace must hold sparse_conv_workspace_size_max(plan, N). */
+sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
+                                      int32_t N, void* workspace_dev, size_t workspace_bytes,
+                                      void* stream);
+
+/* Number of candidates sparse_conv_plan_autotune would time for this plan, and the i-th of them
+ * (for tests that check that every candidate computes the same result). */
+sc_status_t sparse_conv_plan_num_candidates(const sparse_conv_plan_t* plan, int32_t* count);
+sc_status_t sparse_conv_plan_candidate(const sparse_conv_plan_t* plan, int32_t index,
+                                       sc_tuning_t* tuning);
+
+const char* sparse_conv_status_string(sc_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_CONV_H */

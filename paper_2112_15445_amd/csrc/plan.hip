@@ -1,0 +1,670 @@
+// Plan construction, validation, the offset-stretching pass, tuning and dispatch of the C ABI.
+//
+// Follows the paper's section "Convolution operation using a sparse operation on GPGPU": CSR rows
+// are output channels, rows are padded to one common stored count (the "standardised sparse level"),
+// and the column indices are replaced once, ahead of time, by offsets into the padded input.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "sc_internal.h"
+
+namespace sc {
+
+int elem_size_x(sc_dtype_t dt) { return dt == SC_F32 ? 4 : dt == SC_F16 ? 2 : 1; }
+int elem_size_y(sc_dtype_t dt) { return dt == SC_F16 ? 2 : 4; }
+static int elem_size_w_native(sc_dtype_t dt) { return dt == SC_F32 ? 4 : dt == SC_F16 ? 2 : 1; }
+
+// ------------------------------------------------------------------------------------------------
+// Offset-stretching pass.  One thread per stored entry: decode the column into its filter tap
+// (c, r, s) and emit the flat offset for a layout described by pitches.  With nsh = nsw = 1,
+// chan_pitch = Hp*Wp, row_pitch = Wp and scale = 1 this is the canonical offset into one padded
+// sample, c*Hp*Wp + r*Wp + s; the slab kernel uses the same pass with its LDS tile pitches, its
+// stride-phase split and scale = bytes per element.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+stretch_kernel(const int32_t* __restrict__ col, int32_t* __restrict__ lam, int64_t count, int R,
+               int S, int nsh, int nsw, int s_h, int s_w, int chan_pitch, int sub_pitch,
+               int row_pitch, int scale)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    // bit 31 of a column marks a zero-valued filler entry of the 4-bit codebook variant (a 4-bit
+    // index cannot say "zero"); it is carried over to the offset so the kernel can zero the weight
+    const int flag = col[i] & (int)0x80000000;
+    const int k = col[i] & 0x7fffffff;
+    const int c = k / (R * S);
+    const int rs = k - c * (R * S);
+    const int r = rs / S;
+    const int s = rs - r * S;
+    const int phase = (r % nsh) * nsw + (s % nsw);
+    // when a stride exceeds the filter extent only phase 0 exists along that axis and r / s_h is 0
+    lam[i] = ((c * chan_pitch + phase * sub_pitch + (r / s_h) * row_pitch + (s / s_w)) * scale) | flag;
+}
+
+sc_status_t launch_stretch(const Plan& p, int32_t* d_out, int nsh, int nsw, int s_h, int s_w,
+                           int chan_pitch, int sub_pitch, int row_pitch, int scale,
+                           hipStream_t stream)
+{
+    const int64_t count = (int64_t)p.L.D * p.n;
+    if (count == 0) return SC_OK;
+    const unsigned blocks = (unsigned)((count + 255) / 256);
+    hipLaunchKernelGGL(stretch_kernel, dim3(blocks), dim3(256), 0, stream, p.d_col, d_out, count,
+                       p.L.R, p.L.S, nsh, nsw, s_h, s_w, chan_pitch, sub_pitch, row_pitch, scale);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tuning resolution: fill heuristic defaults, derive the slab geometry, check that it fits.
+// ------------------------------------------------------------------------------------------------
+static bool is_pointwise(const sc_layer_t& L)
+{
+    return L.R == 1 && L.S == 1 && L.stride_h == 1 && L.stride_w == 1 && L.pad_h == 0 && L.pad_w == 0;
+}
+
+static int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
+static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int lds_budget, SlabGeom* g)
+{
+    const sc_layer_t& L = p.L;
+    SlabGeom o{};
+    const bool pw = is_pointwise(L);
+    o.Hf = pw ? 1 : L.H;
+    o.Wf = pw ? L.H * L.W : L.W;
+    o.Pf = pw ? 1 : p.P;
+    o.Qf = pw ? p.P * p.Q : p.Q;
+    if (TP < 1 || TQ < 1) return false;
+    o.TP = std::min(TP, o.Pf);
+    o.TQ = std::min(TQ, o.Qf);
+    o.tiles_p = (o.Pf + o.TP - 1) / o.TP;
+    o.tiles_q = (o.Qf + o.TQ - 1) / o.TQ;
+    o.nsh = std::min(L.R, L.stride_h);
+    o.nsw = std::min(L.S, L.stride_w);
+    o.SR = o.TP + (L.R - 1) / L.stride_h;
+    o.Qs = o.TQ + (L.S - 1) / L.stride_w;
+    o.sub_pitch = o.SR * o.Qs;
+    o.chan_pitch = o.nsh * o.nsw * o.sub_pitch;
+    o.F = o.TP * o.Qs;
+    if (o.F > kWave * kMaxVpt) return false;
+    o.vpt = (o.F + kWave - 1) / kWave;
+    o.nwaves = wg_threads / kWave;
+    const int64_t slab = (int64_t)L.C * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
+    if (slab > lds_budget) return false;
+    o.slab_bytes = round_up((int)slab, 16);
+    // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
+    const int64_t total = (int64_t)L.D * p.n;
+    int64_t cap = (lds_budget - o.slab_bytes - 64) / 8;
+    cap = std::min<int64_t>(cap, 4096);
+    cap = std::min<int64_t>(cap, std::max<int64_t>(total, 1));
+    if (cap < std::min<int64_t>(std::max<int64_t>(total, 1), 512)) return false;
+    o.wcap = (int)cap;
+    if (p.n == 0) {
+        o.DS = std::min(L.D, o.nwaves);
+        o.JC = 0;
+    } else if ((int64_t)p.n * std::min(o.nwaves, L.D) <= o.wcap) {
+        o.JC = p.n;                       // whole rows per stage
+        o.DS = std::min(L.D, o.wcap / p.n);
+    } else {
+        o.DS = std::min(L.D, o.nwaves);   // one row per wave, rows cut into chunks
+        o.JC = std::max(1, o.wcap / o.DS);
+    }
+    o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64;
+    if (o.lds_bytes > kMaxLdsBytes) return false;
+    // 16-byte staging needs every tile row start and the plane pitch to be 16-byte aligned
+    const int epv = 16 / p.ex;
+    o.vec = (pw && (o.Wf % epv == 0) && (o.TQ % epv == 0)) ? 1 : 0;
+    o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
+    o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
+    o.inv_Qs = 1.0f / (float)o.Qs;
+    *g = o;
+    return true;
+}
+
+sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom)
+{
+    sc_tuning_t t = in;
+    const sc_layer_t& L = p.L;
+    if (t.variant < SC_VARIANT_AUTO || t.variant > SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
+    if (t.wg_threads == 0) t.wg_threads = 256;
+    if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc < 0 || t.wsrc > 1) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc == 1 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
+    const bool want_slab = t.variant != SC_VARIANT_GATHER;
+    if (want_slab) {
+        const bool pw = is_pointwise(L);
+        if (t.wg_per_cu == 0) t.wg_per_cu = 2;
+        if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
+        const int budget = kMaxLdsBytes / t.wg_per_cu;
+        SlabGeom g{};
+        bool ok = false;
+        if (t.tile_q == 0) {
+            // heuristic: widest tile that fits; pointwise layers tile the flattened plane in
+            // multiples of a wave, other layers take full rows and as many of them as fit
+            if (pw) {
+                const int hw = L.H * L.W;
+                for (int v = kMaxVpt; v >= 1 && !ok; --v) {
+                    const int tq = std::min(hw, 64 * v);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, budget, &g);
+                }
+            } else {
+                for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, budget, &g);
+                    if (t.tile_p) break;
+                }
+            }
+        } else {
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, budget, &g);
+        }
+        if (ok) {
+            t.variant = SC_VARIANT_SLAB;
+            t.tile_p = g.TP;
+            t.tile_q = g.TQ;
+            t.sub_batch = 0;
+            *out = t;
+            *geom = g;
+            return SC_OK;
+        }
+        if (t.variant == SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
+    }
+    t.variant = SC_VARIANT_GATHER;
+    if (t.sub_batch == 0) t.sub_batch = 4;
+    if (t.sub_batch != 1 && t.sub_batch != 2 && t.sub_batch != 4 && t.sub_batch != 8)
+        return SC_ERR_UNSUPPORTED;
+    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = 0;
+    *out = t;
+    *geom = SlabGeom{};
+    return SC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host-side validation and row unification.
+// ------------------------------------------------------------------------------------------------
+static sc_status_t validate_layer(const sc_layer_t* L, sc_dtype_t dt, const float* scales,
+                                  const void* codebook, Plan* p)
+{
+    if (!L) return SC_ERR_NULL;
+    if (dt != SC_F32 && dt != SC_F16 && dt != SC_I8 && dt != SC_CB4_I8) return SC_ERR_UNSUPPORTED;
+    if (L->C <= 0 || L->D <= 0 || L->H <= 0 || L->W <= 0 || L->R <= 0 || L->S <= 0 ||
+        L->stride_h <= 0 || L->stride_w <= 0 || L->pad_h < 0 || L->pad_w < 0)
+        return SC_ERR_SHAPE;
+    const int64_t Hp = (int64_t)L->H + 2 * (int64_t)L->pad_h, Wp = (int64_t)L->W + 2 * (int64_t)L->pad_w;
+    if (Hp < L->R || Wp < L->S) return SC_ERR_SHAPE;
+    const int64_t P = (Hp - L->R) / L->stride_h + 1, Q = (Wp - L->S) / L->stride_w + 1;
+    const int64_t K = (int64_t)L->C * L->R * L->S;
+    const int64_t X_size = (int64_t)L->C * Hp * Wp;
+    const int64_t Y_size = (int64_t)L->D * P * Q;
+    if (K >= (1ll << 31) || X_size >= (1ll << 31) || Y_size >= (1ll << 31)) return SC_ERR_RANGE;
+    if ((dt == SC_I8 || dt == SC_CB4_I8) && !scales) return SC_ERR_UNSUPPORTED;
+    if (dt == SC_CB4_I8 && !codebook) return SC_ERR_UNSUPPORTED;
+    p->L = *L;
+    p->dtype = dt;
+    p->Hp = (int)Hp;
+    p->Wp = (int)Wp;
+    p->P = (int)P;
+    p->Q = (int)Q;
+    p->X_size = X_size;
+    p->ex = elem_size_x(dt);
+    p->ey = elem_size_y(dt);
+    return SC_OK;
+}
+
+// Copy of the caller's values as raw native-width elements, unified to [D][n] with rows sorted by
+// column (stable, so equal columns keep the caller's order).
+struct HostTable {
+    std::vector<int32_t> col;
+    std::vector<uint8_t> val;  // native element bytes: 4 / 2 / 1 / 1 (index)
+};
+
+static sc_status_t unify_rows(const Plan& p, const int32_t* rowptr, const int32_t* colidx,
+                              const void* values, int n, HostTable* t)
+{
+    const int D = p.L.D, wsz = elem_size_w_native(p.dtype);
+    const int64_t K = (int64_t)p.L.C * p.L.R * p.L.S;
+    const uint8_t* v = static_cast<const uint8_t*>(values);
+    t->col.assign((size_t)D * n, 0);
+    t->val.assign((size_t)D * n * wsz, 0);
+    std::vector<int32_t> order;
+    for (int d = 0; d < D; ++d) {
+        const int64_t beg = rowptr[d], len = (int64_t)rowptr[d + 1] - rowptr[d];
+        for (int64_t k = beg; k < beg + len; ++k) {
+            if (colidx[k] < 0 || colidx[k] >= K) return SC_ERR_CSR;
+            if (p.dtype == SC_CB4_I8 && v[k] > 15) return SC_ERR_CSR;
+        }
+        order.resize((size_t)len);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t a, int32_t b) { return colidx[beg + a] < colidx[beg + b]; });
+        for (int j = 0; j < n; ++j) {
+            const size_t o = (size_t)d * n + j;
+            if (j < len) {
+                t->col[o] = colidx[beg + order[j]];
+                std::memcpy(&t->val[o * wsz], v + (size_t)(beg + order[j]) * wsz, wsz);
+            } else {
+                // filler: explicit zero "marked non-zero", at the row's last (largest) column
+                t->col[o] = len > 0 ? (t->col[(size_t)d * n + len - 1] & 0x7fffffff) : 0;
+                if (p.dtype == SC_CB4_I8) t->col[o] |= (int32_t)0x80000000;  // weight must read as 0
+            }
+        }
+    }
+    return SC_OK;
+}
+
+static void free_device(Plan* p)
+{
+    if (p->d_col) (void)hipFree(p->d_col);
+    if (p->d_theta) (void)hipFree(p->d_theta);
+    if (p->d_lam) (void)hipFree(p->d_lam);
+    if (p->d_lam_slab) (void)hipFree(p->d_lam_slab);
+    if (p->d_wl32) (void)hipFree(p->d_wl32);
+    p->d_wl32 = nullptr;
+    if (p->d_scales) (void)hipFree(p->d_scales);
+    if (p->d_codebook) (void)hipFree(p->d_codebook);
+    p->d_col = p->d_lam = p->d_lam_slab = nullptr;
+    p->d_theta = nullptr;
+    p->d_scales = nullptr;
+    p->d_codebook = nullptr;
+}
+
+static sc_status_t hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return SC_OK;
+    return e == hipErrorOutOfMemory ? SC_ERR_OOM : SC_ERR_HIP;
+}
+
+static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom& g, hipStream_t stream)
+{
+    if (t.variant == SC_VARIANT_SLAB) {
+        sc_status_t st = launch_stretch(*p, p->d_lam_slab, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
+                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex, stream);
+        if (st != SC_OK) return st;
+        if (t.wsrc == 1) {
+            st = expand_weights(*p, stream);
+            if (st != SC_OK) return st;
+        }
+        if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
+    }
+    p->tuning = t;
+    p->geom = g;
+    return SC_OK;
+}
+
+// Upload the unified table, run the stretch pass, install the default tuning.
+static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, const void* codebook,
+                                 hipStream_t stream)
+{
+    const size_t cnt = (size_t)p->L.D * p->n;
+    const int wsz = elem_size_w_native(p->dtype);
+    p->h_col = std::move(tab.col);
+    // resolve the default tuning first: it is pure host arithmetic
+    sc_tuning_t t{};
+    SlabGeom g{};
+    sc_status_t st = resolve_tuning(*p, sc_tuning_t{}, &t, &g);
+    if (st != SC_OK) return st;
+
+    std::vector<uint8_t> packed;
+    const uint8_t* theta_src = tab.val.data();
+    size_t theta_bytes = cnt * wsz;
+    if (p->dtype == SC_CB4_I8) {
+        // two 4-bit indices per byte, even entry in the low nibble, over the flat [D*n] table
+        packed.assign((cnt + 1) / 2, 0);
+        for (size_t i = 0; i < cnt; ++i) packed[i / 2] |= (uint8_t)((tab.val[i] & 15) << ((i & 1) * 4));
+        theta_src = packed.data();
+        theta_bytes = packed.size();
+    }
+    hipError_t e;
+    if (cnt) {
+        if ((e = hipMalloc((void**)&p->d_col, cnt * 4)) != hipSuccess) return hip_status(e);
+        if ((e = hipMalloc((void**)&p->d_lam, cnt * 4)) != hipSuccess) return hip_status(e);
+        if ((e = hipMalloc((void**)&p->d_lam_slab, cnt * 4)) != hipSuccess) return hip_status(e);
+        if ((e = hipMalloc(&p->d_theta, theta_bytes)) != hipSuccess) return hip_status(e);
+        if (p->dtype != SC_CB4_I8 && (e = hipMalloc((void**)&p->d_wl32, cnt * 8)) != hipSuccess) return hip_status(e);
+        if ((e = hipMemcpyAsync(p->d_col, p->h_col.data(), cnt * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return hip_status(e);
+        if ((e = hipMemcpyAsync(p->d_theta, theta_src, theta_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return hip_status(e);
+    }
+    if (scales) {
+        if ((e = hipMalloc((void**)&p->d_scales, (size_t)p->L.D * 4)) != hipSuccess) return hip_status(e);
+        if ((e = hipMemcpyAsync(p->d_scales, scales, (size_t)p->L.D * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return hip_status(e);
+    }
+    if (p->dtype == SC_CB4_I8) {
+        if ((e = hipMalloc((void**)&p->d_codebook, 16)) != hipSuccess) return hip_status(e);
+        if ((e = hipMemcpyAsync(p->d_codebook, codebook, 16, hipMemcpyHostToDevice, stream)) != hipSuccess)
+            return hip_status(e);
+    }
+    // canonical offsets into one padded sample
+    st = launch_stretch(*p, p->d_lam, 1, 1, 1, 1, p->Hp * p->Wp, 0, p->Wp, 1, stream);
+    if (st != SC_OK) return st;
+    // the host staging buffers must outlive the async copies
+    if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
+    return install_tuning(p, t, g, stream);
+}
+
+}  // namespace sc
+
+using namespace sc;
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* sparse_conv_status_string(sc_status_t s)
+{
+    switch (s) {
+        case SC_OK: return "ok";
+        case SC_ERR_NULL: return "null pointer argument";
+        case SC_ERR_SHAPE: return "invalid layer shape or batch size";
+        case SC_ERR_CSR: return "malformed sparse weight table";
+        case SC_ERR_UNSUPPORTED: return "unsupported dtype, missing quantisation table, or tuning that does not fit";
+        case SC_ERR_RANGE: return "sample too large for 32-bit offsets";
+        case SC_ERR_OOM: return "out of memory";
+        case SC_ERR_WORKSPACE: return "workspace missing or too small";
+        case SC_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+static sc_status_t create_common(const sc_layer_t* layer, sc_dtype_t dtype, bool csr, int32_t n_ell,
+                                 const int32_t* rowptr, const int32_t* colidx, const void* values,
+                                 const float* scales, const void* codebook, void* stream,
+                                 sparse_conv_plan_t** out)
+{
+    if (!out) return SC_ERR_NULL;
+    *out = nullptr;
+    Plan* p = new (std::nothrow) Plan();
+    if (!p) return SC_ERR_OOM;
+    sc_status_t st = validate_layer(layer, dtype, scales, codebook, p);
+    HostTable tab;
+    std::vector<int32_t> ell_rowptr;
+    if (st == SC_OK) {
+        const int D = layer->D;
+        if (csr) {
+            if (!rowptr) st = SC_ERR_NULL;
+            else if (rowptr[0] != 0) st = SC_ERR_CSR;
+            else {
+                int nmax = 0;
+                for (int d = 0; d < D && st == SC_OK; ++d) {
+                    if (rowptr[d + 1] < rowptr[d]) st = SC_ERR_CSR;
+                    else nmax = std::max(nmax, rowptr[d + 1] - rowptr[d]);
+                }
+                p->n = nmax;
+                if (st == SC_OK && rowptr[D] > 0 && (!colidx || !values)) st = SC_ERR_NULL;
+                if (st == SC_OK) p->true_nnz = rowptr[D];
+            }
+        } else {
+            if (n_ell < 0) st = SC_ERR_SHAPE;
+            else if ((int64_t)n_ell * D >= (1ll << 31)) st = SC_ERR_RANGE;
+            else if (n_ell > 0 && (!colidx || !values)) st = SC_ERR_NULL;
+            else {
+                p->n = n_ell;
+                p->true_nnz = (int64_t)n_ell * D;
+                ell_rowptr.resize((size_t)D + 1);
+                for (int d = 0; d <= D; ++d) ell_rowptr[d] = d * n_ell;
+                rowptr = ell_rowptr.data();
+            }
+        }
+    }
+    if (st == SC_OK) {
+        try {
+            st = unify_rows(*p, rowptr, colidx, values, p->n, &tab);
+        } catch (const std::bad_alloc&) {
+            st = SC_ERR_OOM;
+        }
+    }
+    if (st == SC_OK) {
+        try {
+            st = finish_create(p, tab, scales, codebook, (hipStream_t)stream);
+        } catch (const std::bad_alloc&) {
+            st = SC_ERR_OOM;
+        }
+    }
+    if (st != SC_OK) {
+        free_device(p);
+        delete p;
+        return st;
+    }
+    *out = reinterpret_cast<sparse_conv_plan_t*>(p);
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_plan_create_csr(const sc_layer_t* layer, sc_dtype_t dtype,
+                                        const int32_t* rowptr, const int32_t* colidx,
+                                        const void* values, const float* scales,
+                                        const void* codebook, void* stream,
+                                        sparse_conv_plan_t** out)
+{
+    return create_common(layer, dtype, true, 0, rowptr, colidx, values, scales, codebook, stream, out);
+}
+
+sc_status_t sparse_conv_plan_create_ell(const sc_layer_t* layer, sc_dtype_t dtype, int32_t n,
+                                        const int32_t* colidx, const void* values,
+                                        const float* scales, const void* codebook, void* stream,
+                                        sparse_conv_plan_t** out)
+{
+    return create_common(layer, dtype, false, n, nullptr, colidx, values, scales, codebook, stream, out);
+}
+
+void sparse_conv_plan_destroy(sparse_conv_plan_t* plan)
+{
+    if (!plan) return;
+    Plan* p = reinterpret_cast<Plan*>(plan);
+    free_device(p);
+    delete p;
+}
+
+sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t* info)
+{
+    if (!plan || !info) return SC_ERR_NULL;
+    const Plan* p = reinterpret_cast<const Plan*>(plan);
+    std::memset(info, 0, sizeof(*info));
+    info->n = p->n;
+    info->P = p->P;
+    info->Q = p->Q;
+    info->X_size = p->X_size;
+    info->true_nnz = p->true_nnz;
+    info->macs_per_sample = (int64_t)p->L.D * p->P * p->Q * p->n;
+    info->useful_macs_per_sample = (int64_t)p->P * p->Q * p->true_nnz;
+    info->act_bytes_per_sample = (int64_t)p->L.C * p->L.H * p->L.W * p->ex + (int64_t)p->L.D * p->P * p->Q * p->ey;
+    const int64_t cnt = (int64_t)p->L.D * p->n;
+    int64_t wb = cnt * 4;  // offsets
+    wb += p->dtype == SC_CB4_I8 ? (cnt + 1) / 2 + 16 : cnt * elem_size_w_native(p->dtype);
+    if (p->d_scales) wb += (int64_t)p->L.D * 4;
+    info->weight_bytes = wb;
+    info->tuning = p->tuning;
+    if (p->tuning.variant == SC_VARIANT_SLAB) {
+        info->lds_bytes = p->geom.lds_bytes;
+        info->grid_size = p->last_N ? slab_grid_size(*p, p->geom, p->last_N) : 0;
+    } else {
+        info->lds_bytes = 1024 * 8;
+        const int pix = p->P * p->Q;
+        info->grid_size = p->last_N ? ((pix + p->tuning.wg_threads - 1) / p->tuning.wg_threads) * p->L.D *
+                                          ((p->last_N + p->tuning.sub_batch - 1) / p->tuning.sub_batch)
+                                    : 0;
+    }
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_plan_debug_offsets(const sparse_conv_plan_t* plan, int32_t* host_out)
+{
+    if (!plan || !host_out) return SC_ERR_NULL;
+    const Plan* p = reinterpret_cast<const Plan*>(plan);
+    const size_t cnt = (size_t)p->L.D * p->n;
+    if (cnt == 0) return SC_OK;
+    if (hipDeviceSynchronize() != hipSuccess) return SC_ERR_HIP;
+    if (hipMemcpy(host_out, p->d_lam, cnt * 4, hipMemcpyDeviceToHost) != hipSuccess) return SC_ERR_HIP;
+    for (size_t i = 0; i < cnt; ++i) host_out[i] &= 0x7fffffff;  // drop the filler flag
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tuning_t* tuning, void* stream)
+{
+    if (!plan || !tuning) return SC_ERR_NULL;
+    Plan* p = reinterpret_cast<Plan*>(plan);
+    sc_tuning_t t{};
+    SlabGeom g{};
+    sc_status_t st = resolve_tuning(*p, *tuning, &t, &g);
+    if (st != SC_OK) return st;
+    return install_tuning(p, t, g, (hipStream_t)stream);
+}
+
+sc_status_t sparse_conv_plan_get_tuning(const sparse_conv_plan_t* plan, sc_tuning_t* tuning)
+{
+    if (!plan || !tuning) return SC_ERR_NULL;
+    *tuning = reinterpret_cast<const Plan*>(plan)->tuning;
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes)
+{
+    if (!plan || !bytes) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    const Plan* p = reinterpret_cast<const Plan*>(plan);
+    *bytes = p->tuning.variant == SC_VARIANT_GATHER ? gather_workspace_bytes(*p, N) : 0;
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_workspace_size_max(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes)
+{
+    if (!plan || !bytes) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    *bytes = gather_workspace_bytes(*reinterpret_cast<const Plan*>(plan), N);
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
+                                int32_t N, void* workspace_dev, size_t workspace_bytes, void* stream)
+{
+    if (!plan || !x_dev || !y_dev) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    const Plan* p = reinterpret_cast<const Plan*>(plan);
+    if (p->tuning.variant == SC_VARIANT_SLAB) return launch_slab(*p, x_dev, y_dev, N, (hipStream_t)stream);
+    return launch_gather(*p, x_dev, y_dev, N, workspace_dev, workspace_bytes, (hipStream_t)stream);
+}
+
+// Candidate launch shapes for this layer, in a fixed order.
+static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
+{
+    out->clear();
+    auto push = [&](sc_tuning_t t) {
+        sc_tuning_t r{};
+        SlabGeom g{};
+        if (resolve_tuning(p, t, &r, &g) != SC_OK) return;
+        for (const sc_tuning_t& o : *out)
+            if (std::memcmp(&o, &r, sizeof(r)) == 0) return;
+        out->push_back(r);
+    };
+    for (int sb : {1, 2, 4, 8}) {
+        sc_tuning_t t{};
+        t.variant = SC_VARIANT_GATHER;
+        t.sub_batch = sb;
+        t.wg_threads = 256;
+        push(t);
+    }
+    const bool pw = is_pointwise(p.L);
+    for (int wsrc : {0, 1}) {
+        if (wsrc == 1 && p.dtype == SC_CB4_I8) continue;
+        for (int wpc : {1, 2, 3, 4}) {
+            for (int threads : {256, 512}) {
+                if (pw) {
+                    for (int v : {1, 2, 3, 4, 6, 8}) {
+                        sc_tuning_t t{};
+                        t.variant = SC_VARIANT_SLAB;
+                        t.wsrc = wsrc;
+                        t.wg_per_cu = wpc;
+                        t.wg_threads = threads;
+                        t.tile_p = 1;
+                        t.tile_q = 64 * v;
+                        push(t);
+                    }
+                } else {
+                    for (int tp : {1, 2, 3, 4, 6, 7, 8, 14, 16}) {
+                        sc_tuning_t t{};
+                        t.variant = SC_VARIANT_SLAB;
+                        t.wsrc = wsrc;
+                        t.wg_per_cu = wpc;
+                        t.wg_threads = threads;
+                        t.tile_p = tp;
+                        t.tile_q = p.Q;
+                        push(t);
+                    }
+                }
+            }
+        }
+    }
+}
+
+sc_status_t sparse_conv_plan_num_candidates(const sparse_conv_plan_t* plan, int32_t* count)
+{
+    if (!plan || !count) return SC_ERR_NULL;
+    std::vector<sc_tuning_t> c;
+    build_candidates(*reinterpret_cast<const Plan*>(plan), &c);
+    *count = (int32_t)c.size();
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_plan_candidate(const sparse_conv_plan_t* plan, int32_t index, sc_tuning_t* tuning)
+{
+    if (!plan || !tuning) return SC_ERR_NULL;
+    std::vector<sc_tuning_t> c;
+    build_candidates(*reinterpret_cast<const Plan*>(plan), &c);
+    if (index < 0 || index >= (int32_t)c.size()) return SC_ERR_SHAPE;
+    *tuning = c[index];
+    return SC_OK;
+}
+
+sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
+                                      int32_t N, void* workspace_dev, size_t workspace_bytes, void* stream)
+{
+    if (!plan || !x_dev || !y_dev) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    Plan* p = reinterpret_cast<Plan*>(plan);
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<sc_tuning_t> cands;
+    build_candidates(*p, &cands);
+    if (cands.empty()) return SC_ERR_UNSUPPORTED;
+    if (workspace_bytes < gather_workspace_bytes(*p, N) || (gather_workspace_bytes(*p, N) && !workspace_dev))
+        return SC_ERR_WORKSPACE;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return SC_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SC_ERR_HIP; }
+    sc_status_t st = SC_OK;
+    float best = INFINITY;
+    int best_i = -1;
+    for (size_t i = 0; i < cands.size() && st == SC_OK; ++i) {
+        st = sparse_conv_plan_set_tuning(plan, &cands[i], stream);
+        if (st == SC_ERR_UNSUPPORTED) { st = SC_OK; continue; }
+        if (st != SC_OK) break;
+        // one warm-up launch, then enough repeats for a stable mean
+        st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
+        if (st != SC_OK) break;
+        if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; break; }
+        st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
+        if (st != SC_OK) break;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = SC_ERR_HIP; break; }
+        float ms1 = 0;
+        if (hipEventElapsedTime(&ms1, e0, e1) != hipSuccess) { st = SC_ERR_HIP; break; }
+        int reps = (int)std::min(50.0f, std::max(3.0f, 2.0f / std::max(ms1, 1e-3f)));
+        if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; break; }
+        for (int r = 0; r < reps && st == SC_OK; ++r)
+            st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
+        if (st != SC_OK) break;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = SC_ERR_HIP; break; }
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = SC_ERR_HIP; break; }
+        ms /= reps;
+        if (ms < best) { best = ms; best_i = (int)i; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != SC_OK) return st;
+    if (best_i < 0) return SC_ERR_UNSUPPORTED;
+    p->last_N = N;
+    return sparse_conv_plan_set_tuning(plan, &cands[best_i], stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Device-side element types and conversions shared by the gather and slab kernels.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sparse_conv.h"
+
+namespace sc {
+
+// X: activation storage, Y: output storage, A: accumulator, WL: weight as held in LDS / registers
+template <sc_dtype_t DT> struct Types;
+template <> struct Types<SC_F32> { using X = float; using Y = float; using A = float; using WL = float; };
+template <> struct Types<SC_F16> { using X = __half; using Y = __half; using A = float; using WL = float; };
+template <> struct Types<SC_I8> { using X = int8_t; using Y = int32_t; using A = int32_t; using WL = int32_t; };
+template <> struct Types<SC_CB4_I8> { using X = int8_t; using Y = int32_t; using A = int32_t; using WL = int32_t; };
+
+// Weight i of the flat [D*n] table, widened to the accumulator type.  For the 4-bit codebook
+// variant the table holds two indices per byte (even entry in the low nibble) and the value is
+// looked up in the 16-entry codebook the workgroup keeps in LDS; bit 31 of the entry's offset
+// marks a zero-valued filler of a padded row.
+template <sc_dtype_t DT>
+__device__ inline typename Types<DT>::WL load_weight(const void* theta, int64_t i, int lam,
+                                                     const int8_t* cb_lds)
+{
+    if constexpr (DT == SC_F32) return static_cast<const float*>(theta)[i];
+    else if constexpr (DT == SC_F16) return __half2float(static_cast<const __half*>(theta)[i]);
+    else if constexpr (DT == SC_I8) return (int32_t) static_cast<const int8_t*>(theta)[i];
+    else {
+        const uint8_t byte = static_cast<const uint8_t*>(theta)[i >> 1];
+        const int idx = (byte >> ((i & 1) * 4)) & 15;
+        return lam < 0 ? 0 : (int32_t)cb_lds[idx];
+    }
+}
+
+template <sc_dtype_t DT> __device__ inline typename Types<DT>::A widen(typename Types<DT>::X v)
+{
+    if constexpr (DT == SC_F16) return __half2float(v);
+    else return (typename Types<DT>::A)v;
+}
+
+template <sc_dtype_t DT> __device__ inline typename Types<DT>::Y narrow(typename Types<DT>::A v)
+{
+    if constexpr (DT == SC_F16) return __float2half_rn(v);
+    else return v;
+}
+
+}  // namespace sc

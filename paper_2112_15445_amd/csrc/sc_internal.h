@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of libsparseconv (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "sparse_conv.h"
+
+namespace sc {
+
+constexpr int kMaxLdsBytes = 160 * 1024;  // LDS per CU on gfx950 (one workgroup may take all of it)
+constexpr int kNumCU = 256;
+constexpr int kWave = 64;
+constexpr int kMaxVpt = 8;                // output positions per lane in the slab kernel
+
+// Geometry of the SLAB variant for one (plan, tuning) pair, all derived on the host.
+//
+// The output plane is cut into tiles of TP x TQ pixels.  For one tile the workgroup stages, per
+// input channel, the input region the tile needs, split by stride phase into nsub = nsh*nsw
+// sub-planes of SR rows x Qs columns (row pitch Qs), so that a tile-local output position
+//     f = tp*Qs + tq
+// reads, for filter tap (c, r, s), the LDS element
+//     f + c*chan_pitch + ((r % nsh')*nsw + (s % nsw'))*sub_pitch + (r / s_h)*Qs + (s / s_w)
+// i.e. "position + pre-stretched offset", exactly the addressing of Algorithm 3 but inside the tile.
+// Positions with tq >= TQ are computed on halo data and discarded at the store.
+// Pointwise layers (1x1, stride 1, no padding) are flattened to a single row of H*W pixels.
+struct SlabGeom {
+    int Hf, Wf, Pf, Qf;        // (possibly flattened) input and output extents
+    int TP, TQ;                // output tile
+    int tiles_p, tiles_q;      // tiles per sample along each axis
+    int nsh, nsw;              // stride phases that are actually referenced: min(R, s_h), min(S, s_w)
+    int SR, Qs;                // rows / row pitch of one sub-plane
+    int sub_pitch, chan_pitch; // elements
+    int F;                     // flat positions per tile = TP*Qs
+    int vpt;                   // ceil(F / 64)
+    int slab_bytes;            // C*chan_pitch*e_x rounded up to 16
+    int wcap;                  // (theta, lambda) entries per weight stage in LDS
+    int DS, JC;                // rows per stage, entries per row per stage
+    int lds_bytes;             // total dynamic LDS
+    int vec;                   // 1: slab rows can be staged with 16-byte loads
+    int nwaves;
+    float inv_chan_pitch, inv_sub_pitch, inv_Qs;
+};
+
+struct Plan {
+    sc_layer_t L;
+    sc_dtype_t dtype;
+    int n = 0;
+    int Hp = 0, Wp = 0, P = 0, Q = 0;
+    int64_t X_size = 0;
+    int64_t true_nnz = 0;
+    int ex = 4, ey = 4;             // bytes per input / output element
+    std::vector<int32_t> h_col;     // [D*n] unified table, columns ascending per row
+    int32_t* d_col = nullptr;       // [D*n]
+    void* d_theta = nullptr;        // [D*n] f32 | f16 | i8, or ceil(D*n/2) bytes of packed 4-bit indices
+    int32_t* d_lam = nullptr;       // [D*n] canonical offsets (elements into one padded sample)
+    int32_t* d_lam_slab = nullptr;  // [D*n] byte offsets into the LDS slab of the current tuning
+    int2* d_wl32 = nullptr;         // [D*n] {theta widened to 32 bits, slab byte offset} for scalar loads
+    float* d_scales = nullptr;      // [D]
+    int8_t* d_codebook = nullptr;   // [16]
+    sc_tuning_t tuning{};
+    SlabGeom geom{};
+    int last_N = 0;
+};
+
+// plan.hip
+sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom);
+sc_status_t launch_stretch(const Plan& p, int32_t* d_out, int nsh, int nsw, int s_h, int s_w,
+                           int chan_pitch, int sub_pitch, int row_pitch, int scale,
+                           hipStream_t stream);
+int elem_size_x(sc_dtype_t dt);
+int elem_size_y(sc_dtype_t dt);
+
+// gather.hip
+size_t gather_workspace_bytes(const Plan& p, int N);
+sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws, size_t ws_bytes,
+                          hipStream_t stream);
+
+// slab.hip
+sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
+int slab_grid_size(const Plan& p, const SlabGeom& g, int N);
+sc_status_t expand_weights(const Plan& p, hipStream_t stream);
+
+}  // namespace sc

@@ -1,0 +1,323 @@
+// SLAB variant: the gfx950-first shape of the paper's Algorithm 3.
+//
+// One workgroup owns one sample and one tile of output pixels and computes ALL output channels for
+// it.  It first stages the input region the tile needs -- every input channel, halo and zero
+// padding included -- in LDS (up to 160 KB per CU), so the input is read from HBM once instead of
+// once per output channel, and no padded copy of the input ever exists in HBM.  Then the rows of
+// the (theta, lambda) table are streamed over the resident tile: the waves of the workgroup split
+// the output channels, each lane owns VPT tile positions (lane, lane+64, ...), and for every
+// stored entry the lane gathers   slab[position + lambda]   from LDS -- consecutive lanes read
+// consecutive LDS words, so the gather is bank-conflict free for any lambda -- and accumulates in
+// registers; one store per output value.  lambda here is the offset pre-stretched for the tile's
+// LDS layout (see SlabGeom), already scaled to bytes.
+//
+// (theta, lambda) reaches the lanes in one of two ways (tuning.wsrc):
+//   0  rows are staged in LDS in groups (decoding 4-bit codebook indices on the way) and read back
+//      with wave-uniform (broadcast) LDS reads, as Algorithm 3 does from shared memory;
+//   1  rows are read with scalar loads from a pre-expanded {theta32, lambda} table in global
+//      memory, which keeps the LDS pipe free for the gather itself.
+#include <mutex>
+
+#include "sc_device.h"
+#include "sc_internal.h"
+
+namespace sc {
+
+struct SlabArgs {
+    int C, D, n, N;
+    int Hf, Wf, Pf, Qf;
+    int s_h, s_w, pad_h, pad_w;
+    int TP, TQ, tiles_p, tiles_q;
+    int nsw, Qs, sub_pitch, chan_pitch, F;
+    int slab_elems, slab_bytes, wcap, DS, JC, vec;
+    float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q;
+    int64_t x_sample_stride, y_plane;
+};
+
+// floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
+// product at least 1/(2d) away from every integer, well above the two float roundings)
+__device__ inline int fdiv(int e, float inv) { return (int)(((float)e + 0.5f) * inv); }
+
+template <sc_dtype_t DT> __device__ inline int weight_bits(typename Types<DT>::WL w)
+{
+    if constexpr (DT == SC_F32 || DT == SC_F16) return __float_as_int(w);
+    else return w;
+}
+template <sc_dtype_t DT> __device__ inline typename Types<DT>::WL weight_from_bits(int b)
+{
+    if constexpr (DT == SC_F32 || DT == SC_F16) return __int_as_float(b);
+    else return b;
+}
+
+// Expand the compact weight table to {theta widened to 32 bits, LDS byte offset} pairs for the
+// scalar-load path.
+template <sc_dtype_t DT>
+__global__ void __launch_bounds__(256)
+expand_weights_kernel(const void* __restrict__ theta, const int32_t* __restrict__ lam,
+                      int2* __restrict__ out, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const int l = lam[i];
+    out[i] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
+}
+
+template <sc_dtype_t DT, int VPT, int WSRC>
+__global__ void
+slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+            const void* __restrict__ theta, const int32_t* __restrict__ lam,
+            const int2* __restrict__ wl32, const int8_t* __restrict__ codebook, const SlabArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    X* slab = reinterpret_cast<X*>(lds);
+    int2* wst = reinterpret_cast<int2*>(lds + a.slab_bytes);
+    int8_t* cb_s = reinterpret_cast<int8_t*>(lds + a.slab_bytes + a.wcap * 8);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = nthreads >> 6;
+
+    // workgroup -> (sample, tile)
+    const int tiles = a.tiles_p * a.tiles_q;
+    const int b = fdiv(blockIdx.x, a.inv_tiles);
+    const int t = blockIdx.x - b * tiles;
+    const int tpi = fdiv(t, a.inv_tiles_q);
+    const int tqi = t - tpi * a.tiles_q;
+    const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
+
+    // ---------------------------------------------------------------- stage the input tile in LDS
+    const X* xb = x + (int64_t)b * a.x_sample_stride;
+    if (a.vec) {
+        // pointwise layers: the tile is C rows of TQ consecutive pixels; 16-byte loads
+        constexpr int EPV = 16 / (int)sizeof(X);
+        const int vpr = a.Qs / EPV;
+        const float inv_vpr = 1.0f / (float)vpr;
+        const int total = a.C * vpr;
+        for (int v = tid; v < total; v += nthreads) {
+            const int c = fdiv(v, inv_vpr);
+            const int col = q0 + (v - c * vpr) * EPV;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (col < a.Wf) val = *reinterpret_cast<const uint4*>(xb + (int64_t)c * a.Wf + col);
+            *reinterpret_cast<uint4*>(slab + c * a.chan_pitch + (v - c * vpr) * EPV) = val;
+        }
+    } else {
+        const int row0 = p0 * a.s_h - a.pad_h, col0 = q0 * a.s_w - a.pad_w;
+        const float inv_nsw = 1.0f / (float)a.nsw;
+        for (int e = tid; e < a.slab_elems; e += nthreads) {
+            const int c = fdiv(e, a.inv_chan_pitch);
+            const int rem = e - c * a.chan_pitch;
+            const int sub = fdiv(rem, a.inv_sub_pitch);
+            const int rem2 = rem - sub * a.sub_pitch;
+            const int i = fdiv(rem2, a.inv_Qs);
+            const int k = rem2 - i * a.Qs;
+            const int ph = fdiv(sub, inv_nsw), pw = sub - ph * a.nsw;
+            const int row = row0 + i * a.s_h + ph;
+            const int col = col0 + k * a.s_w + pw;
+            X v = X(0);
+            if (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf)
+                v = xb[((int64_t)c * a.Hf + row) * a.Wf + col];
+            slab[e] = v;
+        }
+    }
+    if constexpr (DT == SC_CB4_I8) {
+        if (tid < 16) cb_s[tid] = codebook[tid];
+    }
+
+    // ---------------------------------------------------------------- per-lane output bookkeeping
+    int out_off[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const int f = k * 64 + lane;
+        const int tp = fdiv(f, a.inv_Qs);
+        const int tq = f - tp * a.Qs;
+        const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf;
+        out_off[k] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
+    }
+    Y* yb = y + (int64_t)b * a.D * a.y_plane;
+    const unsigned char* lane_base = lds + lane * (int)sizeof(X);
+
+    if constexpr (WSRC == 1) __syncthreads();  // slab complete
+
+    // ---------------------------------------------------------------- stream the weight rows
+    A acc[VPT];
+    for (int ds0 = 0; ds0 < a.D; ds0 += a.DS) {
+        const int rows = min(a.DS, a.D - ds0);
+        int j0 = 0;
+        do {
+            const int jc = min(a.JC, a.n - j0);
+            if constexpr (WSRC == 0) {
+                __syncthreads();  // slab complete / previous stage consumed
+                if (jc == a.n) {
+                    const int cnt = rows * a.n;
+                    const int64_t g0 = (int64_t)ds0 * a.n;
+                    for (int e = tid; e < cnt; e += nthreads) {
+                        const int l = lam[g0 + e];
+                        wst[e] = make_int2(weight_bits<DT>(load_weight<DT>(theta, g0 + e, l, cb_s)),
+                                           l & 0x7fffffff);
+                    }
+                } else {
+                    const int cnt = rows * jc;
+                    const float inv_jc = 1.0f / (float)jc;
+                    for (int e = tid; e < cnt; e += nthreads) {
+                        const int dd = fdiv(e, inv_jc);
+                        const int64_t g = (int64_t)(ds0 + dd) * a.n + j0 + (e - dd * jc);
+                        const int l = lam[g];
+                        wst[e] = make_int2(weight_bits<DT>(load_weight<DT>(theta, g, l, cb_s)),
+                                           l & 0x7fffffff);
+                    }
+                }
+                __syncthreads();
+            }
+            for (int dd = wave; dd < rows; dd += nwaves) {
+                if (j0 == 0) {
+#pragma unroll
+                    for (int k = 0; k < VPT; ++k) acc[k] = A(0);
+                }
+                if constexpr (WSRC == 0) {
+                    const int2* wrow = wst + dd * jc;
+#pragma unroll 4
+                    for (int j = 0; j < jc; ++j) {
+                        const int2 e = wrow[j];
+                        const WL w = weight_from_bits<DT>(e.x);
+                        const unsigned char* pj = lane_base + e.y;
+#pragma unroll
+                        for (int k = 0; k < VPT; ++k)
+                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                    }
+                } else {
+                    const int2* wrow = wl32 + ((int64_t)(ds0 + dd) * a.n + j0);
+#pragma unroll 4
+                    for (int j = 0; j < jc; ++j) {
+                        const int2 e = wrow[j];
+                        const WL w = weight_from_bits<DT>(e.x);
+                        const unsigned char* pj = lane_base + e.y;
+#pragma unroll
+                        for (int k = 0; k < VPT; ++k)
+                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                    }
+                }
+                if (j0 + jc >= a.n) {
+                    Y* yd = yb + (int64_t)(ds0 + dd) * a.y_plane;
+#pragma unroll
+                    for (int k = 0; k < VPT; ++k)
+                        if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+                }
+            }
+            j0 += a.JC;
+        } while (j0 < a.n);
+    }
+}
+
+int slab_grid_size(const Plan& p, const SlabGeom& g, int N)
+{
+    (void)p;
+    return N * g.tiles_p * g.tiles_q;
+}
+
+sc_status_t expand_weights(const Plan& p, hipStream_t stream)
+{
+    const int64_t cnt = (int64_t)p.L.D * p.n;
+    if (cnt == 0 || !p.d_wl32) return SC_OK;
+    const unsigned blocks = (unsigned)((cnt + 255) / 256);
+    switch (p.dtype) {
+        case SC_F32:
+            hipLaunchKernelGGL(expand_weights_kernel<SC_F32>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
+                               p.d_lam_slab, p.d_wl32, cnt);
+            break;
+        case SC_F16:
+            hipLaunchKernelGGL(expand_weights_kernel<SC_F16>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
+                               p.d_lam_slab, p.d_wl32, cnt);
+            break;
+        case SC_I8:
+            hipLaunchKernelGGL(expand_weights_kernel<SC_I8>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
+                               p.d_lam_slab, p.d_wl32, cnt);
+            break;
+        default: return SC_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int VPT, int WSRC>
+static sc_status_t launch_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                              hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_kernel<DT, VPT, WSRC>;
+    // a workgroup may use more than the default 64 KB of LDS: raise the limit once per kernel
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_theta, p.d_lam_slab, p.d_wl32,
+                       p.d_codebook, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int WSRC>
+static sc_status_t launch_vpt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                              hipStream_t stream)
+{
+    switch (p.geom.vpt) {
+        case 1: return launch_one<DT, 1, WSRC>(p, a, x, y, grid, stream);
+        case 2: return launch_one<DT, 2, WSRC>(p, a, x, y, grid, stream);
+        case 3: return launch_one<DT, 3, WSRC>(p, a, x, y, grid, stream);
+        case 4: return launch_one<DT, 4, WSRC>(p, a, x, y, grid, stream);
+        case 5: return launch_one<DT, 5, WSRC>(p, a, x, y, grid, stream);
+        case 6: return launch_one<DT, 6, WSRC>(p, a, x, y, grid, stream);
+        case 7: return launch_one<DT, 7, WSRC>(p, a, x, y, grid, stream);
+        case 8: return launch_one<DT, 8, WSRC>(p, a, x, y, grid, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                             hipStream_t stream)
+{
+    if constexpr (DT != SC_CB4_I8) {
+        if (p.tuning.wsrc == 1) return launch_vpt<DT, 1>(p, a, x, y, grid, stream);
+    }
+    return launch_vpt<DT, 0>(p, a, x, y, grid, stream);
+}
+
+sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
+{
+    const SlabGeom& g = p.geom;
+    const int64_t grid64 = (int64_t)N * g.tiles_p * g.tiles_q;
+    if (grid64 >= (1 << 19)) return SC_ERR_UNSUPPORTED;  // fdiv() range for the tile decode
+    SlabArgs a{};
+    a.C = p.L.C; a.D = p.L.D; a.n = p.n; a.N = N;
+    a.Hf = g.Hf; a.Wf = g.Wf; a.Pf = g.Pf; a.Qf = g.Qf;
+    a.s_h = p.L.stride_h; a.s_w = p.L.stride_w; a.pad_h = p.L.pad_h; a.pad_w = p.L.pad_w;
+    a.TP = g.TP; a.TQ = g.TQ; a.tiles_p = g.tiles_p; a.tiles_q = g.tiles_q;
+    a.nsw = g.nsw; a.Qs = g.Qs; a.sub_pitch = g.sub_pitch; a.chan_pitch = g.chan_pitch; a.F = g.F;
+    a.slab_elems = p.L.C * g.chan_pitch;
+    a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC;
+    // 16-byte staging also needs a 16-byte aligned input pointer
+    a.vec = (g.vec && (reinterpret_cast<uintptr_t>(x) % 16 == 0)) ? 1 : 0;
+    a.inv_chan_pitch = g.inv_chan_pitch; a.inv_sub_pitch = g.inv_sub_pitch; a.inv_Qs = g.inv_Qs;
+    a.inv_tiles = 1.0f / (float)(g.tiles_p * g.tiles_q);
+    a.inv_tiles_q = 1.0f / (float)g.tiles_q;
+    a.x_sample_stride = (int64_t)p.L.C * g.Hf * g.Wf;
+    a.y_plane = (int64_t)g.Pf * g.Qf;
+    switch (p.dtype) {
+        case SC_F32: return launch_dt<SC_F32>(p, a, x, y, (int)grid64, stream);
+        case SC_F16: return launch_dt<SC_F16>(p, a, x, y, (int)grid64, stream);
+        case SC_I8: return launch_dt<SC_I8>(p, a, x, y, (int)grid64, stream);
+        case SC_CB4_I8: return launch_dt<SC_CB4_I8>(p, a, x, y, (int)grid64, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+}  // namespace sc

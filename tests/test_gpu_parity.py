@@ -1,0 +1,210 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Tolerances (max|y - ref| / max|ref| per layer): fp32 1e-5, fp16 2e-2, integer paths bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2112_15445_amd import binding as B
+from paper_2112_15445_amd import workloads as wl
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+DT = ["f32", "f16", "i8", "cb4"]
+
+
+def _both_variants(plan):
+    """Yield a label for every kernel family that can run this plan (after installing it)."""
+    for variant, extra in ((B.SC_VARIANT_GATHER, {}), (B.SC_VARIANT_SLAB, {"wsrc": 0}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1})):
+        try:
+            plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
+        except B.SparseConvError as e:
+            assert e.status == 4      # does not fit / not available for this dtype
+            continue
+        yield f"variant={variant} {extra}"
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_config1_layer(dtype):
+    (l,) = wl.config1()
+    l = l.replace(dtype=dtype)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    assert plan.info().n == 58
+    for label in _both_variants(plan):
+        print("case", l.name, dtype, label, flush=True)
+        G.check(l, G.run_gpu(plan, data["x"]), ref, label)
+
+
+def test_stretch_pass_offsets_match_oracle():
+    import oracle
+    for l in (wl.config1()[0], wl.Layer("t", 5, 7, 9, 11, 3, 2, 2, 1, 1, 2, N=1, sparsity=0.5)):
+        data = wl.prepare(l, ragged=True)
+        st = oracle.sparse_conv_steps(data["x"], data["rowptr"], data["colidx"], data["values"], l.R,
+                                      l.S, (l.stride_h, l.stride_w), (l.pad_h, l.pad_w))
+        plan = G.make_plan(l, data)
+        lam = plan.debug_offsets()
+        assert lam.shape == st["lam"].shape and np.array_equal(lam, st["lam"])
+
+
+SHAPES = [
+    # name, C, D, H, W, R, S, sh, sw, ph, pw, N, sparsity
+    ("odd_3x3", 5, 7, 13, 11, 3, 3, 1, 1, 1, 1, 3, 0.6),
+    ("stride2_3x3", 6, 5, 14, 15, 3, 3, 2, 2, 1, 1, 2, 0.7),
+    ("stride2_nopad", 4, 6, 9, 10, 3, 3, 2, 2, 0, 0, 2, 0.5),
+    ("pad2_5x5", 3, 4, 8, 9, 5, 5, 1, 1, 2, 2, 2, 0.8),
+    ("rect_filter", 4, 5, 10, 12, 2, 3, 1, 2, 0, 1, 2, 0.5),
+    ("pointwise", 24, 10, 7, 9, 1, 1, 1, 1, 0, 0, 3, 0.7),
+    ("pointwise_vec", 16, 12, 8, 8, 1, 1, 1, 1, 0, 0, 2, 0.6),
+    ("pointwise_s2", 8, 6, 9, 9, 1, 1, 2, 2, 0, 0, 2, 0.5),
+    ("conv1d_like", 30, 8, 1, 64, 1, 3, 1, 1, 0, 0, 2, 0.8),
+    ("stride3", 3, 4, 11, 13, 3, 3, 3, 3, 1, 1, 2, 0.5),
+    ("wide_tiles", 2, 3, 6, 150, 3, 3, 1, 1, 1, 1, 1, 0.5),
+]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
+def test_shapes_both_variants(shape, dtype):
+    name, C, D, H, W, R, S, sh, sw, ph, pw, N, sp = shape
+    l = wl.Layer(name, C, D, H, W, R, S, sh, sw, ph, pw, N=N, sparsity=sp, dtype=dtype, seed=4242)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    ran = 0
+    for label in _both_variants(plan):
+        print("case", name, dtype, label, flush=True)
+        G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} {label}")
+        ran += 1
+    assert ran >= 1
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_ragged_rows_empty_rows_and_extremes(dtype):
+    base = wl.Layer("ragged", 6, 9, 10, 9, 3, 3, 1, 1, 1, 1, N=2, sparsity=0.6, dtype=dtype, seed=99)
+    cases = {
+        "ragged": wl.prepare(base, ragged=True),
+        "n=1": wl.prepare(base, n=1),
+        "n=K (0% sparsity)": wl.prepare(base, n=base.K),
+    }
+    # a table with empty rows
+    d = wl.prepare(base, ragged=True)
+    rp = d["rowptr"].copy()
+    keep = np.ones(rp[-1], bool)
+    for row in (0, 4):
+        keep[rp[row]:rp[row + 1]] = False
+    lens = np.diff(rp)
+    lens[[0, 4]] = 0
+    d["rowptr"] = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    d["colidx"], d["values"] = d["colidx"][keep], d["values"][keep]
+    cases["empty rows"] = d
+    for what, data in cases.items():
+        ref = G.oracle_out(base, data)
+        plan = G.make_plan(base, data)
+        for label in _both_variants(plan):
+            print("case", what, dtype, label, flush=True)
+            G.check(base, G.run_gpu(plan, data["x"]), ref, f"{what} {label}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "i8"])
+def test_all_zero_table_gives_zero_output(dtype):
+    l = wl.Layer("empty", 3, 4, 6, 6, 3, 3, 1, 1, 1, 1, N=2, dtype=dtype)
+    data = wl.prepare(l, n=0)
+    assert data["rowptr"][-1] == 0
+    plan = G.make_plan(l, data)
+    assert plan.info().n == 0
+    for label in _both_variants(plan):
+        y = G.run_gpu(plan, data["x"])
+        assert y.shape == (2, 4, 6, 6) and not np.any(y), label
+
+
+@pytest.mark.parametrize("dtype", ["f32", "cb4"])
+def test_long_rows_are_chunked(dtype):
+    """n larger than one LDS weight stage / one gather row chunk (dense 3x3 over 160 channels)."""
+    l = wl.Layer("long", 160, 6, 6, 6, 3, 3, 1, 1, 1, 1, N=1, sparsity=0.0, dtype=dtype, seed=5)
+    data = wl.prepare(l)
+    assert l.n == 1440
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    for label in _both_variants(plan):
+        print("case long", dtype, label, flush=True)
+        G.check(l, G.run_gpu(plan, data["x"]), ref, label)
+
+
+def test_ell_entry_point_and_unsorted_duplicate_columns():
+    rng = np.random.default_rng(3)
+    l = wl.Layer("ell", 4, 5, 8, 8, 3, 3, 1, 1, 1, 1, N=2, dtype="i8")
+    n = 7
+    col = rng.integers(0, l.K, size=(l.D, n)).astype(np.int32)       # unsorted, duplicates likely
+    col[:, 3] = col[:, 2]
+    val = rng.integers(-127, 128, size=(l.D, n)).astype(np.int8)
+    x = rng.integers(-127, 128, size=(2, 4, 8, 8)).astype(np.int8)
+    import oracle
+    rp = (np.arange(l.D + 1) * n).astype(np.int32)
+    ref = oracle.sparse_conv(x, rp, col.ravel(), val.ravel(), 3, 3, (1, 1), (1, 1))
+    plan = B.Plan.create_ell(G.layer_desc(l), B.SC_I8, n, col, val, scales=np.ones(l.D, np.float32))
+    for label in _both_variants(plan):
+        assert np.array_equal(G.run_gpu(plan, x), ref), label
+
+
+def test_every_autotune_candidate_gives_the_same_answer():
+    for l in (wl.Layer("cand3x3", 16, 24, 20, 20, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.8, seed=8),
+              wl.Layer("cand1x1", 32, 40, 16, 16, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.8, seed=9)):
+        data = wl.prepare(l)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        nc = plan.num_candidates()
+        assert nc >= 8
+        for i in range(nc):
+            t = plan.candidate(i)
+            plan.set_tuning(t)
+            print("candidate", l.name, i, t.as_dict(), flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} candidate {i} {t.as_dict()}")
+
+
+def test_autotune_installs_a_valid_tuning():
+    import torch
+    l = wl.Layer("tune", 32, 32, 28, 28, 3, 3, 1, 1, 1, 1, N=4, sparsity=0.9, seed=10)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    x = G.to_device(data["x"])
+    y = torch.empty((4, 32, 28, 28), device="cuda")
+    ws = torch.empty(max(plan.workspace_size_max(4), 1), dtype=torch.uint8, device="cuda")
+    plan.autotune(x.data_ptr(), y.data_ptr(), 4, ws.data_ptr(), ws.numel(),
+                  torch.cuda.current_stream().cuda_stream)
+    t = plan.get_tuning()
+    assert t.variant in (B.SC_VARIANT_GATHER, B.SC_VARIANT_SLAB)
+    G.check(l, G.run_gpu(plan, data["x"]), ref, str(t.as_dict()))
+    assert plan.info().grid_size > 0
+
+
+@pytest.mark.parametrize("cfg,dtype", [(2, "f32"), (5, "i8"), (5, "cb4")])
+def test_vgg_stack_layers_at_reduced_batch(cfg, dtype):
+    layers = [l for l in wl.CONFIGS[cfg]() if l.dtype == dtype]
+    assert len(layers) == 13
+    for l in layers:
+        data = wl.prepare(l, N=2)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        print("case", l.name, plan.get_tuning().as_dict(), flush=True)
+        G.check(l, G.run_gpu(plan, data["x"]), ref, l.name)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_resnet_layers_full_batch_sampled(dtype):
+    """Full-size ResNet-50-shaped layers (batch 32, 90 %) in the default launch configuration;
+    the oracle checks the first and last sample completely."""
+    layers = [l for l in wl.config3() if l.name.endswith("sp90")]
+    for l in layers:
+        l = l.replace(dtype=dtype)
+        data = wl.prepare(l)
+        plan = G.make_plan(l, data)
+        print("case", l.name, dtype, plan.get_tuning().as_dict(), flush=True)
+        y = G.run_gpu(plan, data["x"])
+        for b in (0, l.N - 1):
+            ref = G.oracle_out(l, data, samples=[b])
+            G.check(l, y[b:b + 1], ref, f"{l.name} sample {b}")
