@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the direct sparse convolution hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer NAME] [--no-autotune]
+                    [--report PATH]   # optional per-layer table over all five configs
+
+One *step* is one pass of the hot path over one batch of synthetic input: sparse_conv_forward of
+the headline layer (largest ResNet-50-shaped layer at 90 % sparsity: the stage-1 1x1 reduce,
+C=256 -> D=64, 56x56, batch 32, fp32, 26 stored weights per output channel).  The plan (row
+unification, offset stretching, launch-shape autotune) is built once before the timed region, as
+the method prescribes (it is per-layer, offline work).  Inputs are resident in HBM; the step
+rotates over a ring of input/output buffers larger than twice the 256 MB Infinity Cache so that
+every launch really streams from HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+FP32_VALU_PEAK_TFLOPS = 157.3
+INFINITY_CACHE_BYTES = 256 << 20
+
+# HBM traffic per launch of the dominant kernel, measured offline with rocprofv3 --pmc
+# (FETCH_SIZE / WRITE_SIZE, scaled by the same counters on a plain copy kernel); the summaries and
+# the commands that produced them are under profiles/.  Keyed by workload name; None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _ring(plan, data, l, torch, G, B):
+    """Input/output buffer ring > 2x the Infinity Cache (at least 2 pairs)."""
+    inf = plan.info()
+    x0 = G.to_device(data["x"])
+    ybytes = l.N * l.D * inf.P * inf.Q * (2 if l.dtype == "f16" else 4)
+    per = x0.numel() * x0.element_size() + ybytes
+    R = max(2, min(16, int(2 * INFINITY_CACHE_BYTES // per) + 1))
+    xs = [x0] + [x0.clone() for _ in range(R - 1)]
+    ys = [torch.empty((l.N, l.D, inf.P, inf.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
+          for _ in range(R)]
+    return xs, ys
+
+
+def _time_steps(plan, xs, ys, ws, N, steps, warmup, torch):
+    st = torch.cuda.current_stream().cuda_stream
+    R = len(xs)
+    wsp, wsn = (ws.data_ptr(), ws.numel()) if ws is not None else (0, 0)
+    for i in range(warmup):
+        plan.forward(xs[i % R].data_ptr(), ys[i % R].data_ptr(), N, wsp, wsn, st)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        plan.forward(xs[i % R].data_ptr(), ys[i % R].data_ptr(), N, wsp, wsn, st)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, e0.elapsed_time(e1) / steps
+
+
+def _dense_reference_ms(l, torch, reps=30):
+    """Dense MIOpen convolution of the same layer (torch conv2d), cache-warm, for context."""
+    dt = {"f32": torch.float32, "f16": torch.float16}.get(l.dtype)
+    if dt is None:
+        return None
+    x = torch.empty((l.N, l.C, l.H, l.W), dtype=dt, device="cuda").uniform_(-1, 1)
+    w = torch.empty((l.D, l.C, l.R, l.S), dtype=dt, device="cuda").normal_(0, 0.05)
+    conv = lambda: torch.nn.functional.conv2d(x, w, stride=(l.stride_h, l.stride_w),
+                                              padding=(l.pad_h, l.pad_w))
+    for _ in range(3):
+        conv()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        conv()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def _cpu_baseline(l, data, oracle, max_samples):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    ns = min(l.N, max_samples)
+    x = data["x"][:ns]
+    t0 = time.perf_counter()
+    oracle.sparse_conv(x, data["rowptr"], data["colidx"], data["values"], l.R, l.S,
+                       (l.stride_h, l.stride_w), (l.pad_h, l.pad_w), codebook=data["codebook"])
+    dt = time.perf_counter() - t0
+    macs = ns * l.D * l.P * l.Q * l.n
+    return {"value": 2 * macs / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"{ns} of {l.N} samples of {l.name} ({dt:.2f} s, includes the "
+            "oracle's widening to double and its padded copy)"}
+
+
+def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True):
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    xs, ys = _ring(plan, data, l, torch, G, B)
+    ws_bytes = plan.workspace_size_max(l.N)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    if autotune:
+        plan.autotune(xs[0].data_ptr(), ys[0].data_ptr(), l.N, ws.data_ptr(), ws.numel(),
+                      torch.cuda.current_stream().cuda_stream)
+    wall_ms, ev_ms = _time_steps(plan, xs, ys, ws, l.N, steps, warmup, torch)
+    inf = plan.info()
+    useful = 2.0 * l.N * inf.useful_macs_per_sample
+    alg_bytes = l.N * inf.act_bytes_per_sample + inf.weight_bytes
+    out = {
+        "layer": l.name, "dtype": l.dtype, "n": inf.n, "ms_wall": wall_ms, "ms_events": ev_ms,
+        "useful_gflops": useful / (wall_ms * 1e-3) / 1e9,
+        "algorithmic_bytes": alg_bytes,
+        "achieved_gbs": alg_bytes / (ev_ms * 1e-3) / 1e9,
+        "hbm_frac": alg_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "tuning": inf.tuning.as_dict(), "lds_bytes": inf.lds_bytes, "ring": len(xs),
+    }
+    if with_dense:
+        out["dense_miopen_ms"] = _dense_reference_ms(l, torch)
+    return out, data, plan
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--layer", default=None, help="layer name from config 3 (default: headline)")
+    ap.add_argument("--no-autotune", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", default=None, help="also time every layer of all configs -> JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path shards over the batch with no "
+              "exchange step; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import gpu_util as G
+    from paper_2112_15445_amd import binding as B
+    from paper_2112_15445_amd import workloads as wl
+    B.lib()                                  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    l = wl.headline_layer()
+    if args.layer:
+        l = {x.name: x for c in (3, 4, 2, 5, 1) for x in wl.CONFIGS[c]()}[args.layer]
+    res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl)
+
+    line = {
+        "metric": "useful GFLOP/s (nnz MACs) per sparse conv layer",
+        "value": res["useful_gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_wall"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": l.dtype, "data": "synthetic",
+        "config": {"workload": f"resnet50_{l.name}_batch{l.N}_{l.dtype}" if not args.layer else l.name,
+                   "C": l.C, "D": l.D, "H": l.H, "W": l.W, "R": l.R, "S": l.S,
+                   "stride": l.stride_h, "pad": l.pad_h, "batch": l.N, "sparsity": l.sparsity,
+                   "n_per_channel": res["n"], "tuning": res["tuning"], "lds_bytes": res["lds_bytes"],
+                   "buffer_ring": res["ring"], "cache": "cold (ring > 2x Infinity Cache)"},
+        "roofline": {"bound": "hbm", "achieved": res["achieved_gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": res["hbm_frac"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(l.name),
+                     "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
+                     "kernel_ms": res["ms_events"]},
+        "dense_miopen_ms": res.get("dense_miopen_ms"),
+        "sparse_vs_dense_speedup": (res["dense_miopen_ms"] / res["ms_events"]
+                                    if res.get("dense_miopen_ms") else None),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        line["cpu_baseline"] = _cpu_baseline(l, data, oracle, max_samples=l.N)
+    plan.destroy()
+
+    if args.report:
+        rows = []
+        for cfg in (1, 2, 3, 4, 5):
+            for lay in wl.CONFIGS[cfg]():
+                r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl)
+                p.destroy()
+                r["config"] = cfg
+                rows.append(r)
+                print(json.dumps(r), file=sys.stderr, flush=True)
+                torch.cuda.empty_cache()
+        with open(args.report, "w") as f:
+            json.dump(rows, f, indent=1)
+
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -67,7 +67,7 @@ static bool is_pointwise(const sc_layer_t& L)
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
-static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int lds_budget, SlabGeom* g)
+static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int lds_budget, SlabGeom* g)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -99,9 +99,10 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int lds
     int64_t cap = (lds_budget - o.slab_bytes - 64) / 8;
     cap = std::min<int64_t>(cap, 4096);
     cap = std::min<int64_t>(cap, std::max<int64_t>(total, 1));
-    if (cap < std::min<int64_t>(std::max<int64_t>(total, 1), 512)) return false;
+    if (wsrc == 1) cap = 0;  // scalar-load path keeps no weights in LDS
+    else if (cap < std::min<int64_t>(std::max<int64_t>(total, 1), 512)) return false;
     o.wcap = (int)cap;
-    if (p.n == 0) {
+    if (p.n == 0 || wsrc == 1) {
         o.DS = std::min(L.D, o.nwaves);
         o.JC = 0;
     } else if ((int64_t)p.n * std::min(o.nwaves, L.D) <= o.wcap) {
@@ -147,16 +148,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, budget, &g);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, budget, &g);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, budget, &g);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
@@ -297,6 +298,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
 {
     const size_t cnt = (size_t)p->L.D * p->n;
     const int wsz = elem_size_w_native(p->dtype);
+    p->np = (p->n + 7) / 8 * 8;
     p->h_col = std::move(tab.col);
     // resolve the default tuning first: it is pure host arithmetic
     sc_tuning_t t{};
@@ -320,7 +322,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
         if ((e = hipMalloc((void**)&p->d_lam, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc((void**)&p->d_lam_slab, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc(&p->d_theta, theta_bytes)) != hipSuccess) return hip_status(e);
-        if (p->dtype != SC_CB4_I8 && (e = hipMalloc((void**)&p->d_wl32, cnt * 8)) != hipSuccess) return hip_status(e);
+        if (p->dtype != SC_CB4_I8 && (e = hipMalloc((void**)&p->d_wl32, (size_t)p->L.D * p->np * 8)) != hipSuccess) return hip_status(e);
         if ((e = hipMemcpyAsync(p->d_col, p->h_col.data(), cnt * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return hip_status(e);
         if ((e = hipMemcpyAsync(p->d_theta, theta_src, theta_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess)
@@ -569,16 +571,16 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     for (int wsrc : {0, 1}) {
         if (wsrc == 1 && p.dtype == SC_CB4_I8) continue;
         for (int wpc : {1, 2, 3, 4}) {
-            for (int threads : {256, 512}) {
+            for (int threads : {256, 512, 1024}) {
                 if (pw) {
-                    for (int v : {1, 2, 3, 4, 6, 8}) {
+                    for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
                         sc_tuning_t t{};
                         t.variant = SC_VARIANT_SLAB;
                         t.wsrc = wsrc;
                         t.wg_per_cu = wpc;
                         t.wg_threads = threads;
                         t.tile_p = 1;
-                        t.tile_q = 64 * v;
+                        t.tile_q = tq;
                         push(t);
                     }
                 } else {

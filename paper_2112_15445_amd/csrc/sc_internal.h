@@ -47,6 +47,7 @@ struct Plan {
     sc_layer_t L;
     sc_dtype_t dtype;
     int n = 0;
+    int np = 0;                     // n rounded up to a multiple of 8 (row pitch of d_wl32)
     int Hp = 0, Wp = 0, P = 0, Q = 0;
     int64_t X_size = 0;
     int64_t true_nnz = 0;
@@ -56,7 +57,7 @@ struct Plan {
     void* d_theta = nullptr;        // [D*n] f32 | f16 | i8, or ceil(D*n/2) bytes of packed 4-bit indices
     int32_t* d_lam = nullptr;       // [D*n] canonical offsets (elements into one padded sample)
     int32_t* d_lam_slab = nullptr;  // [D*n] byte offsets into the LDS slab of the current tuning
-    int2* d_wl32 = nullptr;         // [D*n] {theta widened to 32 bits, slab byte offset} for scalar loads
+    int2* d_wl32 = nullptr;         // [D*np] {theta widened to 32 bits, slab byte offset} for scalar loads
     float* d_scales = nullptr;      // [D]
     int8_t* d_codebook = nullptr;   // [16]
     sc_tuning_t tuning{};

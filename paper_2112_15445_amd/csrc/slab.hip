@@ -29,7 +29,7 @@ struct SlabArgs {
     int s_h, s_w, pad_h, pad_w;
     int TP, TQ, tiles_p, tiles_q;
     int nsw, Qs, sub_pitch, chan_pitch, F;
-    int slab_elems, slab_bytes, wcap, DS, JC, vec;
+    int slab_elems, slab_bytes, wcap, DS, JC, vec, np;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q;
     int64_t x_sample_stride, y_plane;
 };
@@ -50,17 +50,26 @@ template <sc_dtype_t DT> __device__ inline typename Types<DT>::WL weight_from_bi
 }
 
 // Expand the compact weight table to {theta widened to 32 bits, LDS byte offset} pairs for the
-// scalar-load path.
+// scalar-load path.  Rows are padded to np = round_up(n, 8) pairs (64 bytes per group of 8) with
+// zero weights at offset 0 so the kernel can fetch whole groups with one 16-dword scalar load.
 template <sc_dtype_t DT>
 __global__ void __launch_bounds__(256)
 expand_weights_kernel(const void* __restrict__ theta, const int32_t* __restrict__ lam,
-                      int2* __restrict__ out, int64_t count)
+                      int2* __restrict__ out, int D, int n, int np)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
-    const int l = lam[i];
-    out[i] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
+    if (i >= (int64_t)D * np) return;
+    const int d = (int)(i / np), j = (int)(i - (int64_t)d * np);
+    int2 e = make_int2(0, 0);
+    if (j < n) {
+        const int64_t g = (int64_t)d * n + j;
+        const int l = lam[g];
+        e = make_int2(weight_bits<DT>(load_weight<DT>(theta, g, l, nullptr)), l & 0x7fffffff);
+    }
+    out[i] = e;
 }
+
+typedef int int16v __attribute__((ext_vector_type(16)));
 
 template <sc_dtype_t DT, int VPT, int WSRC>
 __global__ void
@@ -142,7 +151,42 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
     Y* yb = y + (int64_t)b * a.D * a.y_plane;
     const unsigned char* lane_base = lds + lane * (int)sizeof(X);
 
-    if constexpr (WSRC == 1) __syncthreads();  // slab complete
+    if constexpr (WSRC == 1) {
+        // ------------------------------------------------------------ scalar-load weight path
+        // Each wave walks its rows d = wave, wave + nwaves, ...; a row is ng groups of 8
+        // {theta, lambda} pairs fetched with one 16-dword scalar load, one group ahead of the
+        // group being multiplied so the scalar-cache latency overlaps the LDS gather.
+        __syncthreads();  // slab complete
+        const int ng = a.np >> 3;
+        A acc[VPT];
+        for (int d = wave; d < a.D; d += nwaves) {
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc[k] = A(0);
+            if (ng > 0) {
+                const int16v* wg = reinterpret_cast<const int16v*>(wl32 + (int64_t)d * a.np);
+                const int dn = d + nwaves < a.D ? d + nwaves : d;
+                const int16v* wg_next = reinterpret_cast<const int16v*>(wl32 + (int64_t)dn * a.np);
+                int16v cur = wg[0];
+                for (int g = 0; g < ng; ++g) {
+                    const int16v nxt = g + 1 < ng ? wg[g + 1] : wg_next[0];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const WL w = weight_from_bits<DT>(cur[2 * i]);
+                        const unsigned char* pj = lane_base + cur[2 * i + 1];
+#pragma unroll
+                        for (int k = 0; k < VPT; ++k)
+                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                    }
+                    cur = nxt;
+                }
+            }
+            Y* yd = yb + (int64_t)d * a.y_plane;
+#pragma unroll
+            for (int k = 0; k < VPT; ++k)
+                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+        }
+        return;
+    }
 
     // ---------------------------------------------------------------- stream the weight rows
     A acc[VPT];
@@ -181,18 +225,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
                 }
                 if constexpr (WSRC == 0) {
                     const int2* wrow = wst + dd * jc;
-#pragma unroll 4
-                    for (int j = 0; j < jc; ++j) {
-                        const int2 e = wrow[j];
-                        const WL w = weight_from_bits<DT>(e.x);
-                        const unsigned char* pj = lane_base + e.y;
-#pragma unroll
-                        for (int k = 0; k < VPT; ++k)
-                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
-                    }
-                } else {
-                    const int2* wrow = wl32 + ((int64_t)(ds0 + dd) * a.n + j0);
-#pragma unroll 4
+#pragma unroll 8
                     for (int j = 0; j < jc; ++j) {
                         const int2 e = wrow[j];
                         const WL w = weight_from_bits<DT>(e.x);
@@ -222,24 +255,19 @@ int slab_grid_size(const Plan& p, const SlabGeom& g, int N)
 
 sc_status_t expand_weights(const Plan& p, hipStream_t stream)
 {
-    const int64_t cnt = (int64_t)p.L.D * p.n;
+    const int64_t cnt = (int64_t)p.L.D * p.np;
     if (cnt == 0 || !p.d_wl32) return SC_OK;
     const unsigned blocks = (unsigned)((cnt + 255) / 256);
+#define SC_EXPAND(DT)                                                                              \
+    hipLaunchKernelGGL(expand_weights_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
+                       p.d_lam_slab, p.d_wl32, p.L.D, p.n, p.np)
     switch (p.dtype) {
-        case SC_F32:
-            hipLaunchKernelGGL(expand_weights_kernel<SC_F32>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
-                               p.d_lam_slab, p.d_wl32, cnt);
-            break;
-        case SC_F16:
-            hipLaunchKernelGGL(expand_weights_kernel<SC_F16>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
-                               p.d_lam_slab, p.d_wl32, cnt);
-            break;
-        case SC_I8:
-            hipLaunchKernelGGL(expand_weights_kernel<SC_I8>, dim3(blocks), dim3(256), 0, stream, p.d_theta,
-                               p.d_lam_slab, p.d_wl32, cnt);
-            break;
+        case SC_F32: SC_EXPAND(SC_F32); break;
+        case SC_F16: SC_EXPAND(SC_F16); break;
+        case SC_I8: SC_EXPAND(SC_I8); break;
         default: return SC_ERR_UNSUPPORTED;
     }
+#undef SC_EXPAND
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
@@ -303,7 +331,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.TP = g.TP; a.TQ = g.TQ; a.tiles_p = g.tiles_p; a.tiles_q = g.tiles_q;
     a.nsw = g.nsw; a.Qs = g.Qs; a.sub_pitch = g.sub_pitch; a.chan_pitch = g.chan_pitch; a.F = g.F;
     a.slab_elems = p.L.C * g.chan_pitch;
-    a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC;
+    a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC; a.np = p.np;
     // 16-byte staging also needs a 16-byte aligned input pointer
     a.vec = (g.vec && (reinterpret_cast<uintptr_t>(x) % 16 == 0)) ? 1 : 0;
     a.inv_chan_pitch = g.inv_chan_pitch; a.inv_sub_pitch = g.inv_sub_pitch; a.inv_Qs = g.inv_Qs;
