@@ -72,9 +72,10 @@ typedef struct {
 /* Kernel families (sc_tuning_t.variant). */
 enum {
     SC_VARIANT_AUTO = 0,   /* let the library pick by heuristic */
-    SC_VARIANT_GATHER = 1, /* Algorithm-3 shape: one workgroup = one output channel x a pixel tile x
-                              sub_batch samples; (theta, lambda) row in LDS; input gathered from
-                              global memory (a padded copy in the workspace when pad > 0) */
+    SC_VARIANT_GATHER = 1, /* Algorithm-3 shape: one workgroup = one output channel x a tile of output
+                              positions (flat over sample, row, column); (theta, lambda) row in LDS;
+                              input gathered from global memory (a padded copy in the workspace
+                              when pad > 0) */
     SC_VARIANT_SLAB = 2    /* one workgroup = one sample x an output tile x all output channels;
                               the input tile (all C channels, halo and zero padding included) is
                               staged once in LDS and every row of (theta, lambda) is streamed over it */
@@ -86,13 +87,16 @@ enum {
 typedef struct {
     int32_t variant;    /* SC_VARIANT_* */
     int32_t wg_threads; /* workgroup size: 64..1024, multiple of 64 */
-    int32_t sub_batch;  /* GATHER: samples per workgroup (sb_S), 1, 2, 4 or 8 */
+    int32_t sub_batch;  /* GATHER: output positions per thread that share each (theta, lambda) read
+                           from LDS (the role of sb_S), 1, 2, 4 or 8 */
     int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
     int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
     int32_t wsrc;       /* SLAB: how a wave gets (theta, lambda): 0 = LDS broadcast read,
                            1 = scalar loads from global memory */
-    int32_t reserved[5];
+    int32_t split_n;    /* GATHER: lanes that share one output, each summing every split_n-th stored
+                           entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64 */
+    int32_t reserved[4];
 } sc_tuning_t;
 
 typedef struct {

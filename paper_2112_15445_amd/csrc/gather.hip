@@ -1,13 +1,14 @@
 // GATHER variant: the launch shape of the paper's Algorithm 3, written for 64-wide wavefronts.
 //
-// One workgroup computes one output channel d for a tile of output pixels and SB consecutive
-// samples (the paper's sub-batch sb_S, so the grid has pixel_tiles * D * ceil(N / SB) workgroups,
-// the analogue of N_B = b_S * D / sb_S).  The (theta, lambda) row of channel d is staged in LDS in
-// chunks; each thread owns one output pixel, keeps one accumulator per sample in registers, reads
-// every (theta, lambda) pair once from LDS and reuses it for the SB samples, and gathers the input
-// straight from global memory at  sample_base + p*s_h*Wp + q*s_w + lambda.  The input it reads is
-// the physically zero-padded tensor: when the layer has padding, a small pre-pass writes it into
-// the caller's workspace first (the paper feeds its kernel pre-padded inputs).
+// One workgroup computes one output channel d for a tile of output positions.  The (theta, lambda)
+// row of channel d is staged in LDS in chunks; each thread keeps its accumulators in registers,
+// reads every (theta, lambda) pair once from LDS, reuses it for its sub_batch output positions
+// (the role the paper's sub-batch sb_S plays: shared-memory reads are amortised over several
+// outputs, and the grid shrinks to D * positions / (threads * sub_batch) workgroups, the analogue
+// of N_B = b_S * D / sb_S), and gathers the input straight from global memory at
+// sample_base + p*s_h*Wp + q*s_w + lambda.  The input it reads is the physically zero-padded
+// tensor: when the layer has padding, a small pre-pass writes it into the caller's workspace first
+// (the paper feeds its kernel pre-padded inputs).
 #include "sc_device.h"
 #include "sc_internal.h"
 
@@ -33,65 +34,108 @@ pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp, int64_t total, int
     }
 }
 
-template <sc_dtype_t DT, int SB>
+// One workgroup = one output channel d (blockIdx.y) x a tile of output positions.  Positions are
+// numbered flat over (sample, p, q), so layers with tiny output planes still fill every lane when
+// the batch is large.  The 256 threads are laid out as (256 / NSPLIT) position slots x NSPLIT entry
+// slices: a thread owns VPT positions (slot, slot + 256/NSPLIT, ...) and, when NSPLIT > 1, only the
+// stored entries j = slice (mod NSPLIT); the NSPLIT partial sums of one output sit in adjacent
+// lanes and are combined with a butterfly of cross-lane shuffles (wavefront-level reduction), which
+// is what keeps the lanes busy when there are fewer output positions than lanes.
+template <sc_dtype_t DT, int VPT, int NSPLIT>
 __global__ void __launch_bounds__(256)
 gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restrict__ theta,
               const int32_t* __restrict__ lam, const int8_t* __restrict__ codebook,
-              typename Types<DT>::Y* __restrict__ y, int N, int D, int n, int P, int Q, int s_h,
-              int s_w, int Wp, int64_t X_size)
+              typename Types<DT>::Y* __restrict__ y, int64_t total_pos, int D, int n, int PQ, int Q,
+              int s_h, int s_w, int Wp, int64_t X_size)
 {
     using A = typename Types<DT>::A;
     using WL = typename Types<DT>::WL;
     __shared__ WL theta_s[kRowChunk];
     __shared__ int32_t lam_s[kRowChunk];
     __shared__ int8_t cb_s[16];
+    constexpr int SLOTS = 256 / NSPLIT;
 
     const int d = blockIdx.y;
-    const int b0 = blockIdx.z * SB;
-    const int pix = blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = pix < P * Q;
-    const int p = live ? pix / Q : 0;
-    const int q = live ? pix - p * Q : 0;
-    const int base = p * s_h * Wp + q * s_w;
+    const int slice = threadIdx.x % NSPLIT;
+    const int slot = threadIdx.x / NSPLIT;
+    const int64_t g0 = (int64_t)blockIdx.x * (SLOTS * VPT) + slot;
 
     if constexpr (DT == SC_CB4_I8) {
         if (threadIdx.x < 16) cb_s[threadIdx.x] = codebook[threadIdx.x];
     }
-    A acc[SB];
+    // positions past the end re-read position 0; their results are not stored
+    const typename Types<DT>::X* xs[VPT];
+    int64_t yoff[VPT];
+    A acc[VPT];
 #pragma unroll
-    for (int t = 0; t < SB; ++t) acc[t] = A(0);
-    // samples past the end of the batch re-read the last one; their results are not stored
-    const typename Types<DT>::X* xs[SB];
-#pragma unroll
-    for (int t = 0; t < SB; ++t) xs[t] = xp + (int64_t)min(b0 + t, N - 1) * X_size + base;
+    for (int k = 0; k < VPT; ++k) {
+        const int64_t g = g0 + (int64_t)k * SLOTS;
+        const bool live = g < total_pos;
+        const int64_t gc = live ? g : 0;
+        const int64_t b = gc / PQ;
+        const int f = (int)(gc - b * PQ);
+        const int p = f / Q, q = f - p * Q;
+        xs[k] = xp + b * X_size + (int64_t)p * s_h * Wp + q * s_w;
+        yoff[k] = live ? (b * D + d) * (int64_t)PQ + f : -1;
+        acc[k] = A(0);
+    }
 
     for (int j0 = 0; j0 < n; j0 += kRowChunk) {
         const int jc = min(kRowChunk, n - j0);
         __syncthreads();
-        for (int j = threadIdx.x; j < jc; j += blockDim.x) {
+        for (int j = threadIdx.x; j < jc; j += 256) {
             const int64_t i = (int64_t)d * n + j0 + j;
             const int l = lam[i];
             theta_s[j] = load_weight<DT>(theta, i, l, cb_s);
             lam_s[j] = l & 0x7fffffff;
         }
         __syncthreads();
-        for (int j = 0; j < jc; ++j) {
+#pragma unroll 4
+        for (int j = slice; j < jc; j += NSPLIT) {
             const WL w = theta_s[j];
             const int l = lam_s[j];
 #pragma unroll
-            for (int t = 0; t < SB; ++t) acc[t] += w * widen<DT>(xs[t][l]);
+            for (int k = 0; k < VPT; ++k) acc[k] += w * widen<DT>(xs[k][l]);
         }
     }
-    if (!live) return;
 #pragma unroll
-    for (int t = 0; t < SB; ++t)
-        if (b0 + t < N) y[((int64_t)(b0 + t) * D + d) * ((int64_t)P * Q) + pix] = narrow<DT>(acc[t]);
+    for (int k = 0; k < VPT; ++k) {
+        A v = acc[k];
+#pragma unroll
+        for (int m = NSPLIT / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (slice == 0 && yoff[k] >= 0) y[yoff[k]] = narrow<DT>(v);
+    }
 }
 
 size_t gather_workspace_bytes(const Plan& p, int N)
 {
     if (p.L.pad_h == 0 && p.L.pad_w == 0) return 0;
     return (size_t)N * (size_t)p.X_size * (size_t)p.ex;
+}
+
+int gather_grid_size(const Plan& p, const sc_tuning_t& t, int N)
+{
+    const int64_t total = (int64_t)N * p.P * p.Q;
+    const int per_wg = (256 / t.split_n) * t.sub_batch;
+    return (int)((total + per_wg - 1) / per_wg) * p.L.D;
+}
+
+template <sc_dtype_t DT, int VPT>
+static void launch_gather_split(const Plan& p, dim3 grid, hipStream_t stream,
+                                const typename Types<DT>::X* xp, typename Types<DT>::Y* y, int64_t total)
+{
+#define SC_GATHER_LAUNCH(NS)                                                                      \
+    hipLaunchKernelGGL((gather_kernel<DT, VPT, NS>), grid, dim3(256), 0, stream, xp, p.d_theta,   \
+                       p.d_lam, p.d_codebook, y, total, p.L.D, p.n, p.P * p.Q, p.Q, p.L.stride_h, \
+                       p.L.stride_w, p.Wp, p.X_size)
+    switch (p.tuning.split_n) {
+        case 1: SC_GATHER_LAUNCH(1); break;
+        case 4: SC_GATHER_LAUNCH(4); break;
+        case 16: SC_GATHER_LAUNCH(16); break;
+        case 64: SC_GATHER_LAUNCH(64); break;
+        default: break;
+    }
+#undef SC_GATHER_LAUNCH
 }
 
 template <sc_dtype_t DT>
@@ -108,23 +152,20 @@ static sc_status_t launch_gather_t(const Plan& p, const void* x, void* y, int N,
                            static_cast<X*>(ws), total, p.L.H, p.L.W, p.Hp, p.Wp, p.L.pad_h, p.L.pad_w);
         xp = static_cast<const X*>(ws);
     }
-    const int threads = 256;
-    const int pix = p.P * p.Q;
-    const int sb = p.tuning.sub_batch;
-    dim3 grid((pix + threads - 1) / threads, p.L.D, (N + sb - 1) / sb);
-    if (grid.y > 65535 || grid.z > 65535) return SC_ERR_UNSUPPORTED;
-#define SC_GATHER_LAUNCH(SB)                                                                       \
-    hipLaunchKernelGGL((gather_kernel<DT, SB>), grid, dim3(threads), 0, stream, xp, p.d_theta,    \
-                       p.d_lam, p.d_codebook, static_cast<Y*>(y), N, p.L.D, p.n, p.P, p.Q,        \
-                       p.L.stride_h, p.L.stride_w, p.Wp, p.X_size)
-    switch (sb) {
-        case 1: SC_GATHER_LAUNCH(1); break;
-        case 2: SC_GATHER_LAUNCH(2); break;
-        case 4: SC_GATHER_LAUNCH(4); break;
-        case 8: SC_GATHER_LAUNCH(8); break;
+    const int64_t total = (int64_t)N * p.P * p.Q;
+    const int vpt = p.tuning.sub_batch, ns = p.tuning.split_n;
+    if (ns != 1 && ns != 4 && ns != 16 && ns != 64) return SC_ERR_UNSUPPORTED;
+    const int per_wg = (256 / ns) * vpt;
+    const int64_t gx = (total + per_wg - 1) / per_wg;
+    if (gx >= (1ll << 31) || p.L.D > 65535) return SC_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)gx, p.L.D, 1);
+    switch (vpt) {
+        case 1: launch_gather_split<DT, 1>(p, grid, stream, xp, static_cast<Y*>(y), total); break;
+        case 2: launch_gather_split<DT, 2>(p, grid, stream, xp, static_cast<Y*>(y), total); break;
+        case 4: launch_gather_split<DT, 4>(p, grid, stream, xp, static_cast<Y*>(y), total); break;
+        case 8: launch_gather_split<DT, 8>(p, grid, stream, xp, static_cast<Y*>(y), total); break;
         default: return SC_ERR_UNSUPPORTED;
     }
-#undef SC_GATHER_LAUNCH
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 

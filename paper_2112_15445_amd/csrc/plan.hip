@@ -164,6 +164,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.tile_p = g.TP;
             t.tile_q = g.TQ;
             t.sub_batch = 0;
+            t.split_n = 0;
             *out = t;
             *geom = g;
             return SC_OK;
@@ -171,8 +172,12 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         if (t.variant == SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
     }
     t.variant = SC_VARIANT_GATHER;
+    t.wg_threads = 256;
     if (t.sub_batch == 0) t.sub_batch = 4;
     if (t.sub_batch != 1 && t.sub_batch != 2 && t.sub_batch != 4 && t.sub_batch != 8)
+        return SC_ERR_UNSUPPORTED;
+    if (t.split_n == 0) t.split_n = 1;
+    if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
     t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = 0;
     *out = t;
@@ -483,10 +488,7 @@ sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t
         info->grid_size = p->last_N ? slab_grid_size(*p, p->geom, p->last_N) : 0;
     } else {
         info->lds_bytes = 1024 * 8;
-        const int pix = p->P * p->Q;
-        info->grid_size = p->last_N ? ((pix + p->tuning.wg_threads - 1) / p->tuning.wg_threads) * p->L.D *
-                                          ((p->last_N + p->tuning.sub_batch - 1) / p->tuning.sub_batch)
-                                    : 0;
+        info->grid_size = p->last_N ? gather_grid_size(*p, p->tuning, p->last_N) : 0;
     }
     return SC_OK;
 }
@@ -560,12 +562,14 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             if (std::memcmp(&o, &r, sizeof(r)) == 0) return;
         out->push_back(r);
     };
-    for (int sb : {1, 2, 4, 8}) {
-        sc_tuning_t t{};
-        t.variant = SC_VARIANT_GATHER;
-        t.sub_batch = sb;
-        t.wg_threads = 256;
-        push(t);
+    for (int ns : {1, 4, 16, 64}) {
+        for (int sb : {1, 2, 4, 8}) {
+            sc_tuning_t t{};
+            t.variant = SC_VARIANT_GATHER;
+            t.sub_batch = sb;
+            t.split_n = ns;
+            push(t);
+        }
     }
     const bool pw = is_pointwise(p.L);
     for (int wsrc : {0, 1}) {

@@ -75,6 +75,7 @@ int elem_size_y(sc_dtype_t dt);
 
 // gather.hip
 size_t gather_workspace_bytes(const Plan& p, int N);
+int gather_grid_size(const Plan& p, const sc_tuning_t& t, int N);
 sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws, size_t ws_bytes,
                           hipStream_t stream);
 

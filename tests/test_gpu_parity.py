@@ -134,6 +134,22 @@ def test_long_rows_are_chunked(dtype):
         G.check(l, G.run_gpu(plan, data["x"]), ref, label)
 
 
+@pytest.mark.parametrize("dtype", DT)
+def test_wavefront_split_reduction(dtype):
+    """Few output positions (batch 1, 3x3 plane): the stored entries of one output are split over
+    4 / 16 / 64 lanes and combined by the wavefront-level shuffle reduction."""
+    l = wl.Layer("split", 40, 9, 5, 5, 3, 3, 1, 1, 0, 0, N=1, sparsity=0.5, dtype=dtype, seed=77)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    for ns in (1, 4, 16, 64):
+        for sb in (1, 2, 8):
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_GATHER, split_n=ns, sub_batch=sb)
+            t = plan.get_tuning()
+            assert (t.split_n, t.sub_batch) == (ns, sb)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"split_n={ns} sub_batch={sb}")
+
+
 def test_ell_entry_point_and_unsorted_duplicate_columns():
     rng = np.random.default_rng(3)
     l = wl.Layer("ell", 4, 5, 8, 8, 3, 3, 1, 1, 1, 1, N=2, dtype="i8")
