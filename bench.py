@@ -12,7 +12,10 @@ the method prescribes (it is per-layer, offline work).  Inputs are resident in H
 rotates over a ring of input/output buffers larger than twice the 256 MB Infinity Cache so that
 every launch really streams from HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit (useful GFLOP/s of the layer), ms_per_step, config
+(workload and launch shape), roofline (algorithmic bytes per launch over the measured kernel time,
+against the 8 TB/s HBM peak), the dense MIOpen time of the same layer for context, and
+cpu_baseline (the CPU oracle timed on the host cores).
 """
 from __future__ import annotations
 
@@ -103,9 +106,12 @@ def _cpu_baseline(l, data, oracle, max_samples):
             "oracle's widening to double and its padded copy)"}
 
 
-def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True):
+def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuning=None):
     data = wl.prepare(l)
     plan = G.make_plan(l, data)
+    if tuning:
+        plan.set_tuning(B.sc_tuning_t(), **tuning)
+        autotune = False
     xs, ys = _ring(plan, data, l, torch, G, B)
     ws_bytes = plan.workspace_size_max(l.N)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
@@ -137,11 +143,17 @@ def main():
     ap.add_argument("--layer", default=None, help="layer name from config 3 (default: headline)")
     ap.add_argument("--no-autotune", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tuning", default=None,
+                    help='pin the launch shape instead of autotuning, e.g. '
+                         '\'{"variant":2,"wg_threads":1024,"tile_q":64,"wg_per_cu":2,"wsrc":1}\'')
     ap.add_argument("--report", default=None, help="also time every layer of all configs -> JSON file")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark, run 20 plain 256 MiB device copies (the known-size "
+                         "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled against)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the path shards over the batch with no "
-              "exchange step; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (the path would shard over the batch with "
+              "no exchange step); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -152,10 +164,21 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        a = torch.empty(64 << 20, dtype=torch.float32, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        for _ in range(20):
+            torch.mul(a, 1.0, out=b)     # one plain elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "20 x elementwise copy kernel, 268435456 bytes read + "
+                                         "268435456 bytes written per launch"}))
+        return
+
     l = wl.headline_layer()
     if args.layer:
         l = {x.name: x for c in (3, 4, 2, 5, 1) for x in wl.CONFIGS[c]()}[args.layer]
-    res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl)
+    res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
+                                tuning=json.loads(args.tuning) if args.tuning else None)
 
     line = {
         "metric": "useful GFLOP/s (nnz MACs) per sparse conv layer",

@@ -92,11 +92,15 @@ typedef struct {
     int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
     int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
-    int32_t wsrc;       /* SLAB: how a wave gets (theta, lambda): 0 = LDS broadcast read,
-                           1 = scalar loads from global memory */
+    int32_t wsrc;       /* SLAB: how a wave gets (theta, lambda): 0 = staged in LDS, broadcast reads;
+                           1 = scalar loads from global memory; 2 = wave-uniform vector loads from
+                           global memory (vector L1), software-pipelined */
     int32_t split_n;    /* GATHER: lanes that share one output, each summing every split_n-th stored
                            entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64 */
-    int32_t reserved[4];
+    int32_t pipeline;   /* SLAB, pointwise layers: 1 = persistent workgroups that stream tile i+1 into a
+                           second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
+                           tile i is multiplied; needs wsrc = 1 or 2.  0 = one tile per workgroup */
+    int32_t reserved[3];
 } sc_tuning_t;
 
 typedef struct {

@@ -67,7 +67,7 @@ static bool is_pointwise(const sc_layer_t& L)
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
-static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int lds_budget, SlabGeom* g)
+static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int lds_budget, SlabGeom* g)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -99,10 +99,10 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     int64_t cap = (lds_budget - o.slab_bytes - 64) / 8;
     cap = std::min<int64_t>(cap, 4096);
     cap = std::min<int64_t>(cap, std::max<int64_t>(total, 1));
-    if (wsrc == 1) cap = 0;  // scalar-load path keeps no weights in LDS
+    if (wsrc != 0) cap = 0;  // weights straight from global memory: no weight stage in LDS
     else if (cap < std::min<int64_t>(std::max<int64_t>(total, 1), 512)) return false;
     o.wcap = (int)cap;
-    if (p.n == 0 || wsrc == 1) {
+    if (p.n == 0 || wsrc != 0) {
         o.DS = std::min(L.D, o.nwaves);
         o.JC = 0;
     } else if ((int64_t)p.n * std::min(o.nwaves, L.D) <= o.wcap) {
@@ -113,10 +113,17 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         o.JC = std::max(1, o.wcap / o.DS);
     }
     o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64;
-    if (o.lds_bytes > kMaxLdsBytes) return false;
+    if (pipeline == 1) {
+        // two tile buffers, no weight stage; only for pointwise layers whose rows can be copied
+        // 16 bytes at a time, and the workgroup needs consumer waves besides the producers
+        if (!pw || wsrc == 0 || o.nwaves < 4) return false;
+        o.lds_bytes = 2 * o.slab_bytes;
+    }
+    if (o.lds_bytes > lds_budget || o.lds_bytes > kMaxLdsBytes) return false;
     // 16-byte staging needs every tile row start and the plane pitch to be 16-byte aligned
     const int epv = 16 / p.ex;
     o.vec = (pw && (o.Wf % epv == 0) && (o.TQ % epv == 0)) ? 1 : 0;
+    if (pipeline == 1 && !o.vec) return false;
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -131,8 +138,9 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.variant < SC_VARIANT_AUTO || t.variant > SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
     if (t.wg_threads == 0) t.wg_threads = 256;
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc < 0 || t.wsrc > 1) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc == 1 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
+    if (t.wsrc < 0 || t.wsrc > 2) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc != 0 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
+    if (t.pipeline < 0 || t.pipeline > 1) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
         const bool pw = is_pointwise(L);
@@ -148,16 +156,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
@@ -165,6 +173,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.tile_q = g.TQ;
             t.sub_batch = 0;
             t.split_n = 0;
+            if (t.pipeline == 1) t.wg_per_cu = 1;
             *out = t;
             *geom = g;
             return SC_OK;
@@ -179,7 +188,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n == 0) t.split_n = 1;
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
-    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = 0;
+    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = 0;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -286,7 +295,7 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
         sc_status_t st = launch_stretch(*p, p->d_lam_slab, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
                                         g.chan_pitch, g.sub_pitch, g.Qs, p->ex, stream);
         if (st != SC_OK) return st;
-        if (t.wsrc == 1) {
+        if (t.wsrc != 0) {
             st = expand_weights(*p, stream);
             if (st != SC_OK) return st;
         }
@@ -306,9 +315,15 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     p->np = (p->n + 7) / 8 * 8;
     p->h_col = std::move(tab.col);
     // resolve the default tuning first: it is pure host arithmetic
+    // default launch shape before any autotune: the slab kernel with 16 waves per workgroup and
+    // weights by scalar loads where the layer allows it, otherwise whatever the heuristic resolves
     sc_tuning_t t{};
     SlabGeom g{};
-    sc_status_t st = resolve_tuning(*p, sc_tuning_t{}, &t, &g);
+    sc_tuning_t want{};
+    want.wg_threads = 1024;
+    want.wsrc = p->dtype == SC_CB4_I8 ? 0 : 1;
+    sc_status_t st = resolve_tuning(*p, want, &t, &g);
+    if (st != SC_OK) st = resolve_tuning(*p, sc_tuning_t{}, &t, &g);
     if (st != SC_OK) return st;
 
     std::vector<uint8_t> packed;
@@ -572,8 +587,25 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     const bool pw = is_pointwise(p.L);
-    for (int wsrc : {0, 1}) {
-        if (wsrc == 1 && p.dtype == SC_CB4_I8) continue;
+    if (pw && p.dtype != SC_CB4_I8) {
+        for (int threads : {512, 768, 1024}) {
+            for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
+              for (int wsrc : {1, 2}) {
+                sc_tuning_t t{};
+                t.variant = SC_VARIANT_SLAB;
+                t.wsrc = wsrc;
+                t.pipeline = 1;
+                t.wg_per_cu = 1;
+                t.wg_threads = threads;
+                t.tile_p = 1;
+                t.tile_q = tq;
+                push(t);
+              }
+            }
+        }
+    }
+    for (int wsrc : {0, 1, 2}) {
+        if (wsrc != 0 && p.dtype == SC_CB4_I8) continue;
         for (int wpc : {1, 2, 3, 4}) {
             for (int threads : {256, 512, 1024}) {
                 if (pw) {

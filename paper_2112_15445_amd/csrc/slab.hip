@@ -11,11 +11,14 @@
 // registers; one store per output value.  lambda here is the offset pre-stretched for the tile's
 // LDS layout (see SlabGeom), already scaled to bytes.
 //
-// (theta, lambda) reaches the lanes in one of two ways (tuning.wsrc):
+// (theta, lambda) reaches the lanes in one of three ways (tuning.wsrc):
 //   0  rows are staged in LDS in groups (decoding 4-bit codebook indices on the way) and read back
 //      with wave-uniform (broadcast) LDS reads, as Algorithm 3 does from shared memory;
 //   1  rows are read with scalar loads from a pre-expanded {theta32, lambda} table in global
-//      memory, which keeps the LDS pipe free for the gather itself.
+//      memory, which keeps the LDS pipe free for the gather itself;
+//   2  the same table is read with wave-uniform 16-byte vector loads (all lanes the same address),
+//      which are counted by vmcnt and can therefore be kept several groups ahead of their use
+//      without ever waiting on the LDS counter.
 #include <mutex>
 
 #include "sc_device.h"
@@ -70,6 +73,72 @@ expand_weights_kernel(const void* __restrict__ theta, const int32_t* __restrict_
 }
 
 typedef int int16v __attribute__((ext_vector_type(16)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+
+// One group = 8 {theta32, lambda} pairs = 64 bytes of the expanded weight table.
+//   WSRC 1: one 16-dword scalar load (values arrive in SGPRs; latency of the scalar cache / L2)
+//   WSRC 2: four 16-byte buffer loads at a wave-uniform address (values arrive in VGPRs, the same in
+//           every lane; served by the vector L1, counted by vmcnt, so the compiler can keep several
+//           groups in flight independently of the LDS traffic)
+template <int WSRC>
+__device__ inline void load_group(int (&o)[16], const int2* __restrict__ wl32,
+                                  __amdgpu_buffer_rsrc_t rsrc, int64_t entry)
+{
+    if constexpr (WSRC == 1) {
+        const int16v t = *reinterpret_cast<const int16v*>(wl32 + entry);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = t[i];
+    } else {
+        const int base = (int)(entry * 8);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint4v t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, 0, base + q * 16, 0);
+            o[4 * q + 0] = (int)t.x; o[4 * q + 1] = (int)t.y; o[4 * q + 2] = (int)t.z; o[4 * q + 3] = (int)t.w;
+        }
+    }
+}
+
+// Rows d = first, first + stride, ... of the layer over the tile resident at lane_base: for every
+// stored entry gather slab[position + lambda] for the lane's VPT positions and accumulate; one
+// store per output.  Groups are fetched one ahead of the group being multiplied.
+template <sc_dtype_t DT, int VPT, int WSRC>
+__device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffer_rsrc_t rsrc,
+                                   const unsigned char* lane_base, typename Types<DT>::Y* yb,
+                                   const int (&out_off)[VPT], int first, int stride, int D, int np,
+                                   int64_t y_plane)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    const int ng = np >> 3;
+    A acc[VPT];
+    int cur[16], nxt[16];
+    if (ng > 0 && first < D) load_group<WSRC>(cur, wl32, rsrc, (int64_t)first * np);
+    for (int d = first; d < D; d += stride) {
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) acc[k] = A(0);
+        const int dn = d + stride < D ? d + stride : d;
+        for (int g = 0; g < ng; ++g) {
+            const int64_t e_next = g + 1 < ng ? (int64_t)d * np + (g + 1) * 8 : (int64_t)dn * np;
+            load_group<WSRC>(nxt, wl32, rsrc, e_next);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const WL w = weight_from_bits<DT>(cur[2 * i]);
+                const unsigned char* pj = lane_base + cur[2 * i + 1];
+#pragma unroll
+                for (int k = 0; k < VPT; ++k)
+                    acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cur[i] = nxt[i];
+        }
+        Y* yd = yb + (int64_t)d * y_plane;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k)
+            if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+    }
+}
 
 template <sc_dtype_t DT, int VPT, int WSRC>
 __global__ void
@@ -151,40 +220,13 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
     Y* yb = y + (int64_t)b * a.D * a.y_plane;
     const unsigned char* lane_base = lds + lane * (int)sizeof(X);
 
-    if constexpr (WSRC == 1) {
-        // ------------------------------------------------------------ scalar-load weight path
-        // Each wave walks its rows d = wave, wave + nwaves, ...; a row is ng groups of 8
-        // {theta, lambda} pairs fetched with one 16-dword scalar load, one group ahead of the
-        // group being multiplied so the scalar-cache latency overlaps the LDS gather.
+    if constexpr (WSRC != 0) {
+        // ------------------------------------------------------------ weights straight from global
+        // memory (scalar loads or wave-uniform vector loads), no weight stage in LDS
         __syncthreads();  // slab complete
-        const int ng = a.np >> 3;
-        A acc[VPT];
-        for (int d = wave; d < a.D; d += nwaves) {
-#pragma unroll
-            for (int k = 0; k < VPT; ++k) acc[k] = A(0);
-            if (ng > 0) {
-                const int16v* wg = reinterpret_cast<const int16v*>(wl32 + (int64_t)d * a.np);
-                const int dn = d + nwaves < a.D ? d + nwaves : d;
-                const int16v* wg_next = reinterpret_cast<const int16v*>(wl32 + (int64_t)dn * a.np);
-                int16v cur = wg[0];
-                for (int g = 0; g < ng; ++g) {
-                    const int16v nxt = g + 1 < ng ? wg[g + 1] : wg_next[0];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const WL w = weight_from_bits<DT>(cur[2 * i]);
-                        const unsigned char* pj = lane_base + cur[2 * i + 1];
-#pragma unroll
-                        for (int k = 0; k < VPT; ++k)
-                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
-                    }
-                    cur = nxt;
-                }
-            }
-            Y* yd = yb + (int64_t)d * a.y_plane;
-#pragma unroll
-            for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
-        }
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int2*>(wl32), 0, (int)((int64_t)a.D * a.np * 8), 0x00020000);
+        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, nwaves, a.D, a.np, a.y_plane);
         return;
     }
 
@@ -244,6 +286,93 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
             }
             j0 += a.JC;
         } while (j0 < a.n);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Persistent, double-buffered form of the slab kernel for pointwise layers (tuning.pipeline = 1).
+//
+// One workgroup per CU walks over (sample, tile) pairs.  Its last NPROD waves are producers: they
+// copy the next tile global -> LDS with the direct-to-LDS loads of gfx950 (16 bytes per lane, no
+// VGPR staging, up to 63 in flight per wave) into the buffer that is not being read.  The other
+// waves are consumers: they run the scalar-load gather-MAC of the one-shot kernel over the current
+// buffer and store the outputs.  Keeping loads and stores in different waves keeps their vmcnt
+// counters apart, so "my tile has landed" never has to wait for output stores, and the HBM stream
+// of tile i+1 overlaps the arithmetic of tile i.  Two workgroup barriers per tile hand the buffers
+// over.  Lanes whose pixels lie past the end of the plane load nothing; what they compute on stale
+// LDS contents is never stored.
+// ------------------------------------------------------------------------------------------------
+constexpr int kAsyncProducers = 2;
+
+template <sc_dtype_t DT, int VPT, int WSRC>
+__global__ void
+slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                  const int2* __restrict__ wl32, const SlabArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    typedef __attribute__((address_space(1))) const void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int EPV = 16 / (int)sizeof(X);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int ncons = nwaves - kAsyncProducers;
+    const int tiles = a.tiles_q;
+    const int total = a.N * tiles;
+    const int E = a.C * a.TQ;                  // elements of one tile (chan_pitch == TQ here)
+    const float inv_TQ = a.inv_Qs;
+    const int first = blockIdx.x, step = gridDim.x;
+
+    if (wave >= ncons) {
+        // ------------------------------------------------------------------ producer waves
+        const int pw = wave - ncons;
+        auto issue = [&](int t, int buf) {
+            const int b = fdiv(t, a.inv_tiles);
+            const int q0 = (t - b * tiles) * a.TQ;
+            const X* xb = x + (int64_t)b * a.x_sample_stride + q0;
+            unsigned char* dst = lds + buf * a.slab_bytes;
+            for (int i = pw; i * (64 * EPV) < E; i += kAsyncProducers) {
+                const int idx = i * (64 * EPV) + lane * EPV;
+                const int c = fdiv(idx, inv_TQ);
+                const int col = idx - c * a.TQ;
+                if (idx < E && q0 + col < a.Wf)
+                    __builtin_amdgcn_global_load_lds((gptr_t)(xb + (int64_t)c * a.Wf + col),
+                                                     (lptr_t)(dst + i * 1024), 16, 0, 0);
+            }
+        };
+        if (first < total) issue(first, 0);
+        int it = 0;
+        for (int t = first; t < total; t += step, ++it) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile t has landed
+            __syncthreads();                                   // A: consumers may read buffer it&1
+            if (t + step < total) issue(t + step, (it + 1) & 1);
+            __syncthreads();                                   // B: buffer it&1 is free again
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumer waves
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int2*>(wl32), 0, (int)((int64_t)a.D * a.np * 8), 0x00020000);
+    int it = 0;
+    for (int t = first; t < total; t += step, ++it) {
+        const int b = fdiv(t, a.inv_tiles);
+        const int q0 = (t - b * tiles) * a.TQ;
+        int out_off[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int f = k * 64 + lane;
+            out_off[k] = (f < a.TQ && q0 + f < a.Qf) ? q0 + f : -1;
+        }
+        Y* yb = y + (int64_t)b * a.D * a.y_plane;
+        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+        __syncthreads();  // A
+        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.np, a.y_plane);
+        __syncthreads();  // B
     }
 }
 
@@ -309,10 +438,62 @@ static sc_status_t launch_vpt(const Plan& p, const SlabArgs& a, const void* x, v
     return SC_ERR_UNSUPPORTED;
 }
 
+template <sc_dtype_t DT, int VPT, int WSRC>
+static sc_status_t launch_async_one(const Plan& p, const SlabArgs& a, const void* x, void* y,
+                                    hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_async_kernel<DT, VPT, WSRC>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    const int total = a.N * a.tiles_q;
+    const int grid = std::min(total, kNumCU * std::max(1, kMaxLdsBytes / p.geom.lds_bytes));
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_wl32, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int WSRC>
+static sc_status_t launch_async_w(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    switch (p.geom.vpt) {
+        case 1: return launch_async_one<DT, 1, WSRC>(p, a, x, y, stream);
+        case 2: return launch_async_one<DT, 2, WSRC>(p, a, x, y, stream);
+        case 3: return launch_async_one<DT, 3, WSRC>(p, a, x, y, stream);
+        case 4: return launch_async_one<DT, 4, WSRC>(p, a, x, y, stream);
+        case 5: return launch_async_one<DT, 5, WSRC>(p, a, x, y, stream);
+        case 6: return launch_async_one<DT, 6, WSRC>(p, a, x, y, stream);
+        case 7: return launch_async_one<DT, 7, WSRC>(p, a, x, y, stream);
+        case 8: return launch_async_one<DT, 8, WSRC>(p, a, x, y, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_async(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    return p.tuning.wsrc == 2 ? launch_async_w<DT, 2>(p, a, x, y, stream)
+                              : launch_async_w<DT, 1>(p, a, x, y, stream);
+}
+
 template <sc_dtype_t DT>
 static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                              hipStream_t stream)
 {
+    if constexpr (DT != SC_CB4_I8) {
+        if (p.tuning.pipeline == 1) {
+            // the direct-to-LDS copy needs 16-byte aligned rows: checked at tuning time for the
+            // layer, here for the caller's pointer (an unaligned x takes the one-shot kernel)
+            if (a.vec) return launch_async<DT>(p, a, x, y, stream);
+        }
+        if (p.tuning.wsrc == 2) return launch_vpt<DT, 2>(p, a, x, y, grid, stream);
+    }
     if constexpr (DT != SC_CB4_I8) {
         if (p.tuning.wsrc == 1) return launch_vpt<DT, 1>(p, a, x, y, grid, stream);
     }

@@ -17,7 +17,9 @@ DT = ["f32", "f16", "i8", "cb4"]
 def _both_variants(plan):
     """Yield a label for every kernel family that can run this plan (after installing it)."""
     for variant, extra in ((B.SC_VARIANT_GATHER, {}), (B.SC_VARIANT_SLAB, {"wsrc": 0}),
-                           (B.SC_VARIANT_SLAB, {"wsrc": 1})):
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1}), (B.SC_VARIANT_SLAB, {"wsrc": 2}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 256}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 256})):
         try:
             plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
         except B.SparseConvError as e:
