@@ -94,13 +94,15 @@ typedef struct {
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
     int32_t wsrc;       /* SLAB: how a wave gets (theta, lambda): 0 = staged in LDS, broadcast reads;
                            1 = scalar loads from global memory; 2 = wave-uniform vector loads from
-                           global memory (vector L1), software-pipelined */
+                           global memory (vector L1), software-pipelined; 3 = one entry per lane by
+                           coalesced vector loads, broadcast with v_readlane */
     int32_t split_n;    /* GATHER: lanes that share one output, each summing every split_n-th stored
                            entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64 */
     int32_t pipeline;   /* SLAB, pointwise layers: 1 = persistent workgroups that stream tile i+1 into a
                            second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
-                           tile i is multiplied; needs wsrc = 1 or 2.  0 = one tile per workgroup */
-    int32_t reserved[3];
+                           tile i is multiplied; needs wsrc != 0.  0 = one tile per workgroup */
+    int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
+    int32_t reserved[2];
 } sc_tuning_t;
 
 typedef struct {

@@ -44,7 +44,8 @@ class sc_tuning_t(ctypes.Structure):
                 ("sub_batch", ctypes.c_int32), ("tile_p", ctypes.c_int32),
                 ("tile_q", ctypes.c_int32), ("wg_per_cu", ctypes.c_int32),
                 ("wsrc", ctypes.c_int32), ("split_n", ctypes.c_int32),
-                ("pipeline", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("pipeline", ctypes.c_int32), ("producers", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}

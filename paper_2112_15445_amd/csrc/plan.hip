@@ -116,7 +116,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (pipeline == 1) {
         // two tile buffers, no weight stage; only for pointwise layers whose rows can be copied
         // 16 bytes at a time, and the workgroup needs consumer waves besides the producers
-        if (!pw || wsrc == 0 || o.nwaves < 4) return false;
+        if (!pw || wsrc == 0 || o.nwaves < 8) return false;
         o.lds_bytes = 2 * o.slab_bytes;
     }
     if (o.lds_bytes > lds_budget || o.lds_bytes > kMaxLdsBytes) return false;
@@ -138,9 +138,12 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.variant < SC_VARIANT_AUTO || t.variant > SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
     if (t.wg_threads == 0) t.wg_threads = 256;
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc < 0 || t.wsrc > 2) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
     if (t.wsrc != 0 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
     if (t.pipeline < 0 || t.pipeline > 1) return SC_ERR_UNSUPPORTED;
+    if (t.pipeline == 1 && t.producers == 0) t.producers = 2;
+    if (t.pipeline == 0) t.producers = 0;
+    if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
         const bool pw = is_pointwise(L);
@@ -188,7 +191,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n == 0) t.split_n = 1;
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
-    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = 0;
+    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = 0;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -312,7 +315,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
 {
     const size_t cnt = (size_t)p->L.D * p->n;
     const int wsz = elem_size_w_native(p->dtype);
-    p->np = (p->n + 7) / 8 * 8;
+    p->np = (p->n + 1) / 2 * 2;
     p->h_col = std::move(tab.col);
     // resolve the default tuning first: it is pure host arithmetic
     // default launch shape before any autotune: the slab kernel with 16 waves per workgroup and
@@ -590,8 +593,9 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     if (pw && p.dtype != SC_CB4_I8) {
         for (int threads : {512, 768, 1024}) {
             for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
-              for (int wsrc : {1, 2}) {
+              for (int wsrc : {1, 3}) for (int np_ : {1, 2, 4}) {
                 sc_tuning_t t{};
+                t.producers = np_;
                 t.variant = SC_VARIANT_SLAB;
                 t.wsrc = wsrc;
                 t.pipeline = 1;
@@ -604,7 +608,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
-    for (int wsrc : {0, 1, 2}) {
+    for (int wsrc : {0, 1, 2, 3}) {
         if (wsrc != 0 && p.dtype == SC_CB4_I8) continue;
         for (int wpc : {1, 2, 3, 4}) {
             for (int threads : {256, 512, 1024}) {

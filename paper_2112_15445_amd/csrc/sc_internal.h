@@ -47,7 +47,7 @@ struct Plan {
     sc_layer_t L;
     sc_dtype_t dtype;
     int n = 0;
-    int np = 0;                     // n rounded up to a multiple of 8 (row pitch of d_wl32)
+    int np = 0;                     // n rounded up to an even count (row pitch of d_wl32)
     int Hp = 0, Wp = 0, P = 0, Q = 0;
     int64_t X_size = 0;
     int64_t true_nnz = 0;

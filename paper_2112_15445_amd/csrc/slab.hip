@@ -18,7 +18,10 @@
 //      memory, which keeps the LDS pipe free for the gather itself;
 //   2  the same table is read with wave-uniform 16-byte vector loads (all lanes the same address),
 //      which are counted by vmcnt and can therefore be kept several groups ahead of their use
-//      without ever waiting on the LDS counter.
+//      without ever waiting on the LDS counter;
+//   3  lane j of the wave loads entry j of the row (one coalesced vector load per 64 entries, one
+//      chunk ahead) and every entry is broadcast to the wave with two v_readlane: two more VALU
+//      instructions per entry, but no scalar-cache or LDS latency in the inner loop.
 #include <mutex>
 
 #include "sc_device.h"
@@ -32,7 +35,7 @@ struct SlabArgs {
     int s_h, s_w, pad_h, pad_w;
     int TP, TQ, tiles_p, tiles_q;
     int nsw, Qs, sub_pitch, chan_pitch, F;
-    int slab_elems, slab_bytes, wcap, DS, JC, vec, np;
+    int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q;
     int64_t x_sample_stride, y_plane;
 };
@@ -53,8 +56,8 @@ template <sc_dtype_t DT> __device__ inline typename Types<DT>::WL weight_from_bi
 }
 
 // Expand the compact weight table to {theta widened to 32 bits, LDS byte offset} pairs for the
-// scalar-load path.  Rows are padded to np = round_up(n, 8) pairs (64 bytes per group of 8) with
-// zero weights at offset 0 so the kernel can fetch whole groups with one 16-dword scalar load.
+// scalar-load path.  Rows are packed with an even pitch np = round_up(n, 2) (a zero weight at
+// offset 0 fills an odd row), so the table of a small layer stays inside the 16 KB scalar cache.
 template <sc_dtype_t DT>
 __global__ void __launch_bounds__(256)
 expand_weights_kernel(const void* __restrict__ theta, const int32_t* __restrict__ lam,
@@ -84,7 +87,9 @@ template <int WSRC>
 __device__ inline void load_group(int (&o)[16], const int2* __restrict__ wl32,
                                   __amdgpu_buffer_rsrc_t rsrc, int64_t entry)
 {
-    if constexpr (WSRC == 1) {
+    if constexpr (WSRC == 3) {
+        (void)o; (void)wl32; (void)rsrc; (void)entry;
+    } else if constexpr (WSRC == 1) {
         const int16v t = *reinterpret_cast<const int16v*>(wl32 + entry);
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[i] = t[i];
@@ -98,41 +103,130 @@ __device__ inline void load_group(int (&o)[16], const int2* __restrict__ wl32,
     }
 }
 
+// Two {theta32, lambda} pairs (16 bytes).
+template <int WSRC>
+__device__ inline void load_pair(int* o, const int2* __restrict__ wl32, __amdgpu_buffer_rsrc_t rsrc,
+                                 int64_t entry)
+{
+    typedef int int4v __attribute__((ext_vector_type(4)));
+    if constexpr (WSRC == 1) {
+        const int4v t = *reinterpret_cast<const int4v*>(wl32 + entry);
+        o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
+    } else if constexpr (WSRC == 2) {
+        const uint4v t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, 0, (int)(entry * 8), 0);
+        o[0] = (int)t.x; o[1] = (int)t.y; o[2] = (int)t.z; o[3] = (int)t.w;
+    } else {
+        (void)o; (void)wl32; (void)rsrc; (void)entry;
+    }
+}
+
 // Rows d = first, first + stride, ... of the layer over the tile resident at lane_base: for every
 // stored entry gather slab[position + lambda] for the lane's VPT positions and accumulate; one
 // store per output.  Groups are fetched one ahead of the group being multiplied.
 template <sc_dtype_t DT, int VPT, int WSRC>
 __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffer_rsrc_t rsrc,
                                    const unsigned char* lane_base, typename Types<DT>::Y* yb,
-                                   const int (&out_off)[VPT], int first, int stride, int D, int np,
+                                   const int (&out_off)[VPT], int first, int stride, int D, int n, int np,
                                    int64_t y_plane)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
     using A = typename Types<DT>::A;
     using WL = typename Types<DT>::WL;
+    if constexpr (WSRC == 3) {
+        // Lane-distributed rows: lane j of the wave loads entry j of the row chunk (one coalesced
+        // 512-byte vector load per 64 entries, fetched one chunk ahead), and each entry is then
+        // broadcast with two v_readlane.  No scalar-cache latency, no LDS traffic for the weights.
+        const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        A acc3[VPT];
+        int2 cur2 = make_int2(0, 0), nxt2;
+        if (first < D && lane < n) cur2 = wl32[(int64_t)first * np + lane];
+        for (int d = first; d < D; d += stride) {
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc3[k] = A(0);
+            for (int c0 = 0; c0 < n; c0 += 64) {
+                const int cnt = min(64, n - c0);
+                // next chunk: same row, or the first chunk of this wave's next row
+                const bool more = c0 + 64 < n;
+                const int dn = more ? d : d + stride;
+                const int cn = more ? c0 + 64 : 0;
+                nxt2 = make_int2(0, 0);
+                if (dn < D && cn + lane < n) nxt2 = wl32[(int64_t)dn * np + cn + lane];
+                auto mac = [&](int j) {
+                    const WL w = weight_from_bits<DT>(__builtin_amdgcn_readlane(cur2.x, j));
+                    const unsigned char* pj = lane_base + __builtin_amdgcn_readlane(cur2.y, j);
+#pragma unroll
+                    for (int k = 0; k < VPT; ++k)
+                        acc3[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                };
+                int j = 0;
+                for (; j + 8 <= cnt; j += 8) {
+                    mac(j); mac(j + 1); mac(j + 2); mac(j + 3);
+                    mac(j + 4); mac(j + 5); mac(j + 6); mac(j + 7);
+                }
+                for (; j < cnt; ++j) mac(j);
+                cur2 = nxt2;
+            }
+            Y* yd = yb + (int64_t)d * y_plane;
+#pragma unroll
+            for (int k = 0; k < VPT; ++k)
+                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc3[k]);
+        }
+        return;
+    }
+    // Rows are packed with an even pitch np: ng full groups of 8 pairs, then up to 3 pairs of 2.
+    // Full groups ping-pong between two register sets (A, B) and are fetched one ahead of their
+    // use, across row boundaries; the tail pairs of a row are fetched when the row starts.
     const int ng = np >> 3;
+    const int tail = (np & 7) >> 1;
     A acc[VPT];
-    int cur[16], nxt[16];
-    if (ng > 0 && first < D) load_group<WSRC>(cur, wl32, rsrc, (int64_t)first * np);
+    int ga[16], gb[16], tl[12];
+    auto mac = [&](int wbits, int lam) {
+        const WL w = weight_from_bits<DT>(wbits);
+        const unsigned char* pj = lane_base + lam;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k)
+            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+    };
+    auto mac8 = [&](const int (&c)[16]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
+    };
+    if (ng > 0 && first < D) load_group<WSRC>(ga, wl32, rsrc, (int64_t)first * np);
     for (int d = first; d < D; d += stride) {
+        const int64_t rowb = (int64_t)d * np;
+        const bool has_next_row = d + stride < D;
+        const int64_t nextb = (int64_t)(d + stride) * np;
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+            if (t < tail) load_pair<WSRC>(&tl[4 * t], wl32, rsrc, rowb + ng * 8 + 2 * t);
 #pragma unroll
         for (int k = 0; k < VPT; ++k) acc[k] = A(0);
-        const int dn = d + stride < D ? d + stride : d;
-        for (int g = 0; g < ng; ++g) {
-            const int64_t e_next = g + 1 < ng ? (int64_t)d * np + (g + 1) * 8 : (int64_t)dn * np;
-            load_group<WSRC>(nxt, wl32, rsrc, e_next);
+        int g = 0;
+        while (g < ng) {
+            // A holds group g of this row
+            if (g + 1 < ng) load_group<WSRC>(gb, wl32, rsrc, rowb + (g + 1) * 8);
+            else if (has_next_row) load_group<WSRC>(gb, wl32, rsrc, nextb);
+            mac8(ga);
+            ++g;
+            if (g < ng) {
+                // B holds group g of this row
+                if (g + 1 < ng) load_group<WSRC>(ga, wl32, rsrc, rowb + (g + 1) * 8);
+                else if (has_next_row) load_group<WSRC>(ga, wl32, rsrc, nextb);
+                mac8(gb);
+                ++g;
+            } else {
+                // odd group count: the next row's first group sits in B; hand it to A
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const WL w = weight_from_bits<DT>(cur[2 * i]);
-                const unsigned char* pj = lane_base + cur[2 * i + 1];
-#pragma unroll
-                for (int k = 0; k < VPT; ++k)
-                    acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                for (int i = 0; i < 16; ++i) ga[i] = gb[i];
             }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) cur[i] = nxt[i];
         }
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+            if (t < tail) {
+                mac(tl[4 * t + 0], tl[4 * t + 1]);
+                mac(tl[4 * t + 2], tl[4 * t + 3]);
+            }
         Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
         for (int k = 0; k < VPT; ++k)
@@ -226,7 +320,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
         __syncthreads();  // slab complete
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<int2*>(wl32), 0, (int)((int64_t)a.D * a.np * 8), 0x00020000);
-        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, nwaves, a.D, a.np, a.y_plane);
+        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, nwaves, a.D, a.n, a.np, a.y_plane);
         return;
     }
 
@@ -292,7 +386,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 // ------------------------------------------------------------------------------------------------
 // Persistent, double-buffered form of the slab kernel for pointwise layers (tuning.pipeline = 1).
 //
-// One workgroup per CU walks over (sample, tile) pairs.  Its last NPROD waves are producers: they
+// One workgroup per CU walks over (sample, tile) pairs.  Its last tuning.producers waves are producers: they
 // copy the next tile global -> LDS with the direct-to-LDS loads of gfx950 (16 bytes per lane, no
 // VGPR staging, up to 63 in flight per wave) into the buffer that is not being read.  The other
 // waves are consumers: they run the scalar-load gather-MAC of the one-shot kernel over the current
@@ -302,7 +396,6 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 // over.  Lanes whose pixels lie past the end of the plane load nothing; what they compute on stale
 // LDS contents is never stored.
 // ------------------------------------------------------------------------------------------------
-constexpr int kAsyncProducers = 2;
 
 template <sc_dtype_t DT, int VPT, int WSRC>
 __global__ void
@@ -320,7 +413,8 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwaves = blockDim.x >> 6;
-    const int ncons = nwaves - kAsyncProducers;
+    const int nprod = a.nprod;
+    const int ncons = nwaves - nprod;
     const int tiles = a.tiles_q;
     const int total = a.N * tiles;
     const int E = a.C * a.TQ;                  // elements of one tile (chan_pitch == TQ here)
@@ -330,18 +424,32 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     if (wave >= ncons) {
         // ------------------------------------------------------------------ producer waves
         const int pw = wave - ncons;
+        // Producers run at raised wave priority so that their short address arithmetic is not
+        // queued behind the consumers' long instruction streams.  The (channel, column) of a lane's
+        // 16 bytes advances by a fixed step from one copy instruction to the next, so the division
+        // is done once per tile and the rest is increments.
+        __builtin_amdgcn_s_setprio(3);
+        const int EW = 64 * EPV;                          // elements per copy instruction
+        const int stepE = EW * nprod;
+        const int qstep = stepE / a.TQ, rstep = stepE - qstep * a.TQ;
         auto issue = [&](int t, int buf) {
             const int b = fdiv(t, a.inv_tiles);
             const int q0 = (t - b * tiles) * a.TQ;
-            const X* xb = x + (int64_t)b * a.x_sample_stride + q0;
             unsigned char* dst = lds + buf * a.slab_bytes;
-            for (int i = pw; i * (64 * EPV) < E; i += kAsyncProducers) {
-                const int idx = i * (64 * EPV) + lane * EPV;
-                const int c = fdiv(idx, inv_TQ);
-                const int col = idx - c * a.TQ;
+            int idx = pw * EW + lane * EPV;
+            int c = fdiv(idx, inv_TQ);
+            int col = idx - c * a.TQ;
+            const X* src = x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c * a.Wf + col;
+            for (int i = pw; i * EW < E; i += nprod) {
                 if (idx < E && q0 + col < a.Wf)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(xb + (int64_t)c * a.Wf + col),
-                                                     (lptr_t)(dst + i * 1024), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + i * 1024), 16, 0, 0);
+                idx += stepE;
+                col += rstep;
+                src += (int64_t)qstep * a.Wf + rstep;
+                if (col >= a.TQ) {
+                    col -= a.TQ;
+                    src += a.Wf - a.TQ;
+                }
             }
         };
         if (first < total) issue(first, 0);
@@ -371,7 +479,7 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         Y* yb = y + (int64_t)b * a.D * a.y_plane;
         const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
         __syncthreads();  // A
-        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.np, a.y_plane);
+        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.n, a.np, a.y_plane);
         __syncthreads();  // B
     }
 }
@@ -478,6 +586,7 @@ static sc_status_t launch_async_w(const Plan& p, const SlabArgs& a, const void* 
 template <sc_dtype_t DT>
 static sc_status_t launch_async(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
 {
+    if (p.tuning.wsrc == 3) return launch_async_w<DT, 3>(p, a, x, y, stream);
     return p.tuning.wsrc == 2 ? launch_async_w<DT, 2>(p, a, x, y, stream)
                               : launch_async_w<DT, 1>(p, a, x, y, stream);
 }
@@ -493,6 +602,7 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
             if (a.vec) return launch_async<DT>(p, a, x, y, stream);
         }
         if (p.tuning.wsrc == 2) return launch_vpt<DT, 2>(p, a, x, y, grid, stream);
+        if (p.tuning.wsrc == 3) return launch_vpt<DT, 3>(p, a, x, y, grid, stream);
     }
     if constexpr (DT != SC_CB4_I8) {
         if (p.tuning.wsrc == 1) return launch_vpt<DT, 1>(p, a, x, y, grid, stream);
@@ -512,7 +622,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.TP = g.TP; a.TQ = g.TQ; a.tiles_p = g.tiles_p; a.tiles_q = g.tiles_q;
     a.nsw = g.nsw; a.Qs = g.Qs; a.sub_pitch = g.sub_pitch; a.chan_pitch = g.chan_pitch; a.F = g.F;
     a.slab_elems = p.L.C * g.chan_pitch;
-    a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC; a.np = p.np;
+    a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC; a.np = p.np; a.nprod = p.tuning.producers;
     // 16-byte staging also needs a 16-byte aligned input pointer
     a.vec = (g.vec && (reinterpret_cast<uintptr_t>(x) % 16 == 0)) ? 1 : 0;
     a.inv_chan_pitch = g.inv_chan_pitch; a.inv_sub_pitch = g.inv_sub_pitch; a.inv_Qs = g.inv_Qs;

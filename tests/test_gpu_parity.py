@@ -18,8 +18,10 @@ def _both_variants(plan):
     """Yield a label for every kernel family that can run this plan (after installing it)."""
     for variant, extra in ((B.SC_VARIANT_GATHER, {}), (B.SC_VARIANT_SLAB, {"wsrc": 0}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1}), (B.SC_VARIANT_SLAB, {"wsrc": 2}),
-                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 256}),
-                           (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 256})):
+                           (B.SC_VARIANT_SLAB, {"wsrc": 3}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 3, "pipeline": 1, "wg_threads": 512}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "producers": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 512, "producers": 4})):
         try:
             plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
         except B.SparseConvError as e:
