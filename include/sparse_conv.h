@@ -102,7 +102,11 @@ typedef struct {
                            second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
                            tile i is multiplied; needs wsrc != 0.  0 = one tile per workgroup */
     int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
-    int32_t reserved[2];
+    int32_t chunk_c;    /* SLAB with pipeline = 1: input channels per LDS buffer (0 = all of them).  With
+                           chunk_c < C a tile is multiplied chunk by chunk, each wave keeping the
+                           accumulators of its output channels in registers across the chunks, so
+                           wide tiles fit LDS even for layers with many input channels */
+    int32_t tile_d;     /* SLAB with chunk_c > 0: output channels per workgroup (0 = all of them) */
 } sc_tuning_t;
 
 typedef struct {

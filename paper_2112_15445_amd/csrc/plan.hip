@@ -27,7 +27,7 @@ static int elem_size_w_native(sc_dtype_t dt) { return dt == SC_F32 ? 4 : dt == S
 __global__ void __launch_bounds__(256)
 stretch_kernel(const int32_t* __restrict__ col, int32_t* __restrict__ lam, int64_t count, int R,
                int S, int nsh, int nsw, int s_h, int s_w, int chan_pitch, int sub_pitch,
-               int row_pitch, int scale)
+               int row_pitch, int scale, int chan_mod)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
@@ -35,8 +35,9 @@ stretch_kernel(const int32_t* __restrict__ col, int32_t* __restrict__ lam, int64
     // index cannot say "zero"); it is carried over to the offset so the kernel can zero the weight
     const int flag = col[i] & (int)0x80000000;
     const int k = col[i] & 0x7fffffff;
-    const int c = k / (R * S);
-    const int rs = k - c * (R * S);
+    const int cfull = k / (R * S);
+    const int rs = k - cfull * (R * S);
+    const int c = chan_mod > 0 ? cfull % chan_mod : cfull;  // channel within its LDS chunk
     const int r = rs / S;
     const int s = rs - r * S;
     const int phase = (r % nsh) * nsw + (s % nsw);
@@ -45,14 +46,14 @@ stretch_kernel(const int32_t* __restrict__ col, int32_t* __restrict__ lam, int64
 }
 
 sc_status_t launch_stretch(const Plan& p, int32_t* d_out, int nsh, int nsw, int s_h, int s_w,
-                           int chan_pitch, int sub_pitch, int row_pitch, int scale,
+                           int chan_pitch, int sub_pitch, int row_pitch, int scale, int chan_mod,
                            hipStream_t stream)
 {
     const int64_t count = (int64_t)p.L.D * p.n;
     if (count == 0) return SC_OK;
     const unsigned blocks = (unsigned)((count + 255) / 256);
     hipLaunchKernelGGL(stretch_kernel, dim3(blocks), dim3(256), 0, stream, p.d_col, d_out, count,
-                       p.L.R, p.L.S, nsh, nsw, s_h, s_w, chan_pitch, sub_pitch, row_pitch, scale);
+                       p.L.R, p.L.S, nsh, nsw, s_h, s_w, chan_pitch, sub_pitch, row_pitch, scale, chan_mod);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
@@ -67,7 +68,8 @@ static bool is_pointwise(const sc_layer_t& L)
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
-static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int lds_budget, SlabGeom* g)
+static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int producers,
+                          int chunk_c, int tile_d, int lds_budget, SlabGeom* g)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -91,7 +93,21 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (o.F > kWave * kMaxVpt) return false;
     o.vpt = (o.F + kWave - 1) / kWave;
     o.nwaves = wg_threads / kWave;
-    const int64_t slab = (int64_t)L.C * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
+    o.CC = chunk_c > 0 ? std::min(chunk_c, L.C) : L.C;
+    o.nchunks = (L.C + o.CC - 1) / o.CC;
+    o.DTW = (chunk_c > 0 && tile_d > 0) ? std::min(tile_d, L.D) : L.D;
+    o.ndt = (L.D + o.DTW - 1) / o.DTW;
+    o.rpw = 0;
+    if (chunk_c > 0) {
+        // chunked form: pointwise layers, pipelined, weights by scalar loads; every consumer wave
+        // keeps the accumulators of its rows in registers across the chunks of a tile
+        if (!pw || pipeline != 1 || wsrc != 1 || p.dtype == SC_CB4_I8) return false;
+        const int ncons = o.nwaves - producers;
+        if (ncons < 1) return false;
+        o.rpw = (o.DTW + ncons - 1) / ncons;
+        if (o.rpw > kMaxRowsPerWave) return false;
+    }
+    const int64_t slab = (int64_t)o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);
     // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
@@ -143,11 +159,13 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.pipeline < 0 || t.pipeline > 1) return SC_ERR_UNSUPPORTED;
     if (t.pipeline == 1 && t.producers == 0) t.producers = 2;
     if (t.pipeline == 0) t.producers = 0;
+    if (t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
+    if (t.chunk_c == 0) t.tile_d = 0;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
         const bool pw = is_pointwise(L);
-        if (t.wg_per_cu == 0) t.wg_per_cu = 2;
+        if (t.wg_per_cu == 0) t.wg_per_cu = t.pipeline == 1 ? 1 : 2;
         if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
         const int budget = kMaxLdsBytes / t.wg_per_cu;
         SlabGeom g{};
@@ -159,16 +177,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
@@ -177,6 +195,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.sub_batch = 0;
             t.split_n = 0;
             if (t.pipeline == 1) t.wg_per_cu = 1;
+            if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
             *out = t;
             *geom = g;
             return SC_OK;
@@ -191,7 +210,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n == 0) t.split_n = 1;
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
-    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = 0;
+    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = 0;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -278,6 +297,11 @@ static void free_device(Plan* p)
     if (p->d_lam_slab) (void)hipFree(p->d_lam_slab);
     if (p->d_wl32) (void)hipFree(p->d_wl32);
     p->d_wl32 = nullptr;
+    if (p->d_wlc) (void)hipFree(p->d_wlc);
+    if (p->d_seg_off) (void)hipFree(p->d_seg_off);
+    if (p->d_first_j) (void)hipFree(p->d_first_j);
+    p->d_wlc = nullptr;
+    p->d_seg_off = p->d_first_j = nullptr;
     if (p->d_scales) (void)hipFree(p->d_scales);
     if (p->d_codebook) (void)hipFree(p->d_codebook);
     p->d_col = p->d_lam = p->d_lam_slab = nullptr;
@@ -296,11 +320,45 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
 {
     if (t.variant == SC_VARIANT_SLAB) {
         sc_status_t st = launch_stretch(*p, p->d_lam_slab, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
-                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex, stream);
+                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex, t.chunk_c, stream);
         if (st != SC_OK) return st;
-        if (t.wsrc != 0) {
+        if (t.wsrc != 0 && t.chunk_c == 0) {
             st = expand_weights(*p, stream);
             if (st != SC_OK) return st;
+        }
+        if (t.chunk_c > 0) {
+            // segment table of the chunked form: for every (row, chunk) the entries whose input
+            // channel lies in the chunk, contiguous because rows are sorted by column; segments
+            // are padded to an even length.  Counted on the host, filled by a device pass.
+            const int D = p->L.D, nch = g.nchunks, RS = p->L.R * p->L.S;
+            std::vector<int32_t> seg_off((size_t)D * nch + 1, 0), first_j((size_t)D * nch, 0);
+            int64_t total = 0;
+            for (int d = 0; d < D; ++d) {
+                int j = 0;
+                for (int ch = 0; ch < nch; ++ch) {
+                    seg_off[(size_t)d * nch + ch] = (int32_t)total;
+                    first_j[(size_t)d * nch + ch] = j;
+                    int cnt = 0;
+                    while (j < p->n && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt; }
+                    total += (cnt + 1) / 2 * 2;
+                }
+            }
+            seg_off[(size_t)D * nch] = (int32_t)total;
+            if (total + 16 >= (1ll << 28)) return SC_ERR_RANGE;
+            if (p->d_wlc) { (void)hipFree(p->d_wlc); p->d_wlc = nullptr; }
+            if (p->d_seg_off) { (void)hipFree(p->d_seg_off); p->d_seg_off = nullptr; }
+            if (p->d_first_j) { (void)hipFree(p->d_first_j); p->d_first_j = nullptr; }
+            hipError_t e;
+            if ((e = hipMalloc((void**)&p->d_wlc, (size_t)(total + 16) * 8)) != hipSuccess) return hip_status(e);
+            if ((e = hipMalloc((void**)&p->d_seg_off, seg_off.size() * 4)) != hipSuccess) return hip_status(e);
+            if ((e = hipMalloc((void**)&p->d_first_j, std::max<size_t>(first_j.size(), 1) * 4)) != hipSuccess) return hip_status(e);
+            if ((e = hipMemcpyAsync(p->d_seg_off, seg_off.data(), seg_off.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_status(e);
+            if (!first_j.empty() && (e = hipMemcpyAsync(p->d_first_j, first_j.data(), first_j.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_status(e);
+            if ((e = hipMemsetAsync(p->d_wlc, 0, (size_t)(total + 16) * 8, stream)) != hipSuccess) return hip_status(e);
+            st = expand_weights_chunked(*p, g, total, stream);
+            if (st != SC_OK) return st;
+            // seg_off / first_j are read by the async copies until the synchronize below
+            if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
         }
         if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
     }
@@ -362,7 +420,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
             return hip_status(e);
     }
     // canonical offsets into one padded sample
-    st = launch_stretch(*p, p->d_lam, 1, 1, 1, 1, p->Hp * p->Wp, 0, p->Wp, 1, stream);
+    st = launch_stretch(*p, p->d_lam, 1, 1, 1, 1, p->Hp * p->Wp, 0, p->Wp, 1, 0, stream);
     if (st != SC_OK) return st;
     // the host staging buffers must outlive the async copies
     if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
@@ -605,6 +663,26 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_q = tq;
                 push(t);
               }
+            }
+        }
+    }
+    if (pw && p.dtype != SC_CB4_I8) {
+        for (int np_ : {1, 2}) for (int tq : {128, 192, 256, 384, 512}) for (int cc : {16, 32, 64, 128, 256}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                sc_tuning_t t{};
+                t.variant = SC_VARIANT_SLAB;
+                t.wsrc = 1;
+                t.pipeline = 1;
+                t.producers = np_;
+                t.wg_per_cu = 1;
+                t.wg_threads = 1024;
+                t.tile_p = 1;
+                t.tile_q = tq;
+                t.chunk_c = cc;
+                t.tile_d = td;
+                push(t);
             }
         }
     }

@@ -41,6 +41,10 @@ struct SlabGeom {
     int vec;                   // 1: slab rows can be staged with 16-byte loads
     int nwaves;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs;
+    // channel-chunked pipelined form (tuning.chunk_c > 0)
+    int CC, nchunks;           // channels per LDS buffer, buffers per tile
+    int DTW, ndt;              // output channels per workgroup, workgroup columns
+    int rpw;                   // output channels per consumer wave, ceil(DTW / consumers)
 };
 
 struct Plan {
@@ -57,6 +61,9 @@ struct Plan {
     void* d_theta = nullptr;        // [D*n] f32 | f16 | i8, or ceil(D*n/2) bytes of packed 4-bit indices
     int32_t* d_lam = nullptr;       // [D*n] canonical offsets (elements into one padded sample)
     int32_t* d_lam_slab = nullptr;  // [D*n] byte offsets into the LDS slab of the current tuning
+    int2* d_wlc = nullptr;          // chunked form of that table: segments (row, chunk), even-padded
+    int32_t* d_seg_off = nullptr;   // [D*nchunks + 1] start of every segment in d_wlc (entries)
+    int32_t* d_first_j = nullptr;   // [D*nchunks] index within its row of a segment's first entry
     int2* d_wl32 = nullptr;         // [D*np] {theta widened to 32 bits, slab byte offset} for scalar loads
     float* d_scales = nullptr;      // [D]
     int8_t* d_codebook = nullptr;   // [16]
@@ -83,5 +90,7 @@ sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 int slab_grid_size(const Plan& p, const SlabGeom& g, int N);
 sc_status_t expand_weights(const Plan& p, hipStream_t stream);
+sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream);
+constexpr int kMaxRowsPerWave = 8;
 
 }  // namespace sc

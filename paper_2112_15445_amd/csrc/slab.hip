@@ -484,6 +484,290 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Channel-chunked, pipelined form for pointwise layers (tuning.chunk_c > 0).
+//
+// A tile of TQ pixels is multiplied chunk by chunk: an LDS buffer holds CC input channels of the
+// tile, the producers stream chunk i+1 into the other buffer while the consumers work on chunk i,
+// and every consumer wave keeps the accumulators of its RPW output channels x VPT positions in
+// registers from the first chunk of a tile to the last.  Because a buffer only holds CC channels,
+// TQ can be 2..8 waves wide even when C*TQ would not fit LDS: every (theta, lambda) then feeds VPT
+// multiply-adds and one paired LDS read serves two of them, and the global loads become long
+// contiguous runs.  The weight table is stored as segments (output channel, chunk) -- the entries
+// of a row whose input channel lies in the chunk, contiguous because rows are sorted by column --
+// each padded to an even length; lambda is the byte offset inside the chunk buffer.
+// A workgroup handles DTW output channels (all of them unless tuning.tile_d says otherwise).
+// ------------------------------------------------------------------------------------------------
+template <sc_dtype_t DT>
+__global__ void __launch_bounds__(256)
+expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict__ lam,
+                      const int32_t* __restrict__ col, const int32_t* __restrict__ seg_off,
+                      const int32_t* __restrict__ first_j, int2* __restrict__ out, int D, int n,
+                      int RS, int CC, int nch)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)D * n) return;
+    const int d = (int)(i / n), j = (int)(i - (int64_t)d * n);
+    const int ch = ((col[i] & 0x7fffffff) / RS) / CC;
+    const int l = lam[i];
+    const int64_t dst = (int64_t)seg_off[(int64_t)d * nch + ch] + (j - first_j[(int64_t)d * nch + ch]);
+    out[dst] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
+}
+
+sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream)
+{
+    (void)total_entries;
+    const int64_t cnt = (int64_t)p.L.D * p.n;
+    if (cnt == 0) return SC_OK;
+    const unsigned blocks = (unsigned)((cnt + 255) / 256);
+#define SC_EXPANDC(DT)                                                                             \
+    hipLaunchKernelGGL(expand_chunked_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
+                       p.d_lam_slab, p.d_col, p.d_seg_off, p.d_first_j, p.d_wlc, p.L.D, p.n,       \
+                       p.L.R * p.L.S, g.CC, g.nchunks)
+    switch (p.dtype) {
+        case SC_F32: SC_EXPANDC(SC_F32); break;
+        case SC_F16: SC_EXPANDC(SC_F16); break;
+        case SC_I8: SC_EXPANDC(SC_I8); break;
+        default: return SC_ERR_UNSUPPORTED;
+    }
+#undef SC_EXPANDC
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+struct ChunkArgs {
+    int C, D, N, Wf, TQ, tiles, CC, nchunks, DTW, ndt, nprod, slab_bytes;
+    float inv_tiles, inv_TQ, inv_ndt;
+    int64_t x_sample_stride, y_plane;
+};
+
+template <sc_dtype_t DT, int VPT, int RPW>
+__global__ void
+slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                  const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const ChunkArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    typedef __attribute__((address_space(1))) const void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int EPV = 16 / (int)sizeof(X);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int nprod = a.nprod;
+    const int ncons = nwaves - nprod;
+    const int units = a.N * a.tiles * a.ndt;        // (sample, tile, output-channel block)
+    const int first = blockIdx.x, step = gridDim.x;
+    // unit u -> (sample b, tile, dt); consecutive units share the input tile
+    auto decode = [&](int u, int& b, int& q0, int& dt) {
+        const int bt = fdiv(u, a.inv_ndt);
+        dt = u - bt * a.ndt;
+        b = fdiv(bt, a.inv_tiles);
+        q0 = (bt - b * a.tiles) * a.TQ;
+    };
+
+    if (wave >= ncons) {
+        // ------------------------------------------------------------------ producer waves
+        __builtin_amdgcn_s_setprio(3);
+        const int pw = wave - ncons;
+        const int EW = 64 * EPV;
+        const int stepE = EW * nprod;
+        const int qstep = stepE / a.TQ, rstep = stepE - qstep * a.TQ;
+        auto issue = [&](int u, int ch, int buf) {
+            int b, q0, dt;
+            decode(u, b, q0, dt);
+            const int c0 = ch * a.CC;
+            const int E = min(a.CC, a.C - c0) * a.TQ;
+            unsigned char* dst = lds + buf * a.slab_bytes;
+            int idx = pw * EW + lane * EPV;
+            int c = fdiv(idx, a.inv_TQ);
+            int col = idx - c * a.TQ;
+            const X* src = x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)(c0 + c) * a.Wf + col;
+            for (int i = pw; i * EW < E; i += nprod) {
+                if (idx < E && q0 + col < a.Wf)
+                    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + i * 1024), 16, 0, 0);
+                idx += stepE;
+                col += rstep;
+                src += (int64_t)qstep * a.Wf + rstep;
+                if (col >= a.TQ) {
+                    col -= a.TQ;
+                    src += a.Wf - a.TQ;
+                }
+            }
+        };
+        if (first < units) issue(first, 0, 0);
+        int it = 0;
+        for (int u = first; u < units; u += step) {
+            for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // item (u, ch) has landed
+                __syncthreads();                                   // A
+                int un = u, chn = ch + 1;
+                if (chn == a.nchunks) { chn = 0; un = u + step; }
+                if (un < units) issue(un, chn, (it + 1) & 1);
+                __syncthreads();                                   // B
+            }
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumer waves
+    A acc[RPW][VPT];
+    int out_off[VPT];
+    int it = 0;
+    for (int u = first; u < units; u += step) {
+        int b, q0, dt;
+        decode(u, b, q0, dt);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int f = k * 64 + lane;
+            out_off[k] = (f < a.TQ && q0 + f < a.Wf) ? q0 + f : -1;
+        }
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+        const int d0 = dt * a.DTW;
+        const int dend = min(a.D, d0 + a.DTW);
+        for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
+            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+            // segment bounds of this wave's rows for this chunk: independent scalar loads issued
+            // together (before the barrier), so their latency is paid once per item
+            int s0[RPW], ln[RPW];
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const int d = d0 + wave + r * ncons;
+                const int64_t si = (int64_t)min(d, dend - 1) * a.nchunks + ch;
+                s0[r] = seg_off[si];
+                ln[r] = d < dend ? seg_off[si + 1] - s0[r] : 0;     // even
+            }
+            // first group of the first segment; every later segment's first group is fetched
+            // while the segment before it is being multiplied
+            int gc[16];
+            load_group<1>(gc, wlc, __amdgpu_buffer_rsrc_t(), s0[0]);
+            __syncthreads();  // A
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const int len = ln[r];
+                const int2* seg = wlc + s0[r];
+                const int ngroups = (len + 7) >> 3;
+                int ga[16], gb[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ga[i] = gc[i];
+                if (r + 1 < RPW) load_group<1>(gc, wlc, __amdgpu_buffer_rsrc_t(), s0[r + 1 < RPW ? r + 1 : r]);
+                auto mac = [&](int wbits, int lam) {
+                    const WL w = weight_from_bits<DT>(wbits);
+                    const unsigned char* pj = lane_base + lam;
+#pragma unroll
+                    for (int k = 0; k < VPT; ++k)
+                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                };
+                // a partial last group reads past the segment (the table has 16 spare entries)
+                // and uses only len - 8*gi entries
+                auto process = [&](const int (&g)[16], int gi) {
+                    const int cnt = len - (gi << 3);
+                    if (cnt >= 8) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) mac(g[2 * i], g[2 * i + 1]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; i += 2)
+                            if (i < cnt) {
+                                mac(g[2 * i], g[2 * i + 1]);
+                                mac(g[2 * i + 2], g[2 * i + 3]);
+                            }
+                    }
+                };
+                int gi = 0;
+                while (gi < ngroups) {
+                    if (gi + 1 < ngroups) load_group<1>(gb, seg, __amdgpu_buffer_rsrc_t(), (gi + 1) * 8);
+                    process(ga, gi);
+                    if (++gi >= ngroups) break;
+                    if (gi + 1 < ngroups) load_group<1>(ga, seg, __amdgpu_buffer_rsrc_t(), (gi + 1) * 8);
+                    process(gb, gi);
+                    ++gi;
+                }
+            }
+            __syncthreads();  // B
+        }
+        Y* yb = y + (int64_t)b * a.D * a.y_plane;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int d = d0 + wave + r * ncons;
+            if (d < dend) {
+                Y* yd = yb + (int64_t)d * a.y_plane;
+#pragma unroll
+                for (int k = 0; k < VPT; ++k)
+                    if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[r][k]);
+            }
+        }
+    }
+}
+
+template <sc_dtype_t DT, int VPT, int RPW>
+static sc_status_t launch_chunk_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_chunk_kernel<DT, VPT, RPW>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    const int units = a.N * a.tiles * a.ndt;
+    const int grid = std::min(units, kNumCU * std::max(1, kMaxLdsBytes / p.geom.lds_bytes));
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_wlc, p.d_seg_off, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int VPT>
+static sc_status_t launch_chunk_rpw(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    switch (p.geom.rpw) {
+        case 1: return launch_chunk_one<DT, VPT, 1>(p, a, x, y, stream);
+        case 2: return launch_chunk_one<DT, VPT, 2>(p, a, x, y, stream);
+        case 3: return launch_chunk_one<DT, VPT, 3>(p, a, x, y, stream);
+        case 4: return launch_chunk_one<DT, VPT, 4>(p, a, x, y, stream);
+        case 5: return launch_chunk_one<DT, VPT, 5>(p, a, x, y, stream);
+        case 6: return launch_chunk_one<DT, VPT, 6>(p, a, x, y, stream);
+        case 7: return launch_chunk_one<DT, VPT, 7>(p, a, x, y, stream);
+        case 8: return launch_chunk_one<DT, VPT, 8>(p, a, x, y, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_chunk(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
+{
+    const SlabGeom& g = p.geom;
+    ChunkArgs a{};
+    a.C = p.L.C; a.D = p.L.D; a.N = N; a.Wf = g.Wf; a.TQ = g.TQ; a.tiles = g.tiles_q;
+    a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt; a.nprod = p.tuning.producers;
+    a.slab_bytes = g.slab_bytes;
+    a.inv_tiles = 1.0f / (float)g.tiles_q; a.inv_TQ = 1.0f / (float)g.TQ; a.inv_ndt = 1.0f / (float)g.ndt;
+    a.x_sample_stride = (int64_t)p.L.C * g.Wf;
+    a.y_plane = (int64_t)g.Qf;
+    if ((int64_t)N * g.tiles_q * g.ndt >= (1 << 19)) return SC_ERR_UNSUPPORTED;
+    switch (g.vpt) {
+        case 1: return launch_chunk_rpw<DT, 1>(p, a, x, y, stream);
+        case 2: return launch_chunk_rpw<DT, 2>(p, a, x, y, stream);
+        case 3: return launch_chunk_rpw<DT, 3>(p, a, x, y, stream);
+        case 4: return launch_chunk_rpw<DT, 4>(p, a, x, y, stream);
+        case 5: return launch_chunk_rpw<DT, 5>(p, a, x, y, stream);
+        case 6: return launch_chunk_rpw<DT, 6>(p, a, x, y, stream);
+        case 7: return launch_chunk_rpw<DT, 7>(p, a, x, y, stream);
+        case 8: return launch_chunk_rpw<DT, 8>(p, a, x, y, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
 int slab_grid_size(const Plan& p, const SlabGeom& g, int N)
 {
     (void)p;
@@ -613,6 +897,16 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
 {
     const SlabGeom& g = p.geom;
+    if (p.tuning.chunk_c > 0) {
+        // 16-byte direct-to-LDS copies: the caller's pointer must be 16-byte aligned as well
+        if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return SC_ERR_UNSUPPORTED;
+        switch (p.dtype) {
+            case SC_F32: return launch_chunk<SC_F32>(p, x, y, N, stream);
+            case SC_F16: return launch_chunk<SC_F16>(p, x, y, N, stream);
+            case SC_I8: return launch_chunk<SC_I8>(p, x, y, N, stream);
+            default: return SC_ERR_UNSUPPORTED;
+        }
+    }
     const int64_t grid64 = (int64_t)N * g.tiles_p * g.tiles_q;
     if (grid64 >= (1 << 19)) return SC_ERR_UNSUPPORTED;  // fdiv() range for the tile decode
     SlabArgs a{};

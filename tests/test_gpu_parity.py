@@ -20,6 +20,10 @@ def _both_variants(plan):
                            (B.SC_VARIANT_SLAB, {"wsrc": 1}), (B.SC_VARIANT_SLAB, {"wsrc": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 3}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 3, "pipeline": 1, "wg_threads": 512}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "chunk_c": 5,
+                                                "tile_q": 128}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 256, "chunk_c": 8,
+                                                "tile_d": 4, "tile_q": 64, "producers": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "producers": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 512, "producers": 4})):
         try:
@@ -152,6 +156,30 @@ def test_wavefront_split_reduction(dtype):
             t = plan.get_tuning()
             assert (t.split_n, t.sub_batch) == (ns, sb)
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"split_n={ns} sub_batch={sb}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_channel_chunked_pipeline(dtype):
+    """Pointwise layer through the channel-chunked persistent kernel: chunk sizes that do and do not
+    divide C, output-channel blocks, many tiles per workgroup, ragged rows."""
+    l = wl.Layer("chunked", 40, 24, 12, 12, 1, 1, 1, 1, 0, 0, N=50, sparsity=0.6, dtype=dtype, seed=5)
+    data = wl.prepare(l, ragged=True)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    ran = 0
+    for thr, tq, cc, td, npd in ((512, 64, 8, 0, 2), (1024, 128, 16, 16, 2), (1024, 144, 33, 0, 1),
+                                 (512, 144, 7, 10, 4), (256, 64, 40, 0, 1)):
+        try:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pipeline=1, wg_threads=thr,
+                            tile_q=tq, chunk_c=cc, tile_d=td, producers=npd)
+        except B.SparseConvError as e:
+            assert e.status == 4
+            continue
+        t = plan.get_tuning()
+        assert t.chunk_c == min(cc, 40) and t.pipeline == 1
+        G.check(l, G.run_gpu(plan, data["x"]), ref, str(t.as_dict()))
+        ran += 1
+    assert ran >= 3
 
 
 def test_ell_entry_point_and_unsorted_duplicate_columns():
