@@ -100,9 +100,13 @@ typedef struct {
                            entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64 */
     int32_t pipeline;   /* SLAB, pointwise layers: 1 = persistent workgroups that stream tile i+1 into a
                            second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
-                           tile i is multiplied; needs wsrc != 0.  0 = one tile per workgroup */
+                           tile i is multiplied; needs wsrc != 0.  2 = the same double buffering with
+                           no dedicated waves: every wave issues its share of the copy of tile i+1 and
+                           then multiplies its rows of tile i (contiguous row ranges, one barrier per
+                           tile); needs wsrc = 1 and at least one stored weight per row; with chunk_c > 0 at
+                           most 4 positions per lane and 8 rows per wave.  0 = one tile per workgroup */
     int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
-    int32_t chunk_c;    /* SLAB with pipeline = 1: input channels per LDS buffer (0 = all of them).  With
+    int32_t chunk_c;    /* SLAB with pipeline = 1 or 2: input channels per LDS buffer (0 = all of them).  With
                            chunk_c < C a tile is multiplied chunk by chunk, each wave keeping the
                            accumulators of its output channels in registers across the chunks, so
                            wide tiles fit LDS even for layers with many input channels */

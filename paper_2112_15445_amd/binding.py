@@ -77,6 +77,10 @@ def lib() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # PyTorch bundles its own HIP runtime.  Import it before the library so that both bind to the one
+    # runtime already in the process; loaded the other way round the process ends up with two runtimes
+    # and the second to initialise reports that it sees no GPU.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     P = ctypes.POINTER

@@ -101,9 +101,10 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (chunk_c > 0) {
         // chunked form: pointwise layers, pipelined, weights by scalar loads; every consumer wave
         // keeps the accumulators of its rows in registers across the chunks of a tile
-        if (!pw || pipeline != 1 || wsrc != 1 || p.dtype == SC_CB4_I8) return false;
-        const int ncons = o.nwaves - producers;
+        if (!pw || pipeline < 1 || wsrc != 1 || p.dtype == SC_CB4_I8) return false;
+        const int ncons = o.nwaves - (pipeline == 1 ? producers : 0);
         if (ncons < 1) return false;
+        if (pipeline == 2 && o.vpt > 4) return false;
         o.rpw = (o.DTW + ncons - 1) / ncons;
         if (o.rpw > kMaxRowsPerWave) return false;
     }
@@ -135,11 +136,16 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (!pw || wsrc == 0 || o.nwaves < 8) return false;
         o.lds_bytes = 2 * o.slab_bytes;
     }
+    if (pipeline == 2) {
+        // symmetric form: two tile buffers, scalar-load weights, at least one stored entry per row
+        if (!pw || wsrc != 1 || p.n == 0) return false;
+        o.lds_bytes = 2 * o.slab_bytes;
+    }
     if (o.lds_bytes > lds_budget || o.lds_bytes > kMaxLdsBytes) return false;
     // 16-byte staging needs every tile row start and the plane pitch to be 16-byte aligned
     const int epv = 16 / p.ex;
     o.vec = (pw && (o.Wf % epv == 0) && (o.TQ % epv == 0)) ? 1 : 0;
-    if (pipeline == 1 && !o.vec) return false;
+    if (pipeline >= 1 && !o.vec) return false;
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -156,16 +162,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
     if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
     if (t.wsrc != 0 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
-    if (t.pipeline < 0 || t.pipeline > 1) return SC_ERR_UNSUPPORTED;
+    if (t.pipeline < 0 || t.pipeline > 2) return SC_ERR_UNSUPPORTED;
     if (t.pipeline == 1 && t.producers == 0) t.producers = 2;
-    if (t.pipeline == 0) t.producers = 0;
+    if (t.pipeline != 1) t.producers = 0;
     if (t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.tile_d = 0;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
         const bool pw = is_pointwise(L);
-        if (t.wg_per_cu == 0) t.wg_per_cu = t.pipeline == 1 ? 1 : 2;
+        if (t.wg_per_cu == 0) t.wg_per_cu = t.pipeline >= 1 ? 1 : 2;
         if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
         const int budget = kMaxLdsBytes / t.wg_per_cu;
         SlabGeom g{};
@@ -194,7 +200,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.tile_q = g.TQ;
             t.sub_batch = 0;
             t.split_n = 0;
-            if (t.pipeline == 1) t.wg_per_cu = 1;
+            if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
             *out = t;
             *geom = g;
@@ -329,8 +335,10 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
         if (t.chunk_c > 0) {
             // segment table of the chunked form: for every (row, chunk) the entries whose input
             // channel lies in the chunk, contiguous because rows are sorted by column; segments
-            // are padded to an even length.  Counted on the host, filled by a device pass.
+            // are padded with zero weights to an even length (to whole 8-entry groups for the
+            // symmetric kernel).  Counted on the host, filled by a device pass.
             const int D = p->L.D, nch = g.nchunks, RS = p->L.R * p->L.S;
+            const int pad = t.pipeline == 2 ? 8 : 2;     // the symmetric kernel reads whole 8-entry groups
             std::vector<int32_t> seg_off((size_t)D * nch + 1, 0), first_j((size_t)D * nch, 0);
             int64_t total = 0;
             for (int d = 0; d < D; ++d) {
@@ -340,7 +348,7 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
                     first_j[(size_t)d * nch + ch] = j;
                     int cnt = 0;
                     while (j < p->n && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt; }
-                    total += (cnt + 1) / 2 * 2;
+                    total += (cnt + pad - 1) / pad * pad;
                 }
             }
             seg_off[(size_t)D * nch] = (int32_t)total;
@@ -403,7 +411,13 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
         if ((e = hipMalloc((void**)&p->d_lam, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc((void**)&p->d_lam_slab, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc(&p->d_theta, theta_bytes)) != hipSuccess) return hip_status(e);
-        if (p->dtype != SC_CB4_I8 && (e = hipMalloc((void**)&p->d_wl32, (size_t)p->L.D * p->np * 8)) != hipSuccess) return hip_status(e);
+        if (p->dtype != SC_CB4_I8) {
+            // expanded {theta32, lambda} table plus 8 zeroed entries of slack: the symmetric kernel
+            // reads whole 8-entry groups and the last one of a row may reach past the row
+            const size_t wl_bytes = ((size_t)p->L.D * p->np + 8) * 8;
+            if ((e = hipMalloc((void**)&p->d_wl32, wl_bytes)) != hipSuccess) return hip_status(e);
+            if ((e = hipMemsetAsync(p->d_wl32, 0, wl_bytes, stream)) != hipSuccess) return hip_status(e);
+        }
         if ((e = hipMemcpyAsync(p->d_col, p->h_col.data(), cnt * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return hip_status(e);
         if ((e = hipMemcpyAsync(p->d_theta, theta_src, theta_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess)
@@ -663,6 +677,40 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_q = tq;
                 push(t);
               }
+            }
+        }
+    }
+    if (pw && p.dtype != SC_CB4_I8) {
+        for (int threads : {512, 768, 1024}) {
+            for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
+                sc_tuning_t t{};
+                t.variant = SC_VARIANT_SLAB;
+                t.wsrc = 1;
+                t.pipeline = 2;
+                t.wg_per_cu = 1;
+                t.wg_threads = threads;
+                t.tile_p = 1;
+                t.tile_q = tq;
+                push(t);
+            }
+        }
+    }
+    if (pw && p.dtype != SC_CB4_I8) {
+        for (int tq : {128, 256}) for (int cc : {32, 64, 128, 256}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                sc_tuning_t t{};
+                t.variant = SC_VARIANT_SLAB;
+                t.wsrc = 1;
+                t.pipeline = 2;
+                t.wg_per_cu = 1;
+                t.wg_threads = 1024;
+                t.tile_p = 1;
+                t.tile_q = tq;
+                t.chunk_c = cc;
+                t.tile_d = td;
+                push(t);
             }
         }
     }

@@ -384,6 +384,107 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 }
 
 // ------------------------------------------------------------------------------------------------
+// Producer-side tile copy, global -> LDS, with the direct-to-LDS loads of gfx950 (16 bytes per lane,
+// 1 KB per instruction, no VGPR staging).  Copies nch channel rows of TQ elements (global row pitch
+// Wf elements, tb = address of channel 0 / column q0 of the tile, wave-uniform) to the flat
+// [channel][TQ] image at dst; the instructions are dealt round-robin to the nprod producer waves.
+// When one instruction covers whole channel rows (or a row is a whole number of instructions), a
+// lane's byte offset from the instruction's base address never changes, so the base is advanced
+// with scalar arithmetic and the loop body holds no vector ALU work at all; other tile widths take
+// the generic incremental path.  Lanes whose pixels lie past the end of the plane load nothing.
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One copy instruction: 16 bytes per lane from base + lane_off (base wave-uniform) to the LDS
+// image at dst + 16 * lane.  HAND = true issues it as inline assembly, which keeps it out of the
+// compiler's bookkeeping: a wave that both copies tile i+1 and reads tile i would otherwise be
+// made to wait for the copy before its first LDS read.  The caller then waits on vmcnt itself.
+template <bool HAND>
+__device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, unsigned char* dst)
+{
+    if constexpr (HAND) {
+        const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(lane_off), "s"(base), "s"(l) : "memory");
+    } else {
+        __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 0);
+    }
+}
+template <bool HAND>
+__device__ __forceinline__ void dma16_ptr(const void* src, unsigned char* dst)
+{
+    if constexpr (HAND) {
+        const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     : : "v"(src), "s"(l) : "memory");
+    } else {
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+    }
+}
+
+template <typename X, bool HAND = false>
+__device__ __forceinline__ void
+dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int pw, int nprod, int lane,
+         float inv_TQ)
+{
+    constexpr int EPV = 16 / (int)sizeof(X);
+    constexpr int EW = 64 * EPV;                          // elements per copy instruction
+    const int e = lane * EPV;
+    if ((TQ & (TQ - 1)) == 0 && TQ <= EW) {
+        // one instruction = cpi whole channel rows
+        const int sh = __builtin_ctz(TQ);
+        const int cpi = EW >> sh;
+        const int c_sub = e >> sh;
+        const int col = e - (c_sub << sh);
+        const uint32_t lane_off = (uint32_t)(c_sub * Wf + col) * (uint32_t)sizeof(X);
+        const int nfull = nch >> __builtin_ctz(cpi);
+        const int64_t gstride = (int64_t)cpi * Wf * (int64_t)sizeof(X);
+        const char* base = reinterpret_cast<const char*>(tb);
+        if (q0 + col < Wf) {
+            int g = pw;
+            for (; g < nfull; g += nprod) dma16<HAND>(base + g * gstride, lane_off, dst + g * 1024);
+            // a last, partial group of channel rows falls to the wave whose turn it is
+            if (g == nfull && c_sub < nch - nfull * cpi)
+                dma16<HAND>(base + nfull * gstride, lane_off, dst + nfull * 1024);
+        }
+        return;
+    }
+    if (TQ % EW == 0) {
+        // one channel row = ipc whole instructions
+        const int ipc = TQ / EW;
+        const int64_t cstride = (int64_t)Wf * (int64_t)sizeof(X);
+        for (int seg = 0; seg < ipc; ++seg) {
+            if (q0 + seg * EW + e < Wf) {
+                const char* base = reinterpret_cast<const char*>(tb + seg * EW);
+                for (int c = pw; c < nch; c += nprod)
+                    dma16<HAND>(base + c * cstride, (uint32_t)(e * (int)sizeof(X)), dst + (c * ipc + seg) * 1024);
+            }
+        }
+        return;
+    }
+    // generic: the (channel, column) of a lane's 16 bytes advances by a fixed step from one
+    // instruction to the next, so the division is done once and the rest is increments
+    const int E = nch * TQ;
+    const int stepE = EW * nprod;
+    const int qstep = stepE / TQ, rstep = stepE - qstep * TQ;
+    int idx = pw * EW + e;
+    int c = fdiv(idx, inv_TQ);
+    int col = idx - c * TQ;
+    const X* src = tb + (int64_t)c * Wf + col;
+    for (int i = pw; i * EW < E; i += nprod) {
+        if (idx < E && q0 + col < Wf) dma16_ptr<HAND>(src, dst + i * 1024);
+        idx += stepE;
+        col += rstep;
+        src += (int64_t)qstep * Wf + rstep;
+        if (col >= TQ) {
+            col -= TQ;
+            src += Wf - TQ;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Persistent, double-buffered form of the slab kernel for pointwise layers (tuning.pipeline = 1).
 //
 // One workgroup per CU walks over (sample, tile) pairs.  Its last tuning.producers waves are producers: they
@@ -404,8 +505,6 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    typedef __attribute__((address_space(1))) const void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int EPV = 16 / (int)sizeof(X);
 
@@ -417,40 +516,20 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     const int ncons = nwaves - nprod;
     const int tiles = a.tiles_q;
     const int total = a.N * tiles;
-    const int E = a.C * a.TQ;                  // elements of one tile (chan_pitch == TQ here)
     const float inv_TQ = a.inv_Qs;
     const int first = blockIdx.x, step = gridDim.x;
 
     if (wave >= ncons) {
         // ------------------------------------------------------------------ producer waves
         const int pw = wave - ncons;
-        // Producers run at raised wave priority so that their short address arithmetic is not
-        // queued behind the consumers' long instruction streams.  The (channel, column) of a lane's
-        // 16 bytes advances by a fixed step from one copy instruction to the next, so the division
-        // is done once per tile and the rest is increments.
+        // Producers run at raised wave priority so that their short instruction streams are not
+        // queued behind the consumers' long ones.
         __builtin_amdgcn_s_setprio(3);
-        const int EW = 64 * EPV;                          // elements per copy instruction
-        const int stepE = EW * nprod;
-        const int qstep = stepE / a.TQ, rstep = stepE - qstep * a.TQ;
         auto issue = [&](int t, int buf) {
             const int b = fdiv(t, a.inv_tiles);
             const int q0 = (t - b * tiles) * a.TQ;
-            unsigned char* dst = lds + buf * a.slab_bytes;
-            int idx = pw * EW + lane * EPV;
-            int c = fdiv(idx, inv_TQ);
-            int col = idx - c * a.TQ;
-            const X* src = x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c * a.Wf + col;
-            for (int i = pw; i * EW < E; i += nprod) {
-                if (idx < E && q0 + col < a.Wf)
-                    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + i * 1024), 16, 0, 0);
-                idx += stepE;
-                col += rstep;
-                src += (int64_t)qstep * a.Wf + rstep;
-                if (col >= a.TQ) {
-                    col -= a.TQ;
-                    src += a.Wf - a.TQ;
-                }
-            }
+            dma_tile<X>(x + (int64_t)b * a.x_sample_stride + q0, lds + buf * a.slab_bytes, a.C, a.TQ,
+                        a.Wf, q0, pw, nprod, lane, inv_TQ);
         };
         if (first < total) issue(first, 0);
         int it = 0;
@@ -481,6 +560,114 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         __syncthreads();  // A
         stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.n, a.np, a.y_plane);
         __syncthreads();  // B
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Symmetric persistent form for pointwise layers (tuning.pipeline = 2): every wave of the
+// workgroup both copies and multiplies.
+//
+// Right after the barrier that opens tile i each wave issues its share of the direct-to-LDS copy of
+// tile i+1 into the other buffer, then multiplies its rows of tile i.  The D rows are dealt to the
+// waves as contiguous ranges, so with D a multiple of the wave count every wave has the same work
+// and no wave is set aside for copying; one barrier per tile both publishes tile i+1 and frees the
+// buffer of tile i-1.  The copies are hand-issued (dma16<true>), so the wave waits on vmcnt itself:
+// once per tile, just before the store of its last row -- by then its share of tile i+1 (issued a
+// whole tile earlier) and its earlier stores have long completed, and the last store stays in
+// flight across the barrier.
+//
+// Rows are packed with an even pitch np and fetched 8 entries at a time by scalar loads through
+// the constant address space.
+// ------------------------------------------------------------------------------------------------
+template <sc_dtype_t DT, int VPT>
+__global__ void
+slab_sym_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                const int2* __restrict__ wl32, const SlabArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    typedef const int16v __attribute__((address_space(4)))* c16_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int tiles = a.tiles_q;
+    const int total = a.N * tiles;
+    const int first = blockIdx.x, step = gridDim.x;
+    if (first >= total) return;
+
+    // contiguous row range of this wave
+    const int base_rows = a.D / nwaves, extra = a.D - base_rows * nwaves;
+    const int row0 = wave * base_rows + min(wave, extra);
+    const int nrows = base_rows + (wave < extra ? 1 : 0);
+    const int ng = a.np >> 3, tp = (a.np & 7) >> 1;              // full 8-entry groups and tail pairs per row
+
+    auto issue = [&](int t, int buf) {
+        const int b = fdiv(t, a.inv_tiles);
+        const int q0 = (t - b * tiles) * a.TQ;
+        dma_tile<X, true>(x + (int64_t)b * a.x_sample_stride + q0, lds + buf * a.slab_bytes, a.C, a.TQ,
+                          a.Wf, q0, wave, nwaves, lane, a.inv_Qs);
+    };
+    issue(first, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int it = 0;
+    for (int t = first; t < total; t += step, ++it) {
+        __syncthreads();      // tile t is complete in buffer it&1; the other buffer is free
+        if (t + step < total) issue(t + step, (it + 1) & 1);
+        if (nrows == 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            continue;
+        }
+        const int b = fdiv(t, a.inv_tiles);
+        const int q0 = (t - b * tiles) * a.TQ;
+        int out_off[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int f = k * 64 + lane;
+            out_off[k] = (f < a.TQ && q0 + f < a.Qf) ? q0 + f : -1;
+        }
+        Y* yd = y + ((int64_t)b * a.D + row0) * a.y_plane;
+        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+        for (int r = 0; r < nrows; ++r) {
+            A acc[VPT];
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc[k] = A(0);
+            const int2* prow = wl32 + (int64_t)(row0 + r) * a.np;
+            auto mac = [&](int wbits, int lam) {
+                const WL w = weight_from_bits<DT>(wbits);
+                const unsigned char* pj = lane_base + lam;
+#pragma unroll
+                for (int k = 0; k < VPT; ++k)
+                    acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+            };
+            for (int g = 0; g < ng; ++g) {
+                // no software prefetch on purpose: with nothing else pending on the scalar/LDS
+                // counter the eight gathers can be waited for one by one, so the multiply-adds
+                // start when the first value arrives; the other waves hide the scalar load
+                const int16v c = *(c16_t)(prow + 8 * g);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
+            }
+            if (tp > 0) {
+                // the last 1..3 pairs of the row: one more 8-entry load (it reaches into the next
+                // row, or into the slack behind the table), of which only the row's pairs are used
+                const int16v c = *(c16_t)(prow + 8 * ng);
+                mac(c[0], c[1]); mac(c[2], c[3]);
+                if (tp > 1) { mac(c[4], c[5]); mac(c[6], c[7]); }
+                if (tp > 2) { mac(c[8], c[9]); mac(c[10], c[11]); }
+            }
+            // before the store of the wave's last row: this wave's share of the next tile and its
+            // earlier stores are complete
+            if (r == nrows - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int k = 0; k < VPT; ++k)
+                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+            yd += a.y_plane;
+        }
     }
 }
 
@@ -549,8 +736,6 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     using Y = typename Types<DT>::Y;
     using A = typename Types<DT>::A;
     using WL = typename Types<DT>::WL;
-    typedef __attribute__((address_space(1))) const void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int EPV = 16 / (int)sizeof(X);
 
@@ -574,30 +759,13 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         // ------------------------------------------------------------------ producer waves
         __builtin_amdgcn_s_setprio(3);
         const int pw = wave - ncons;
-        const int EW = 64 * EPV;
-        const int stepE = EW * nprod;
-        const int qstep = stepE / a.TQ, rstep = stepE - qstep * a.TQ;
         auto issue = [&](int u, int ch, int buf) {
             int b, q0, dt;
             decode(u, b, q0, dt);
             const int c0 = ch * a.CC;
-            const int E = min(a.CC, a.C - c0) * a.TQ;
-            unsigned char* dst = lds + buf * a.slab_bytes;
-            int idx = pw * EW + lane * EPV;
-            int c = fdiv(idx, a.inv_TQ);
-            int col = idx - c * a.TQ;
-            const X* src = x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)(c0 + c) * a.Wf + col;
-            for (int i = pw; i * EW < E; i += nprod) {
-                if (idx < E && q0 + col < a.Wf)
-                    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + i * 1024), 16, 0, 0);
-                idx += stepE;
-                col += rstep;
-                src += (int64_t)qstep * a.Wf + rstep;
-                if (col >= a.TQ) {
-                    col -= a.TQ;
-                    src += a.Wf - a.TQ;
-                }
-            }
+            dma_tile<X>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
+                        lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, pw, nprod, lane,
+                        a.inv_TQ);
         };
         if (first < units) issue(first, 0, 0);
         int it = 0;
@@ -707,6 +875,135 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Symmetric persistent form with channel chunks (tuning.pipeline = 2, tuning.chunk_c > 0).
+//
+// As slab_sym_kernel, but an LDS buffer holds only CC input channels of a tile of TQ pixels, so
+// tiles 2..4 waves wide fit twice into LDS even for layers with many input channels; one LDS
+// instruction then serves two positions of a lane (they are 64 elements apart, which the paired
+// read covers) and every scalar-loaded entry feeds VPT multiply-adds.  A workgroup walks over
+// (tile, chunk) items; each wave keeps the accumulators of its rows (at most kMaxRowsPerWave) in
+// registers from the first chunk of a tile to the last and stores after the last.  The weight
+// table holds one segment per (row, chunk), padded with zero weights to whole 8-entry groups.
+// ------------------------------------------------------------------------------------------------
+template <sc_dtype_t DT, int VPT>
+__global__ void
+slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                 const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const ChunkArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    typedef const int16v __attribute__((address_space(4)))* c16_t;
+    typedef const int32_t __attribute__((address_space(4)))* ci_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int RPW = kMaxRowsPerWave;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int units = a.N * a.tiles * a.ndt;        // (sample, tile, output-channel block)
+    const int first = blockIdx.x, step = gridDim.x;
+    if (first >= units) return;
+    auto decode = [&](int u, int& b, int& q0, int& dt) {
+        const int bt = fdiv(u, a.inv_ndt);
+        dt = u - bt * a.ndt;
+        b = fdiv(bt, a.inv_tiles);
+        q0 = (bt - b * a.tiles) * a.TQ;
+    };
+    auto issue = [&](int u, int ch, int buf) {
+        int b, q0, dt;
+        decode(u, b, q0, dt);
+        const int c0 = ch * a.CC;
+        dma_tile<X, true>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
+                          lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, wave, nwaves,
+                          lane, a.inv_TQ);
+    };
+    const ci_t segs = (ci_t)seg_off;
+    const c16_t wl = (c16_t)wlc;
+
+    issue(first, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int it = 0;
+    for (int u = first; u < units; u += step) {
+        int b, q0, dt;
+        decode(u, b, q0, dt);
+        // contiguous row range of this wave inside the output-channel block
+        const int d0 = dt * a.DTW, dcnt = min(a.DTW, a.D - d0);
+        const int base_rows = dcnt / nwaves, extra = dcnt - base_rows * nwaves;
+        const int row0 = d0 + wave * base_rows + min(wave, extra);
+        const int nrows = base_rows + (wave < extra ? 1 : 0);
+        A acc[RPW][VPT];
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+        for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
+            __syncthreads();      // item (u, ch) is complete in buffer it&1; the other buffer is free
+            {
+                int un = u, chn = ch + 1;
+                if (chn == a.nchunks) { chn = 0; un = u + step; }
+                if (un < units) issue(un, chn, (it + 1) & 1);
+            }
+            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                if (r < nrows) {
+                    const int si = (row0 + r) * a.nchunks + ch;
+                    const int s0 = segs[si], s1 = segs[si + 1];       // multiples of 8 entries
+                    for (int e = s0; e < s1; e += 8) {
+                        const int16v c = wl[e >> 3];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const WL w = weight_from_bits<DT>(c[2 * i]);
+                            const unsigned char* pj = lane_base + c[2 * i + 1];
+#pragma unroll
+                            for (int k = 0; k < VPT; ++k)
+                                acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                        }
+                    }
+                }
+            }
+            // this wave's share of the next item (and, after a tile's last chunk, nothing younger
+            // than stores issued a whole item ago) must be complete before the next barrier
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        Y* yd = y + ((int64_t)b * a.D + row0) * a.y_plane;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            if (r < nrows) {
+#pragma unroll
+                for (int k = 0; k < VPT; ++k) {
+                    const int f = k * 64 + lane;
+                    if (f < a.TQ && q0 + f < a.Wf) yd[(int64_t)r * a.y_plane + q0 + f] = narrow<DT>(acc[r][k]);
+                }
+            }
+        }
+    }
+}
+
+template <sc_dtype_t DT, int VPT>
+static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_symc_kernel<DT, VPT>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    const int units = a.N * a.tiles * a.ndt;
+    const int grid = std::min(units, kNumCU * std::max(1, kMaxLdsBytes / p.geom.lds_bytes));
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_wlc, p.d_seg_off, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
 template <sc_dtype_t DT, int VPT, int RPW>
 static sc_status_t launch_chunk_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
 {
@@ -755,6 +1052,15 @@ static sc_status_t launch_chunk(const Plan& p, const void* x, void* y, int N, hi
     a.x_sample_stride = (int64_t)p.L.C * g.Wf;
     a.y_plane = (int64_t)g.Qf;
     if ((int64_t)N * g.tiles_q * g.ndt >= (1 << 19)) return SC_ERR_UNSUPPORTED;
+    if (p.tuning.pipeline == 2) {
+        switch (g.vpt) {
+            case 1: return launch_symc_one<DT, 1>(p, a, x, y, stream);
+            case 2: return launch_symc_one<DT, 2>(p, a, x, y, stream);
+            case 3: return launch_symc_one<DT, 3>(p, a, x, y, stream);
+            case 4: return launch_symc_one<DT, 4>(p, a, x, y, stream);
+        }
+        return SC_ERR_UNSUPPORTED;
+    }
     switch (g.vpt) {
         case 1: return launch_chunk_rpw<DT, 1>(p, a, x, y, stream);
         case 2: return launch_chunk_rpw<DT, 2>(p, a, x, y, stream);
@@ -875,11 +1181,51 @@ static sc_status_t launch_async(const Plan& p, const SlabArgs& a, const void* x,
                               : launch_async_w<DT, 1>(p, a, x, y, stream);
 }
 
+template <sc_dtype_t DT, int VPT>
+static sc_status_t launch_sym_one(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_sym_kernel<DT, VPT>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    const int total = a.N * a.tiles_q;
+    const int grid = std::min(total, kNumCU * std::max(1, kMaxLdsBytes / p.geom.lds_bytes));
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_wl32, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_sym(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
+{
+    switch (p.geom.vpt) {
+        case 1: return launch_sym_one<DT, 1>(p, a, x, y, stream);
+        case 2: return launch_sym_one<DT, 2>(p, a, x, y, stream);
+        case 3: return launch_sym_one<DT, 3>(p, a, x, y, stream);
+        case 4: return launch_sym_one<DT, 4>(p, a, x, y, stream);
+        case 5: return launch_sym_one<DT, 5>(p, a, x, y, stream);
+        case 6: return launch_sym_one<DT, 6>(p, a, x, y, stream);
+        case 7: return launch_sym_one<DT, 7>(p, a, x, y, stream);
+        case 8: return launch_sym_one<DT, 8>(p, a, x, y, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
 template <sc_dtype_t DT>
 static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                              hipStream_t stream)
 {
     if constexpr (DT != SC_CB4_I8) {
+        if (p.tuning.pipeline == 2) {
+            // as for pipeline 1: an unaligned x takes the one-shot kernel
+            if (a.vec) return launch_sym<DT>(p, a, x, y, stream);
+        }
         if (p.tuning.pipeline == 1) {
             // the direct-to-LDS copy needs 16-byte aligned rows: checked at tuning time for the
             // layer, here for the caller's pointer (an unaligned x takes the one-shot kernel)

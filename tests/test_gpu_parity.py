@@ -25,7 +25,10 @@ def _both_variants(plan):
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 256, "chunk_c": 8,
                                                 "tile_d": 4, "tile_q": 64, "producers": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "producers": 1}),
-                           (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 512, "producers": 4})):
+                           (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 512, "producers": 4}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
         try:
             plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
         except B.SparseConvError as e:
@@ -180,6 +183,34 @@ def test_channel_chunked_pipeline(dtype):
         G.check(l, G.run_gpu(plan, data["x"]), ref, str(t.as_dict()))
         ran += 1
     assert ran >= 3
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+@pytest.mark.parametrize("D", [24, 10, 1])
+def test_symmetric_pipeline(dtype, D):
+    """Pointwise layer through the persistent kernel in which every wave copies and multiplies: more
+    tiles than workgroups, row counts that do and do not divide the wave count (including waves
+    without rows), ragged rows, odd and tiny row lengths, a tile tail."""
+    l = wl.Layer("sym", 40, D, 16, 16, 1, 1, 1, 1, 0, 0, N=70, sparsity=0.6, dtype=dtype, seed=7)
+    ran = 0
+    for n, ragged in ((None, True), (1, False), (3, False)):
+        data = wl.prepare(l, n=n, ragged=ragged)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for thr, tq, cc, td in ((64, 32, 0, 0), (320, 64, 0, 0), (1024, 48, 0, 0), (1024, 128, 0, 0),
+                                (704, 256, 0, 0), (1024, 128, 16, 0), (256, 256, 7, 0), (128, 64, 20, 8),
+                                (512, 192, 33, 0)):
+            try:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pipeline=2,
+                                wg_threads=thr, tile_q=tq, chunk_c=cc, tile_d=td)
+            except B.SparseConvError as e:
+                assert e.status == 4
+                continue
+            t = plan.get_tuning()
+            assert t.pipeline == 2 and t.producers == 0
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"n={n} {t.as_dict()}")
+            ran += 1
+    assert ran >= 15
 
 
 def test_ell_entry_point_and_unsorted_duplicate_columns():
