@@ -175,12 +175,9 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
         return;
     }
     // Rows are packed with an even pitch np: ng full groups of 8 pairs, then up to 3 pairs of 2.
-    // Full groups ping-pong between two register sets (A, B) and are fetched one ahead of their
-    // use, across row boundaries; the tail pairs of a row are fetched when the row starts.
     const int ng = np >> 3;
     const int tail = (np & 7) >> 1;
     A acc[VPT];
-    int ga[16], gb[16], tl[12];
     auto mac = [&](int wbits, int lam) {
         const WL w = weight_from_bits<DT>(wbits);
         const unsigned char* pj = lane_base + lam;
@@ -188,6 +185,39 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
         for (int k = 0; k < VPT; ++k)
             acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
     };
+    if constexpr (WSRC == 1) {
+        // Scalar loads, 8 entries at a time, through the constant address space and with no
+        // software prefetch: with nothing else pending on the scalar/LDS counter the eight gathers
+        // of a group can be waited for one by one, so the multiply-adds start when the first value
+        // arrives, and the other waves of the workgroup hide the scalar load.  The tail load
+        // reaches up to six entries past the row (the next row, or the slack behind the table).
+        typedef const int16v __attribute__((address_space(4)))* c16_t;
+        for (int d = first; d < D; d += stride) {
+            const int2* prow = wl32 + (int64_t)d * np;
+#pragma unroll
+            for (int k = 0; k < VPT; ++k) acc[k] = A(0);
+            for (int g = 0; g < ng; ++g) {
+                const int16v c = *(c16_t)(prow + 8 * g);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
+            }
+            if (tail > 0) {
+                const int16v c = *(c16_t)(prow + 8 * ng);
+                mac(c[0], c[1]); mac(c[2], c[3]);
+                if (tail > 1) { mac(c[4], c[5]); mac(c[6], c[7]); }
+                if (tail > 2) { mac(c[8], c[9]); mac(c[10], c[11]); }
+            }
+            Y* yd = yb + (int64_t)d * y_plane;
+#pragma unroll
+            for (int k = 0; k < VPT; ++k)
+                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+        }
+        return;
+    }
+    // Wave-uniform vector loads: full groups ping-pong between two register sets (A, B) and are
+    // fetched one ahead of their use, across row boundaries; the tail pairs of a row are fetched
+    // when the row starts.
+    int ga[16], gb[16], tl[12];
     auto mac8 = [&](const int (&c)[16]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
