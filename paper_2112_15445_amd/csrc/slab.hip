@@ -767,7 +767,6 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     using A = typename Types<DT>::A;
     using WL = typename Types<DT>::WL;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int EPV = 16 / (int)sizeof(X);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -777,6 +776,9 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     const int ncons = nwaves - nprod;
     const int units = a.N * a.tiles * a.ndt;        // (sample, tile, output-channel block)
     const int first = blockIdx.x, step = gridDim.x;
+    typedef const int16v __attribute__((address_space(4)))* c16_t;
+    typedef const int32_t __attribute__((address_space(4)))* ci_t;
+    const ci_t segs = (ci_t)seg_off;                // read through the constant address space
     // unit u -> (sample b, tile, dt); consecutive units share the input tile
     auto decode = [&](int u, int& b, int& q0, int& dt) {
         const int bt = fdiv(u, a.inv_ndt);
@@ -832,61 +834,38 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         const int dend = min(a.D, d0 + a.DTW);
         for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
             const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
-            // segment bounds of this wave's rows for this chunk: independent scalar loads issued
-            // together (before the barrier), so their latency is paid once per item
-            int s0[RPW], ln[RPW];
+            __syncthreads();  // A
+            // one segment per row and chunk, multiplied 8 entries at a time with no software
+            // prefetch (the gathers of a group are then waited for one by one, and the other
+            // waves hide the scalar loads); a partial last group is loaded whole -- the table has
+            // 16 spare entries -- and only its pairs inside the segment are used
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
                 const int d = d0 + wave + r * ncons;
-                const int64_t si = (int64_t)min(d, dend - 1) * a.nchunks + ch;
-                s0[r] = seg_off[si];
-                ln[r] = d < dend ? seg_off[si + 1] - s0[r] : 0;     // even
-            }
-            // first group of the first segment; every later segment's first group is fetched
-            // while the segment before it is being multiplied
-            int gc[16];
-            load_group<1>(gc, wlc, __amdgpu_buffer_rsrc_t(), s0[0]);
-            __syncthreads();  // A
+                if (d < dend) {
+                    const int si = d * a.nchunks + ch;
+                    const int s0 = segs[si], len = segs[si + 1] - s0;     // even
+                    auto mac = [&](int wbits, int lam) {
+                        const WL w = weight_from_bits<DT>(wbits);
+                        const unsigned char* pj = lane_base + lam;
 #pragma unroll
-            for (int r = 0; r < RPW; ++r) {
-                const int len = ln[r];
-                const int2* seg = wlc + s0[r];
-                const int ngroups = (len + 7) >> 3;
-                int ga[16], gb[16];
+                        for (int k = 0; k < VPT; ++k)
+                            acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                    };
+                    const int2* seg = wlc + s0;
+                    int e = 0;
+                    for (; e + 8 <= len; e += 8) {
+                        const int16v c = *(c16_t)(seg + e);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) ga[i] = gc[i];
-                if (r + 1 < RPW) load_group<1>(gc, wlc, __amdgpu_buffer_rsrc_t(), s0[r + 1 < RPW ? r + 1 : r]);
-                auto mac = [&](int wbits, int lam) {
-                    const WL w = weight_from_bits<DT>(wbits);
-                    const unsigned char* pj = lane_base + lam;
-#pragma unroll
-                    for (int k = 0; k < VPT; ++k)
-                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
-                };
-                // a partial last group reads past the segment (the table has 16 spare entries)
-                // and uses only len - 8*gi entries
-                auto process = [&](const int (&g)[16], int gi) {
-                    const int cnt = len - (gi << 3);
-                    if (cnt >= 8) {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) mac(g[2 * i], g[2 * i + 1]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 8; i += 2)
-                            if (i < cnt) {
-                                mac(g[2 * i], g[2 * i + 1]);
-                                mac(g[2 * i + 2], g[2 * i + 3]);
-                            }
+                        for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
                     }
-                };
-                int gi = 0;
-                while (gi < ngroups) {
-                    if (gi + 1 < ngroups) load_group<1>(gb, seg, __amdgpu_buffer_rsrc_t(), (gi + 1) * 8);
-                    process(ga, gi);
-                    if (++gi >= ngroups) break;
-                    if (gi + 1 < ngroups) load_group<1>(ga, seg, __amdgpu_buffer_rsrc_t(), (gi + 1) * 8);
-                    process(gb, gi);
-                    ++gi;
+                    const int tail = (len - e) >> 1;                      // 0..3 pairs
+                    if (tail > 0) {
+                        const int16v c = *(c16_t)(seg + e);
+                        mac(c[0], c[1]); mac(c[2], c[3]);
+                        if (tail > 1) { mac(c[4], c[5]); mac(c[6], c[7]); }
+                        if (tail > 2) { mac(c[8], c[9]); mac(c[10], c[11]); }
+                    }
                 }
             }
             __syncthreads();  // B
