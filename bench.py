@@ -2,7 +2,7 @@
 """Benchmark of the direct sparse convolution hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer NAME] [--no-autotune]
-                    [--report PATH]   # optional per-layer table over all five configs
+                    [--report PATH]   # optional per-layer table over all five configs (PATH, PATH.txt)
 
 One *step* is one pass of the hot path over one batch of synthetic input: sparse_conv_forward of
 the headline layer (largest ResNet-50-shaped layer at 90 % sparsity: the stage-1 1x1 reduce,
@@ -223,6 +223,15 @@ def main():
                 torch.cuda.empty_cache()
         with open(args.report, "w") as f:
             json.dump(rows, f, indent=1)
+        with open(args.report + ".txt", "w") as f:      # the same rows as a table
+            f.write("cfg layer                      dtype    n   sparse_us  alg_GB/s  hbm_frac  useful_TF  "
+                    "dense_us  launch shape\n")
+            for r in rows:
+                t = {k: v for k, v in r["tuning"].items() if v}
+                dm = r.get("dense_miopen_ms")
+                f.write(f"{r['config']:3d} {r['layer']:26s} {r['dtype']:4s} {r['n']:5d} {r['ms_events']*1e3:10.2f} "
+                        f"{r['achieved_gbs']:9.0f} {r['hbm_frac']*100:8.1f}% {r['useful_gflops']/1e3:9.2f} "
+                        f"{(dm*1e3 if dm else float('nan')):9.2f}  {json.dumps(t)}\n")
 
     print(json.dumps(line), flush=True)
 
