@@ -145,7 +145,12 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     // 16-byte staging needs every tile row start and the plane pitch to be 16-byte aligned
     const int epv = 16 / p.ex;
     o.vec = (pw && (o.Wf % epv == 0) && (o.TQ % epv == 0)) ? 1 : 0;
-    if (pipeline >= 1 && !o.vec) return false;
+    // direct-to-LDS copies: 16 bytes per lane for such rows, else 4 bytes per lane when the rows are
+    // at least 4-byte aligned (only the symmetric kernels take that form)
+    const int epd = std::max(1, 4 / p.ex);
+    o.dmab = o.vec ? 16 : ((pw && (o.Wf % epd == 0) && (o.TQ % epd == 0)) ? 4 : 0);
+    if (pipeline == 1 && !o.vec) return false;
+    if (pipeline == 2 && o.dmab == 0) return false;
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -696,9 +701,9 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     if (pw && p.dtype != SC_CB4_I8) {
-        for (int tq : {128, 256}) for (int cc : {32, 64, 128, 256}) {
+        for (int tq : {64, 128, 256}) for (int cc : {32, 64, 128, 256, 512}) {
             if (cc >= p.L.C) continue;
-            for (int td : {0, 128}) {
+            for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 sc_tuning_t t{};
                 t.variant = SC_VARIANT_SLAB;

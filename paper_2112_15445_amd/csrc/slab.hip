@@ -35,7 +35,7 @@ struct SlabArgs {
     int s_h, s_w, pad_h, pad_w;
     int TP, TQ, tiles_p, tiles_q;
     int nsw, Qs, sub_pitch, chan_pitch, F;
-    int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod;
+    int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod, dmab;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q;
     int64_t x_sample_stride, y_plane;
 };
@@ -415,7 +415,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 
 // ------------------------------------------------------------------------------------------------
 // Producer-side tile copy, global -> LDS, with the direct-to-LDS loads of gfx950 (16 bytes per lane,
-// 1 KB per instruction, no VGPR staging).  Copies nch channel rows of TQ elements (global row pitch
+// 1 KB per instruction, no VGPR staging; 4 bytes per lane for rows that are not 16-byte aligned).  Copies nch channel rows of TQ elements (global row pitch
 // Wf elements, tb = address of channel 0 / column q0 of the tile, wave-uniform) to the flat
 // [channel][TQ] image at dst; the instructions are dealt round-robin to the nprod producer waves.
 // When one instruction covers whole channel rows (or a row is a whole number of instructions), a
@@ -426,40 +426,52 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// One copy instruction: 16 bytes per lane from base + lane_off (base wave-uniform) to the LDS
-// image at dst + 16 * lane.  HAND = true issues it as inline assembly, which keeps it out of the
-// compiler's bookkeeping: a wave that both copies tile i+1 and reads tile i would otherwise be
+// One copy instruction: BYTES (16 or 4) per lane from base + lane_off (base wave-uniform) to the
+// LDS image at dst + BYTES * lane.  HAND = true issues it as inline assembly, which keeps it out of
+// the compiler's bookkeeping: a wave that both copies tile i+1 and reads tile i would otherwise be
 // made to wait for the copy before its first LDS read.  The caller then waits on vmcnt itself.
-template <bool HAND>
+template <bool HAND, int BYTES>
 __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, unsigned char* dst)
 {
+    static_assert(BYTES == 16 || BYTES == 4, "copy width");
     if constexpr (HAND) {
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                     : : "v"(lane_off), "s"(base), "s"(l) : "memory");
+        if constexpr (BYTES == 16)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         : : "v"(lane_off), "s"(base), "s"(l) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                         : : "v"(lane_off), "s"(base), "s"(l) : "memory");
     } else {
-        __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 0);
+        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 4, 0, 0);
     }
 }
-template <bool HAND>
+template <bool HAND, int BYTES>
 __device__ __forceinline__ void dma16_ptr(const void* src, unsigned char* dst)
 {
     if constexpr (HAND) {
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                     : : "v"(src), "s"(l) : "memory");
+        if constexpr (BYTES == 16)
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                         : : "v"(src), "s"(l) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                         : : "v"(src), "s"(l) : "memory");
     } else {
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 4, 0, 0);
     }
 }
 
-template <typename X, bool HAND = false>
+template <typename X, bool HAND = false, int BYTES = 16>
 __device__ __forceinline__ void
 dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int pw, int nprod, int lane,
          float inv_TQ)
 {
-    constexpr int EPV = 16 / (int)sizeof(X);
+    constexpr int EPV = BYTES / (int)sizeof(X);
     constexpr int EW = 64 * EPV;                          // elements per copy instruction
+    constexpr int IB = 64 * BYTES;                        // bytes per copy instruction
     const int e = lane * EPV;
     if ((TQ & (TQ - 1)) == 0 && TQ <= EW) {
         // one instruction = cpi whole channel rows
@@ -473,10 +485,10 @@ dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int p
         const char* base = reinterpret_cast<const char*>(tb);
         if (q0 + col < Wf) {
             int g = pw;
-            for (; g < nfull; g += nprod) dma16<HAND>(base + g * gstride, lane_off, dst + g * 1024);
+            for (; g < nfull; g += nprod) dma16<HAND, BYTES>(base + g * gstride, lane_off, dst + g * IB);
             // a last, partial group of channel rows falls to the wave whose turn it is
             if (g == nfull && c_sub < nch - nfull * cpi)
-                dma16<HAND>(base + nfull * gstride, lane_off, dst + nfull * 1024);
+                dma16<HAND, BYTES>(base + nfull * gstride, lane_off, dst + nfull * IB);
         }
         return;
     }
@@ -488,12 +500,12 @@ dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int p
             if (q0 + seg * EW + e < Wf) {
                 const char* base = reinterpret_cast<const char*>(tb + seg * EW);
                 for (int c = pw; c < nch; c += nprod)
-                    dma16<HAND>(base + c * cstride, (uint32_t)(e * (int)sizeof(X)), dst + (c * ipc + seg) * 1024);
+                    dma16<HAND, BYTES>(base + c * cstride, (uint32_t)(e * (int)sizeof(X)), dst + (c * ipc + seg) * IB);
             }
         }
         return;
     }
-    // generic: the (channel, column) of a lane's 16 bytes advances by a fixed step from one
+    // generic: the (channel, column) of a lane's bytes advances by a fixed step from one
     // instruction to the next, so the division is done once and the rest is increments
     const int E = nch * TQ;
     const int stepE = EW * nprod;
@@ -503,7 +515,7 @@ dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int p
     int col = idx - c * TQ;
     const X* src = tb + (int64_t)c * Wf + col;
     for (int i = pw; i * EW < E; i += nprod) {
-        if (idx < E && q0 + col < Wf) dma16_ptr<HAND>(src, dst + i * 1024);
+        if (idx < E && q0 + col < Wf) dma16_ptr<HAND, BYTES>(src, dst + i * IB);
         idx += stepE;
         col += rstep;
         src += (int64_t)qstep * Wf + rstep;
@@ -639,8 +651,12 @@ slab_sym_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>:
     auto issue = [&](int t, int buf) {
         const int b = fdiv(t, a.inv_tiles);
         const int q0 = (t - b * tiles) * a.TQ;
-        dma_tile<X, true>(x + (int64_t)b * a.x_sample_stride + q0, lds + buf * a.slab_bytes, a.C, a.TQ,
-                          a.Wf, q0, wave, nwaves, lane, a.inv_Qs);
+        if (a.dmab == 16)
+            dma_tile<X, true, 16>(x + (int64_t)b * a.x_sample_stride + q0, lds + buf * a.slab_bytes, a.C,
+                                  a.TQ, a.Wf, q0, wave, nwaves, lane, a.inv_Qs);
+        else
+            dma_tile<X, true, 4>(x + (int64_t)b * a.x_sample_stride + q0, lds + buf * a.slab_bytes, a.C,
+                                 a.TQ, a.Wf, q0, wave, nwaves, lane, a.inv_Qs);
     };
     issue(first, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -752,7 +768,7 @@ sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t tot
 }
 
 struct ChunkArgs {
-    int C, D, N, Wf, TQ, tiles, CC, nchunks, DTW, ndt, nprod, slab_bytes;
+    int C, D, N, Wf, TQ, tiles, CC, nchunks, DTW, ndt, nprod, slab_bytes, dmab;
     float inv_tiles, inv_TQ, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -926,9 +942,14 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         int b, q0, dt;
         decode(u, b, q0, dt);
         const int c0 = ch * a.CC;
-        dma_tile<X, true>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
-                          lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, wave, nwaves,
-                          lane, a.inv_TQ);
+        if (a.dmab == 16)
+            dma_tile<X, true, 16>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
+                                  lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, wave,
+                                  nwaves, lane, a.inv_TQ);
+        else
+            dma_tile<X, true, 4>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
+                                 lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, wave,
+                                 nwaves, lane, a.inv_TQ);
     };
     const ci_t segs = (ci_t)seg_off;
     const c16_t wl = (c16_t)wlc;
@@ -1057,6 +1078,7 @@ static sc_status_t launch_chunk(const Plan& p, const void* x, void* y, int N, hi
     a.C = p.L.C; a.D = p.L.D; a.N = N; a.Wf = g.Wf; a.TQ = g.TQ; a.tiles = g.tiles_q;
     a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt; a.nprod = p.tuning.producers;
     a.slab_bytes = g.slab_bytes;
+    a.dmab = g.dmab;
     a.inv_tiles = 1.0f / (float)g.tiles_q; a.inv_TQ = 1.0f / (float)g.TQ; a.inv_ndt = 1.0f / (float)g.ndt;
     a.x_sample_stride = (int64_t)p.L.C * g.Wf;
     a.y_plane = (int64_t)g.Qf;
@@ -1233,7 +1255,7 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
     if constexpr (DT != SC_CB4_I8) {
         if (p.tuning.pipeline == 2) {
             // as for pipeline 1: an unaligned x takes the one-shot kernel
-            if (a.vec) return launch_sym<DT>(p, a, x, y, stream);
+            if (a.dmab) return launch_sym<DT>(p, a, x, y, stream);
         }
         if (p.tuning.pipeline == 1) {
             // the direct-to-LDS copy needs 16-byte aligned rows: checked at tuning time for the
@@ -1253,8 +1275,8 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
 {
     const SlabGeom& g = p.geom;
     if (p.tuning.chunk_c > 0) {
-        // 16-byte direct-to-LDS copies: the caller's pointer must be 16-byte aligned as well
-        if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return SC_ERR_UNSUPPORTED;
+        // direct-to-LDS copies: the caller's pointer must be aligned like the rows
+        if (reinterpret_cast<uintptr_t>(x) % (uintptr_t)std::max(g.dmab, 1) != 0) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {
             case SC_F32: return launch_chunk<SC_F32>(p, x, y, N, stream);
             case SC_F16: return launch_chunk<SC_F16>(p, x, y, N, stream);
@@ -1274,6 +1296,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC; a.np = p.np; a.nprod = p.tuning.producers;
     // 16-byte staging also needs a 16-byte aligned input pointer
     a.vec = (g.vec && (reinterpret_cast<uintptr_t>(x) % 16 == 0)) ? 1 : 0;
+    a.dmab = (g.dmab && reinterpret_cast<uintptr_t>(x) % (uintptr_t)g.dmab == 0) ? g.dmab : 0;
     a.inv_chan_pitch = g.inv_chan_pitch; a.inv_sub_pitch = g.inv_sub_pitch; a.inv_Qs = g.inv_Qs;
     a.inv_tiles = 1.0f / (float)(g.tiles_p * g.tiles_q);
     a.inv_tiles_q = 1.0f / (float)g.tiles_q;

@@ -213,6 +213,28 @@ def test_symmetric_pipeline(dtype, D):
     assert ran >= 15
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_symmetric_pipeline_rows_not_16_byte_aligned(dtype):
+    """7x7 planes (49 elements per channel row): fp32 rows are only 4-byte aligned, so the symmetric
+    kernels copy 4 bytes per lane; fp16 / int8 rows of odd length cannot be copied that way and the
+    tuning must be refused."""
+    l = wl.Layer("sym7", 72, 40, 7, 7, 1, 1, 1, 1, 0, 0, N=9, sparsity=0.7, dtype=dtype, seed=11)
+    data = wl.prepare(l, ragged=True)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    ran = 0
+    for thr, tq, cc, td in ((1024, 64, 0, 0), (384, 49, 24, 0), (512, 32, 16, 16), (1024, 64, 36, 8)):
+        try:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pipeline=2,
+                            wg_threads=thr, tile_q=tq, chunk_c=cc, tile_d=td)
+        except B.SparseConvError as e:
+            assert e.status == 4
+            continue
+        G.check(l, G.run_gpu(plan, data["x"]), ref, str(plan.get_tuning().as_dict()))
+        ran += 1
+    assert ran == (4 if dtype == "f32" else 0)
+
+
 def test_ell_entry_point_and_unsorted_duplicate_columns():
     rng = np.random.default_rng(3)
     l = wl.Layer("ell", 4, 5, 8, 8, 3, 3, 1, 1, 1, 1, N=2, dtype="i8")
