@@ -264,6 +264,77 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
     }
 }
 
+// Scalar-load row stream for 16- and 8-bit activations of pointwise layers, positions packed by
+// the dword: lane l owns the E = 2 (fp16) or 4 (int8) adjacent positions (k*64 + l)*E .. +E-1, so
+// one ds_read_b32 feeds E multiply-adds and the outputs of a lane leave as one 4- or 16-byte
+// store.  Needs 4-byte aligned channel rows (tile width and plane size multiples of E), which the
+// direct-to-LDS forms guarantee.  out_off[k] is the element offset of the lane's first position
+// of dword k inside the output plane, or -1.  Same loop shape as the unpacked stream: 8 entries
+// per scalar load, no software prefetch, tail pairs from one over-reaching load.
+template <sc_dtype_t DT, int VW>
+__device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const unsigned char* lane_base,
+                                          typename Types<DT>::Y* yb, const int (&out_off)[VW], int first,
+                                          int stride, int D, int np, int64_t y_plane)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    static_assert(DT == SC_F16 || DT == SC_I8, "packed positions: 16- or 8-bit activations");
+    constexpr int E = 4 / (int)sizeof(X);
+    typedef const int16v __attribute__((address_space(4)))* c16_t;
+    const int ng = np >> 3;
+    const int tail = (np & 7) >> 1;
+    A acc[VW][E];
+    auto mac = [&](int wbits, int lam) {
+        const WL w = weight_from_bits<DT>(wbits);
+        const unsigned char* pj = lane_base + lam;
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            const uint32_t xd = *reinterpret_cast<const uint32_t*>(pj + k * 256);
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                if constexpr (DT == SC_F16)
+                    acc[k][e] += w * __half2float(__ushort_as_half((unsigned short)(xd >> (16 * e))));
+                else
+                    acc[k][e] += w * (int32_t)(int8_t)(xd >> (8 * e));
+            }
+        }
+    };
+    for (int d = first; d < D; d += stride) {
+        const int2* prow = wl32 + (int64_t)d * np;
+#pragma unroll
+        for (int k = 0; k < VW; ++k)
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[k][e] = A(0);
+        for (int g = 0; g < ng; ++g) {
+            const int16v c = *(c16_t)(prow + 8 * g);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
+        }
+        if (tail > 0) {
+            const int16v c = *(c16_t)(prow + 8 * ng);
+            mac(c[0], c[1]); mac(c[2], c[3]);
+            if (tail > 1) { mac(c[4], c[5]); mac(c[6], c[7]); }
+            if (tail > 2) { mac(c[8], c[9]); mac(c[10], c[11]); }
+        }
+        Y* yd = yb + (int64_t)d * y_plane;
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            if (out_off[k] >= 0) {
+                if constexpr (DT == SC_F16) {
+                    const uint32_t lo = __half_as_ushort(__float2half(acc[k][0]));
+                    const uint32_t hi = __half_as_ushort(__float2half(acc[k][1]));
+                    *reinterpret_cast<uint32_t*>(yd + out_off[k]) = lo | (hi << 16);
+                } else {
+                    *reinterpret_cast<int4*>(yd + out_off[k]) =
+                        make_int4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+                }
+            }
+        }
+    }
+}
+
 template <sc_dtype_t DT, int VPT, int WSRC>
 __global__ void
 slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
@@ -591,16 +662,23 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     for (int t = first; t < total; t += step, ++it) {
         const int b = fdiv(t, a.inv_tiles);
         const int q0 = (t - b * tiles) * a.TQ;
+        // 16- and 8-bit activations with scalar-load weights: positions packed by the dword (VPT
+        // then counts dwords per lane); otherwise lane l owns positions l, l + 64, ...
+        constexpr bool kPacked = DT != SC_F32 && WSRC == 1;
+        constexpr int E = kPacked ? 4 / (int)sizeof(X) : 1;
         int out_off[VPT];
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            const int f = k * 64 + lane;
+            const int f = (k * 64 + lane) * E;
             out_off[k] = (f < a.TQ && q0 + f < a.Qf) ? q0 + f : -1;
         }
         Y* yb = y + (int64_t)b * a.D * a.y_plane;
-        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (kPacked ? 4 : (int)sizeof(X));
         __syncthreads();  // A
-        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.n, a.np, a.y_plane);
+        if constexpr (kPacked)
+            stream_rows_packed<DT, VPT>(wl32, lane_base, yb, out_off, wave, ncons, a.D, a.np, a.y_plane);
+        else
+            stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.n, a.np, a.y_plane);
         __syncthreads();  // B
     }
 }
@@ -1191,6 +1269,17 @@ static sc_status_t launch_async_one(const Plan& p, const SlabArgs& a, const void
 template <sc_dtype_t DT, int WSRC>
 static sc_status_t launch_async_w(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
 {
+    if constexpr (DT != SC_F32 && WSRC == 1) {
+        // positions packed by the dword: the kernel's count is dwords per lane
+        const int per_dword = 4 / p.ex;
+        switch ((p.geom.TQ + 64 * per_dword - 1) / (64 * per_dword)) {
+            case 1: return launch_async_one<DT, 1, WSRC>(p, a, x, y, stream);
+            case 2: return launch_async_one<DT, 2, WSRC>(p, a, x, y, stream);
+            case 3: return launch_async_one<DT, 3, WSRC>(p, a, x, y, stream);
+            case 4: return launch_async_one<DT, 4, WSRC>(p, a, x, y, stream);
+        }
+        return SC_ERR_UNSUPPORTED;
+    }
     switch (p.geom.vpt) {
         case 1: return launch_async_one<DT, 1, WSRC>(p, a, x, y, stream);
         case 2: return launch_async_one<DT, 2, WSRC>(p, a, x, y, stream);
@@ -1295,7 +1384,8 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.slab_elems = p.L.C * g.chan_pitch;
     a.slab_bytes = g.slab_bytes; a.wcap = g.wcap; a.DS = g.DS; a.JC = g.JC; a.np = p.np; a.nprod = p.tuning.producers;
     // 16-byte staging also needs a 16-byte aligned input pointer
-    a.vec = (g.vec && (reinterpret_cast<uintptr_t>(x) % 16 == 0)) ? 1 : 0;
+    // (the packed 16- and 8-bit stream also stores 4 / 16 bytes per lane: y aligned like x)
+    a.vec = (g.vec && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) ? 1 : 0;
     a.dmab = (g.dmab && reinterpret_cast<uintptr_t>(x) % (uintptr_t)g.dmab == 0) ? g.dmab : 0;
     a.inv_chan_pitch = g.inv_chan_pitch; a.inv_sub_pitch = g.inv_sub_pitch; a.inv_Qs = g.inv_Qs;
     a.inv_tiles = 1.0f / (float)(g.tiles_p * g.tiles_q);

@@ -213,6 +213,27 @@ def test_symmetric_pipeline(dtype, D):
     assert ran >= 15
 
 
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+def test_packed_positions_in_the_producer_consumer_kernel(dtype):
+    """16- and 8-bit activations through the persistent kernel whose lanes own 2 / 4 adjacent
+    positions per LDS dword: one to four dwords per lane, a ragged last tile, ragged rows."""
+    l = wl.Layer("packed", 24, 20, 24, 24, 1, 1, 1, 1, 0, 0, N=40, sparsity=0.5, dtype=dtype, seed=13)
+    data = wl.prepare(l, ragged=True)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    ran = 0
+    for thr, tq, npd in ((1024, 128, 2), (512, 256, 1), (1024, 512, 4), (768, 192, 1), (1024, 64, 2)):
+        try:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pipeline=1,
+                            wg_threads=thr, tile_q=tq, producers=npd)
+        except B.SparseConvError as e:
+            assert e.status == 4
+            continue
+        G.check(l, G.run_gpu(plan, data["x"]), ref, str(plan.get_tuning().as_dict()))
+        ran += 1
+    assert ran >= 4
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
 def test_symmetric_pipeline_rows_not_16_byte_aligned(dtype):
     """7x7 planes (49 elements per channel row): fp32 rows are only 4-byte aligned, so the symmetric
