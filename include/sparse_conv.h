@@ -106,7 +106,9 @@ typedef struct {
                            tile); needs wsrc = 1 and at least one stored weight per row; with chunk_c > 0 at
                            most 4 positions per lane and 8 rows per wave.  0 = one tile per workgroup */
     int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
-    int32_t chunk_c;    /* SLAB with pipeline = 1 or 2: input channels per LDS buffer (0 = all of them).  With
+    int32_t chunk_c;    /* SLAB: input channels per LDS buffer (0 = all of them); with pipeline = 0 for any
+                           layer shape (wsrc = 1, at most 4 positions per lane and 8 rows per wave), with
+                           pipeline = 1 or 2 for pointwise layers.  With
                            chunk_c < C a tile is multiplied chunk by chunk, each wave keeping the
                            accumulators of its output channels in registers across the chunks, so
                            wide tiles fit LDS even for layers with many input channels */

@@ -101,10 +101,11 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (chunk_c > 0) {
         // chunked form: pointwise layers, pipelined, weights by scalar loads; every consumer wave
         // keeps the accumulators of its rows in registers across the chunks of a tile
-        if (!pw || pipeline < 1 || wsrc != 1 || p.dtype == SC_CB4_I8) return false;
+        // (pipeline 1 / 2: pointwise layers only; the one-shot chunked form takes any layer)
+        if ((!pw && pipeline >= 1) || wsrc != 1 || p.dtype == SC_CB4_I8 || p.n == 0) return false;
         const int ncons = o.nwaves - (pipeline == 1 ? producers : 0);
         if (ncons < 1) return false;
-        if (pipeline == 2 && o.vpt > 4) return false;
+        if (pipeline != 1 && o.vpt > 4) return false;
         o.rpw = (o.DTW + ncons - 1) / ncons;
         if (o.rpw > kMaxRowsPerWave) return false;
     }
@@ -765,6 +766,27 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                         t.tile_q = p.Q;
                         push(t);
                     }
+                }
+            }
+        }
+    }
+    // channel-chunked one-shot form (any layer shape): tiles several output rows high
+    if (!pw && p.dtype != SC_CB4_I8 && p.n > 0) {
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                for (int tp : {2, 4, 7, 8, 14, 16, 28}) {
+                    sc_tuning_t t{};
+                    t.variant = SC_VARIANT_SLAB;
+                    t.wsrc = 1;
+                    t.wg_per_cu = wpc;
+                    t.wg_threads = 1024;
+                    t.tile_p = tp;
+                    t.tile_q = p.Q;
+                    t.chunk_c = cc;
+                    t.tile_d = td;
+                    push(t);
                 }
             }
         }

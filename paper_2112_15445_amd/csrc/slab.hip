@@ -36,7 +36,8 @@ struct SlabArgs {
     int TP, TQ, tiles_p, tiles_q;
     int nsw, Qs, sub_pitch, chan_pitch, F;
     int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod, dmab;
-    float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q;
+    int CC, nchunks, DTW, ndt;           // channel-chunked one-shot form
+    float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
 
@@ -1112,6 +1113,168 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Channel-chunked one-shot form for any layer shape (tuning.pipeline = 0, tuning.chunk_c > 0).
+//
+// One workgroup = one sample x one output tile x one block of DTW output channels.  The input
+// region of the tile (halo, zero padding and stride phases as in slab_kernel) is staged CC input
+// channels at a time; every wave keeps the accumulators of its rows (a contiguous range, at most
+// kMaxRowsPerWave) x positions in registers across the chunks and stores after the last.  Because
+// only CC channels are resident, layers with many input channels can take tiles several output
+// rows high -- all 64 lanes of a wave busy on strided and small-plane layers where a full-channel
+// tile is limited by LDS to a fraction of a wave.  Weights: the per-(row, chunk) segments of the
+// chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
+// alternate; two or more workgroups per CU overlap them.
+// ------------------------------------------------------------------------------------------------
+template <sc_dtype_t DT, int VPT>
+__global__ void
+slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+               const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    typedef const int16v __attribute__((address_space(4)))* c16_t;
+    typedef const int32_t __attribute__((address_space(4)))* ci_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int RPW = kMaxRowsPerWave;
+    X* slab = reinterpret_cast<X*>(lds);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = nthreads >> 6;
+
+    // workgroup -> (sample, tile, output-channel block); consecutive workgroups share the tile
+    const int tiles = a.tiles_p * a.tiles_q;
+    const int bt = fdiv(blockIdx.x, a.inv_ndt);
+    const int dt = blockIdx.x - bt * a.ndt;
+    const int b = fdiv(bt, a.inv_tiles);
+    const int t = bt - b * tiles;
+    const int tpi = fdiv(t, a.inv_tiles_q);
+    const int tqi = t - tpi * a.tiles_q;
+    const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
+    const int row0 = p0 * a.s_h - a.pad_h, col0 = q0 * a.s_w - a.pad_w;
+    const float inv_nsw = 1.0f / (float)a.nsw;
+    const X* xb = x + (int64_t)b * a.x_sample_stride;
+
+    int out_off[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const int f = k * 64 + lane;
+        const int tp = fdiv(f, a.inv_Qs);
+        const int tq = f - tp * a.Qs;
+        const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf;
+        out_off[k] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
+    }
+    const unsigned char* lane_base = lds + lane * (int)sizeof(X);
+
+    // contiguous row range of this wave inside the output-channel block
+    const int d0 = dt * a.DTW, dcnt = min(a.DTW, a.D - d0);
+    const int base_rows = dcnt / nwaves, extra = dcnt - base_rows * nwaves;
+    const int drow0 = d0 + wave * base_rows + min(wave, extra);
+    const int nrows = base_rows + (wave < extra ? 1 : 0);
+    const ci_t segs = (ci_t)seg_off;
+
+    A acc[RPW][VPT];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r)
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const int c0 = ch * a.CC;
+        const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
+        if (ch > 0) __syncthreads();      // the previous chunk has been consumed
+        for (int e = tid; e < elems; e += nthreads) {
+            const int c = fdiv(e, a.inv_chan_pitch);
+            const int rem = e - c * a.chan_pitch;
+            const int sub = fdiv(rem, a.inv_sub_pitch);
+            const int rem2 = rem - sub * a.sub_pitch;
+            const int i = fdiv(rem2, a.inv_Qs);
+            const int k = rem2 - i * a.Qs;
+            const int ph = fdiv(sub, inv_nsw), pw = sub - ph * a.nsw;
+            const int row = row0 + i * a.s_h + ph;
+            const int col = col0 + k * a.s_w + pw;
+            X v = X(0);
+            if (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf)
+                v = xb[((int64_t)(c0 + c) * a.Hf + row) * a.Wf + col];
+            slab[e] = v;
+        }
+        __syncthreads();                  // chunk staged
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            if (r < nrows) {
+                const int si = (drow0 + r) * a.nchunks + ch;
+                const int s0 = segs[si], len = segs[si + 1] - s0;     // even
+                auto mac = [&](int wbits, int lam) {
+                    const WL w = weight_from_bits<DT>(wbits);
+                    const unsigned char* pj = lane_base + lam;
+#pragma unroll
+                    for (int k = 0; k < VPT; ++k)
+                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                };
+                const int2* seg = wlc + s0;
+                int e = 0;
+                for (; e + 8 <= len; e += 8) {
+                    const int16v c = *(c16_t)(seg + e);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) mac(c[2 * i], c[2 * i + 1]);
+                }
+                const int tail = (len - e) >> 1;                      // 0..3 pairs
+                if (tail > 0) {
+                    const int16v c = *(c16_t)(seg + e);
+                    mac(c[0], c[1]); mac(c[2], c[3]);
+                    if (tail > 1) { mac(c[4], c[5]); mac(c[6], c[7]); }
+                    if (tail > 2) { mac(c[8], c[9]); mac(c[10], c[11]); }
+                }
+            }
+        }
+    }
+    Y* yd = y + ((int64_t)b * a.D + drow0) * a.y_plane;
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        if (r < nrows) {
+#pragma unroll
+            for (int k = 0; k < VPT; ++k)
+                if (out_off[k] >= 0) yd[(int64_t)r * a.y_plane + out_off[k]] = narrow<DT>(acc[r][k]);
+        }
+    }
+}
+
+template <sc_dtype_t DT, int VPT>
+static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                                 hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = slab_cc_kernel<DT, VPT>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
+                       static_cast<const X*>(x), static_cast<Y*>(y), p.d_wlc, p.d_seg_off, a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_cc(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+{
+    switch (p.geom.vpt) {
+        case 1: return launch_cc_one<DT, 1>(p, a, x, y, grid, stream);
+        case 2: return launch_cc_one<DT, 2>(p, a, x, y, grid, stream);
+        case 3: return launch_cc_one<DT, 3>(p, a, x, y, grid, stream);
+        case 4: return launch_cc_one<DT, 4>(p, a, x, y, grid, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
 template <sc_dtype_t DT, int VPT, int RPW>
 static sc_status_t launch_chunk_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
 {
@@ -1363,7 +1526,7 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
 {
     const SlabGeom& g = p.geom;
-    if (p.tuning.chunk_c > 0) {
+    if (p.tuning.chunk_c > 0 && p.tuning.pipeline >= 1) {
         // direct-to-LDS copies: the caller's pointer must be aligned like the rows
         if (reinterpret_cast<uintptr_t>(x) % (uintptr_t)std::max(g.dmab, 1) != 0) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {
@@ -1392,6 +1555,18 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.inv_tiles_q = 1.0f / (float)g.tiles_q;
     a.x_sample_stride = (int64_t)p.L.C * g.Hf * g.Wf;
     a.y_plane = (int64_t)g.Pf * g.Qf;
+    if (p.tuning.chunk_c > 0) {
+        a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt;
+        a.inv_ndt = 1.0f / (float)g.ndt;
+        const int64_t gridc = grid64 * g.ndt;
+        if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
+        switch (p.dtype) {
+            case SC_F32: return launch_cc<SC_F32>(p, a, x, y, (int)gridc, stream);
+            case SC_F16: return launch_cc<SC_F16>(p, a, x, y, (int)gridc, stream);
+            case SC_I8: return launch_cc<SC_I8>(p, a, x, y, (int)gridc, stream);
+            default: return SC_ERR_UNSUPPORTED;
+        }
+    }
     switch (p.dtype) {
         case SC_F32: return launch_dt<SC_F32>(p, a, x, y, (int)grid64, stream);
         case SC_F16: return launch_dt<SC_F16>(p, a, x, y, (int)grid64, stream);

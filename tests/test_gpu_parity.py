@@ -26,6 +26,9 @@ def _both_variants(plan):
                                                 "tile_d": 4, "tile_q": 64, "producers": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "producers": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 2, "pipeline": 1, "wg_threads": 512, "producers": 4}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 256}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
+                                                "tile_q": 1000}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
