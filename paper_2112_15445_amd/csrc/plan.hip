@@ -770,6 +770,28 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
+    // channel-chunked one-shot form on pointwise layers: for planes too small or too oddly sized
+    // for the persistent forms
+    if (pw && p.dtype != SC_CB4_I8 && p.n > 0) {
+        for (int wpc : {1, 2, 3}) for (int cc : {32, 64, 128, 256}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                for (int tq : {64, 128, 256}) {
+                    sc_tuning_t t{};
+                    t.variant = SC_VARIANT_SLAB;
+                    t.wsrc = 1;
+                    t.wg_per_cu = wpc;
+                    t.wg_threads = 1024;
+                    t.tile_p = 1;
+                    t.tile_q = tq;
+                    t.chunk_c = cc;
+                    t.tile_d = td;
+                    push(t);
+                }
+            }
+        }
+    }
     // channel-chunked one-shot form (any layer shape): tiles several output rows high
     if (!pw && p.dtype != SC_CB4_I8 && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128}) {

@@ -1188,6 +1188,15 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         const int c0 = ch * a.CC;
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
         if (ch > 0) __syncthreads();      // the previous chunk has been consumed
+        if (a.Hf == 1 && a.chan_pitch == a.TQ) {
+            // pointwise layers: a chunk is rows of TQ consecutive pixels, one wave per channel row
+            const int ccn = min(a.CC, a.C - c0);
+            for (int c = wave; c < ccn; c += nwaves) {
+                const X* src = xb + (int64_t)(c0 + c) * a.Wf + q0;
+                for (int col = lane; col < a.TQ; col += 64)
+                    slab[c * a.TQ + col] = (q0 + col < a.Wf) ? src[col] : X(0);
+            }
+        } else
         for (int e = tid; e < elems; e += nthreads) {
             const int c = fdiv(e, a.inv_chan_pitch);
             const int rem = e - c * a.chan_pitch;
