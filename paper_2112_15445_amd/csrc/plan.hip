@@ -131,6 +131,8 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         o.JC = std::max(1, o.wcap / o.DS);
     }
     o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64;
+    // the chunked one-shot form keeps a table of chan_pitch plane offsets behind the slab
+    if (pipeline == 0 && chunk_c > 0) o.lds_bytes = o.slab_bytes + round_up(o.chan_pitch * 4, 16) + 64;
     if (pipeline == 1) {
         // two tile buffers, no weight stage; only for pointwise layers whose rows can be copied
         // 16 bytes at a time, and the workgroup needs consumer waves besides the producers

@@ -1171,6 +1171,23 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
     const unsigned char* lane_base = lds + lane * (int)sizeof(X);
 
+    // Offset of every element of one staged channel image inside the input plane, or -1 where the
+    // image shows zero padding / lies outside the plane: computed once, so that staging a chunk
+    // costs one division, one table read and one load per element.
+    int* tab = reinterpret_cast<int*>(lds + a.slab_bytes);
+    const int plane = a.Hf * a.Wf;
+    for (int rem = tid; rem < a.chan_pitch; rem += nthreads) {
+        const int sub = fdiv(rem, a.inv_sub_pitch);
+        const int rem2 = rem - sub * a.sub_pitch;
+        const int i = fdiv(rem2, a.inv_Qs);
+        const int k = rem2 - i * a.Qs;
+        const int ph = fdiv(sub, inv_nsw), pw = sub - ph * a.nsw;
+        const int row = row0 + i * a.s_h + ph;
+        const int col = col0 + k * a.s_w + pw;
+        tab[rem] = (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf) ? row * a.Wf + col : -1;
+    }
+    __syncthreads();
+
     // contiguous row range of this wave inside the output-channel block
     const int d0 = dt * a.DTW, dcnt = min(a.DTW, a.D - d0);
     const int base_rows = dcnt / nwaves, extra = dcnt - base_rows * nwaves;
@@ -1188,29 +1205,25 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         const int c0 = ch * a.CC;
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
         if (ch > 0) __syncthreads();      // the previous chunk has been consumed
-        if (a.Hf == 1 && a.chan_pitch == a.TQ) {
-            // pointwise layers: a chunk is rows of TQ consecutive pixels, one wave per channel row
-            const int ccn = min(a.CC, a.C - c0);
-            for (int c = wave; c < ccn; c += nwaves) {
-                const X* src = xb + (int64_t)(c0 + c) * a.Wf + q0;
-                for (int col = lane; col < a.TQ; col += 64)
-                    slab[c * a.TQ + col] = (q0 + col < a.Wf) ? src[col] : X(0);
+        // four elements per thread and pass, loads first, so that four loads are in flight
+        const X* xc = xb + (int64_t)c0 * plane;
+        for (int e0 = tid; e0 < elems; e0 += 4 * nthreads) {
+            X v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * nthreads;
+                v[u] = X(0);
+                if (e < elems) {
+                    const int c = fdiv(e, a.inv_chan_pitch);
+                    const int o = tab[e - c * a.chan_pitch];
+                    if (o >= 0) v[u] = xc[(int64_t)c * plane + o];
+                }
             }
-        } else
-        for (int e = tid; e < elems; e += nthreads) {
-            const int c = fdiv(e, a.inv_chan_pitch);
-            const int rem = e - c * a.chan_pitch;
-            const int sub = fdiv(rem, a.inv_sub_pitch);
-            const int rem2 = rem - sub * a.sub_pitch;
-            const int i = fdiv(rem2, a.inv_Qs);
-            const int k = rem2 - i * a.Qs;
-            const int ph = fdiv(sub, inv_nsw), pw = sub - ph * a.nsw;
-            const int row = row0 + i * a.s_h + ph;
-            const int col = col0 + k * a.s_w + pw;
-            X v = X(0);
-            if (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf)
-                v = xb[((int64_t)(c0 + c) * a.Hf + row) * a.Wf + col];
-            slab[e] = v;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * nthreads;
+                if (e < elems) slab[e] = v[u];
+            }
         }
         __syncthreads();                  // chunk staged
 #pragma unroll
