@@ -114,7 +114,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.slab_bytes = round_up((int)slab, 16);
     // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
     const int64_t total = (int64_t)L.D * p.n;
-    int64_t cap = (lds_budget - o.slab_bytes - 64) / 8;
+    int64_t cap = (lds_budget - o.slab_bytes - 64 - round_up(o.chan_pitch * 4, 16)) / 8;
     cap = std::min<int64_t>(cap, 4096);
     cap = std::min<int64_t>(cap, std::max<int64_t>(total, 1));
     if (wsrc != 0) cap = 0;  // weights straight from global memory: no weight stage in LDS
@@ -130,8 +130,9 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         o.DS = std::min(L.D, o.nwaves);   // one row per wave, rows cut into chunks
         o.JC = std::max(1, o.wcap / o.DS);
     }
-    o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64;
-    // the chunked one-shot form keeps a table of chan_pitch plane offsets behind the slab
+    // the one-shot forms keep a table of chan_pitch plane offsets behind the slab (chunked form) or
+    // behind the weight stage and the codebook (full-channel form)
+    o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64 + round_up(o.chan_pitch * 4, 16);
     if (pipeline == 0 && chunk_c > 0) o.lds_bytes = o.slab_bytes + round_up(o.chan_pitch * 4, 16) + 64;
     if (pipeline == 1) {
         // two tile buffers, no weight stage; only for pointwise layers whose rows can be copied

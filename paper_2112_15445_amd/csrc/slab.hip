@@ -381,11 +381,15 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
             *reinterpret_cast<uint4*>(slab + c * a.chan_pitch + (v - c * vpr) * EPV) = val;
         }
     } else {
+        // Offset of every element of one staged channel image inside the input plane, or -1 where
+        // the image shows zero padding / lies outside the plane: computed once, so that staging
+        // costs one division, one table read and one load per element; four elements per thread
+        // and pass, loads first, so that four loads are in flight.
         const int row0 = p0 * a.s_h - a.pad_h, col0 = q0 * a.s_w - a.pad_w;
         const float inv_nsw = 1.0f / (float)a.nsw;
-        for (int e = tid; e < a.slab_elems; e += nthreads) {
-            const int c = fdiv(e, a.inv_chan_pitch);
-            const int rem = e - c * a.chan_pitch;
+        int* tab = reinterpret_cast<int*>(lds + a.slab_bytes + a.wcap * 8 + 64);
+        const int plane = a.Hf * a.Wf;
+        for (int rem = tid; rem < a.chan_pitch; rem += nthreads) {
             const int sub = fdiv(rem, a.inv_sub_pitch);
             const int rem2 = rem - sub * a.sub_pitch;
             const int i = fdiv(rem2, a.inv_Qs);
@@ -393,10 +397,26 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
             const int ph = fdiv(sub, inv_nsw), pw = sub - ph * a.nsw;
             const int row = row0 + i * a.s_h + ph;
             const int col = col0 + k * a.s_w + pw;
-            X v = X(0);
-            if (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf)
-                v = xb[((int64_t)c * a.Hf + row) * a.Wf + col];
-            slab[e] = v;
+            tab[rem] = (row >= 0 && row < a.Hf && col >= 0 && col < a.Wf) ? row * a.Wf + col : -1;
+        }
+        __syncthreads();
+        for (int e0 = tid; e0 < a.slab_elems; e0 += 4 * nthreads) {
+            X v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * nthreads;
+                v[u] = X(0);
+                if (e < a.slab_elems) {
+                    const int c = fdiv(e, a.inv_chan_pitch);
+                    const int o = tab[e - c * a.chan_pitch];
+                    if (o >= 0) v[u] = xb[(int64_t)c * plane + o];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * nthreads;
+                if (e < a.slab_elems) slab[e] = v[u];
+            }
         }
     }
     if constexpr (DT == SC_CB4_I8) {
