@@ -651,7 +651,10 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     const int tiles = a.tiles_q;
     const int total = a.N * tiles;
     const float inv_TQ = a.inv_Qs;
-    const int first = blockIdx.x, step = gridDim.x;
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles per
+    // round (its L2 then sees whole stretches of every channel row) when the grid is a multiple of 8
+    const int step = gridDim.x;
+    const int first = (step & 7) == 0 ? (int)(blockIdx.x & 7) * (step >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
 
     if (wave >= ncons) {
         // ------------------------------------------------------------------ producer waves
@@ -738,7 +741,9 @@ slab_sym_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>:
     const int nwaves = blockDim.x >> 6;
     const int tiles = a.tiles_q;
     const int total = a.N * tiles;
-    const int first = blockIdx.x, step = gridDim.x;
+    // (XCD-aware: contiguous runs of work items per XCD, see slab_async_kernel)
+    const int step = gridDim.x;
+    const int first = (step & 7) == 0 ? (int)(blockIdx.x & 7) * (step >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     if (first >= total) return;
 
     // contiguous row range of this wave
@@ -890,7 +895,9 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     const int nprod = a.nprod;
     const int ncons = nwaves - nprod;
     const int units = a.N * a.tiles * a.ndt;        // (sample, tile, output-channel block)
-    const int first = blockIdx.x, step = gridDim.x;
+    // (XCD-aware: contiguous runs of work items per XCD, see slab_async_kernel)
+    const int step = gridDim.x;
+    const int first = (step & 7) == 0 ? (int)(blockIdx.x & 7) * (step >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     typedef const int16v __attribute__((address_space(4)))* c16_t;
     typedef const int32_t __attribute__((address_space(4)))* ci_t;
     const ci_t segs = (ci_t)seg_off;                // read through the constant address space
@@ -1029,7 +1036,9 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwaves = blockDim.x >> 6;
     const int units = a.N * a.tiles * a.ndt;        // (sample, tile, output-channel block)
-    const int first = blockIdx.x, step = gridDim.x;
+    // (XCD-aware: contiguous runs of work items per XCD, see slab_async_kernel)
+    const int step = gridDim.x;
+    const int first = (step & 7) == 0 ? (int)(blockIdx.x & 7) * (step >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     if (first >= units) return;
     auto decode = [&](int u, int& b, int& q0, int& dt) {
         const int bt = fdiv(u, a.inv_ndt);
@@ -1169,8 +1178,12 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 
     // workgroup -> (sample, tile, output-channel block); consecutive workgroups share the tile
     const int tiles = a.tiles_p * a.tiles_q;
-    const int bt = fdiv(blockIdx.x, a.inv_ndt);
-    const int dt = blockIdx.x - bt * a.ndt;
+    // (XCD-aware: workgroups are dealt round-robin to the 8 XCDs; number them so that each XCD gets
+    // a contiguous run, and the output-channel blocks of one tile share an L2)
+    const int grid = gridDim.x;
+    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int bt = fdiv(wg, a.inv_ndt);
+    const int dt = wg - bt * a.ndt;
     const int b = fdiv(bt, a.inv_tiles);
     const int t = bt - b * tiles;
     const int tpi = fdiv(t, a.inv_tiles_q);
