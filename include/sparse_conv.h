@@ -88,7 +88,9 @@ typedef struct {
     int32_t variant;    /* SC_VARIANT_* */
     int32_t wg_threads; /* workgroup size: 64..1024, multiple of 64 */
     int32_t sub_batch;  /* GATHER: output positions per thread that share each (theta, lambda) read
-                           from LDS (the role of sb_S), 1, 2, 4 or 8 */
+                           from LDS (the role of sb_S), 1, 2, 4 or 8.  SLAB with pipeline = 0 and
+                           chunk_c > 0: samples per workgroup (0 / 1 = one; 2..4 for tiles of at most
+                           64 positions, each scalar-loaded weight then feeds that many samples) */
     int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
     int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */

@@ -69,7 +69,7 @@ static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
 static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int producers,
-                          int chunk_c, int tile_d, int lds_budget, SlabGeom* g)
+                          int chunk_c, int tile_d, int samples, int lds_budget, SlabGeom* g)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -109,7 +109,13 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         o.rpw = (o.DTW + ncons - 1) / ncons;
         if (o.rpw > kMaxRowsPerWave) return false;
     }
-    const int64_t slab = (int64_t)o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
+    // several samples per workgroup: chunked one-shot form, tiles of at most one wave of positions
+    o.ns = 1;
+    if (samples > 1) {
+        if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
+        o.ns = samples;
+    }
+    const int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);
     // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
@@ -185,6 +191,9 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         const int budget = kMaxLdsBytes / t.wg_per_cu;
         SlabGeom g{};
         bool ok = false;
+        // sub_batch means samples per workgroup for the chunked one-shot form only
+        const int samples = (t.pipeline == 0 && t.chunk_c > 0) ? t.sub_batch : 0;
+        if (samples < 0 || samples > 4) return SC_ERR_UNSUPPORTED;
         if (t.tile_q == 0) {
             // heuristic: widest tile that fits; pointwise layers tile the flattened plane in
             // multiples of a wave, other layers take full rows and as many of them as fit
@@ -192,22 +201,22 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
             t.tile_p = g.TP;
             t.tile_q = g.TQ;
-            t.sub_batch = 0;
+            t.sub_batch = g.ns > 1 ? g.ns : 0;
             t.split_n = 0;
             if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
@@ -790,6 +799,28 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_q = tq;
                     t.chunk_c = cc;
                     t.tile_d = td;
+                    push(t);
+                }
+            }
+        }
+    }
+    // the same with several samples per workgroup, for planes of at most one wave of positions
+    if (p.dtype != SC_CB4_I8 && p.n > 0 && p.P * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 64) {
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 32, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                for (int ns : {2, 4}) {
+                    sc_tuning_t t{};
+                    t.variant = SC_VARIANT_SLAB;
+                    t.wsrc = 1;
+                    t.wg_per_cu = wpc;
+                    t.wg_threads = 1024;
+                    t.tile_p = pw ? 1 : p.P;
+                    t.tile_q = pw ? p.P * p.Q : p.Q;
+                    t.chunk_c = cc;
+                    t.tile_d = td;
+                    t.sub_batch = ns;
                     push(t);
                 }
             }

@@ -1155,7 +1155,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT>
+template <sc_dtype_t DT, int VPT, bool MS>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1184,8 +1184,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     const int bt = fdiv(wg, a.inv_ndt);
     const int dt = wg - bt * a.ndt;
-    const int b = fdiv(bt, a.inv_tiles);
-    const int t = bt - b * tiles;
+    const int bg = fdiv(bt, a.inv_tiles);
+    const int t = bt - bg * tiles;
+    // MS: the workgroup takes VPT samples of a tile of at most 64 positions (slot k of a lane is
+    // sample b + k); otherwise one sample, and slot k is position k * 64 + lane
+    const int b = MS ? bg * VPT : bg;
     const int tpi = fdiv(t, a.inv_tiles_q);
     const int tqi = t - tpi * a.tiles_q;
     const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
@@ -1196,12 +1199,14 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     int out_off[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const int f = k * 64 + lane;
+        const int f = MS ? lane : k * 64 + lane;
         const int tp = fdiv(f, a.inv_Qs);
         const int tq = f - tp * a.Qs;
-        const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf;
+        const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
         out_off[k] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
     }
+    const int img_elems = a.CC * a.chan_pitch;                       // one sample's chunk image
+    const int koff = MS ? img_elems * (int)sizeof(X) : 64 * (int)sizeof(X);
     const unsigned char* lane_base = lds + lane * (int)sizeof(X);
 
     // Offset of every element of one staged channel image inside the input plane, or -1 where the
@@ -1239,7 +1244,10 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
         if (ch > 0) __syncthreads();      // the previous chunk has been consumed
         // four elements per thread and pass, loads first, so that four loads are in flight
-        const X* xc = xb + (int64_t)c0 * plane;
+        for (int sm = 0; sm < (MS ? VPT : 1); ++sm) {
+        if (MS && b + sm >= a.N) break;
+        const X* xc = xb + (int64_t)sm * a.x_sample_stride + (int64_t)c0 * plane;
+        X* simg = slab + sm * img_elems;
         for (int e0 = tid; e0 < elems; e0 += 4 * nthreads) {
             X v[4];
 #pragma unroll
@@ -1255,8 +1263,9 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int e = e0 + u * nthreads;
-                if (e < elems) slab[e] = v[u];
+                if (e < elems) simg[e] = v[u];
             }
+        }
         }
         __syncthreads();                  // chunk staged
 #pragma unroll
@@ -1269,7 +1278,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                     const unsigned char* pj = lane_base + lam;
 #pragma unroll
                     for (int k = 0; k < VPT; ++k)
-                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * koff));
                 };
                 const int2* seg = wlc + s0;
                 int e = 0;
@@ -1294,18 +1303,20 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         if (r < nrows) {
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) yd[(int64_t)r * a.y_plane + out_off[k]] = narrow<DT>(acc[r][k]);
+                if (out_off[k] >= 0)
+                    yd[(int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k]] =
+                        narrow<DT>(acc[r][k]);
         }
     }
 }
 
-template <sc_dtype_t DT, int VPT>
+template <sc_dtype_t DT, int VPT, bool MS>
 static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                  hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1321,11 +1332,19 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
 template <sc_dtype_t DT>
 static sc_status_t launch_cc(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
+    if (p.geom.ns > 1) {
+        switch (p.geom.ns) {
+            case 2: return launch_cc_one<DT, 2, true>(p, a, x, y, grid, stream);
+            case 3: return launch_cc_one<DT, 3, true>(p, a, x, y, grid, stream);
+            case 4: return launch_cc_one<DT, 4, true>(p, a, x, y, grid, stream);
+        }
+        return SC_ERR_UNSUPPORTED;
+    }
     switch (p.geom.vpt) {
-        case 1: return launch_cc_one<DT, 1>(p, a, x, y, grid, stream);
-        case 2: return launch_cc_one<DT, 2>(p, a, x, y, grid, stream);
-        case 3: return launch_cc_one<DT, 3>(p, a, x, y, grid, stream);
-        case 4: return launch_cc_one<DT, 4>(p, a, x, y, grid, stream);
+        case 1: return launch_cc_one<DT, 1, false>(p, a, x, y, grid, stream);
+        case 2: return launch_cc_one<DT, 2, false>(p, a, x, y, grid, stream);
+        case 3: return launch_cc_one<DT, 3, false>(p, a, x, y, grid, stream);
+        case 4: return launch_cc_one<DT, 4, false>(p, a, x, y, grid, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }
@@ -1613,7 +1632,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     if (p.tuning.chunk_c > 0) {
         a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt;
         a.inv_ndt = 1.0f / (float)g.ndt;
-        const int64_t gridc = grid64 * g.ndt;
+        const int64_t gridc = (int64_t)((N + g.ns - 1) / g.ns) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {
             case SC_F32: return launch_cc<SC_F32>(p, a, x, y, (int)gridc, stream);

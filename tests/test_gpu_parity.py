@@ -29,6 +29,10 @@ def _both_variants(plan):
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 256}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
                                                 "tile_q": 1000}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 256, "tile_p": 3,
+                                                "tile_q": 16, "sub_batch": 2}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 128, "tile_p": 4,
+                                                "tile_q": 8, "sub_batch": 3}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
