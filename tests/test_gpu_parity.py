@@ -337,3 +337,53 @@ def test_resnet_layers_full_batch_sampled(dtype):
         for b in (0, l.N - 1):
             ref = G.oracle_out(l, data, samples=[b])
             G.check(l, y[b:b + 1], ref, f"{l.name} sample {b}")
+
+
+def test_headline_layer_full_size_as_benchmarked():
+    """The benchmark's layer at full size in the launch shape the benchmark times: autotuned, then
+    the oracle checks the first and the last sample completely; also the three persistent kernel
+    families pinned explicitly."""
+    import torch
+    l = wl.headline_layer()
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    x = G.to_device(data["x"])
+    y = torch.empty((l.N, l.D, l.P, l.Q), device="cuda")
+    ws = torch.empty(max(plan.workspace_size_max(l.N), 1), dtype=torch.uint8, device="cuda")
+    plan.autotune(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(),
+                  torch.cuda.current_stream().cuda_stream)
+    refs = {b: G.oracle_out(l, data, samples=[b]) for b in (0, l.N - 1)}
+    tuned = plan.get_tuning().as_dict()
+    print("autotuned", tuned, flush=True)
+    assert tuned["variant"] == B.SC_VARIANT_SLAB and tuned["pipeline"] >= 1
+    y = G.run_gpu(plan, data["x"])
+    for b, ref in refs.items():
+        G.check(l, y[b:b + 1], ref, f"autotuned {tuned} sample {b}")
+    for extra in ({"pipeline": 1, "producers": 1, "tile_q": 64}, {"pipeline": 2, "tile_q": 64},
+                  {"pipeline": 1, "producers": 2, "tile_q": 256, "chunk_c": 64},
+                  {"pipeline": 2, "tile_q": 128, "chunk_c": 128}):
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, **extra)
+        y = G.run_gpu(plan, data["x"])
+        for b, ref in refs.items():
+            G.check(l, y[b:b + 1], ref, f"{extra} sample {b}")
+
+
+@pytest.mark.parametrize("name,extra", [
+    ("s28_conv3x3_s2_sp90", {"tile_p": 4, "chunk_c": 64, "wg_per_cu": 1}),
+    ("s14_conv3x3_sp90", {"tile_p": 7, "chunk_c": 128, "tile_d": 128, "wg_per_cu": 2}),
+    ("s7_conv3x3_sp90", {"tile_p": 7, "chunk_c": 64, "tile_d": 128, "sub_batch": 2}),
+    ("s7_expand1x1_sp90", {"tile_p": 1, "tile_q": 49, "chunk_c": 128, "tile_d": 128, "sub_batch": 4, "wg_per_cu": 1}),
+    ("s14_reduce1x1_sp90", {"tile_p": 1, "tile_q": 128, "chunk_c": 128, "tile_d": 128, "pipeline": 2}),
+])
+def test_full_size_layers_through_the_chunked_kernels(name, extra):
+    """Full-size ResNet-50-shaped layers (batch 32) through the channel-chunked kernels with
+    output-channel blocks and several samples per workgroup; first and last sample checked."""
+    l = {x.name: x for x in wl.config3()}[name]
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, **extra)
+    t = plan.get_tuning().as_dict()
+    assert t["chunk_c"] == extra["chunk_c"]
+    y = G.run_gpu(plan, data["x"])
+    for b in (0, l.N - 1):
+        G.check(l, y[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{name} {t} sample {b}")
