@@ -11,7 +11,18 @@
 // registers; one store per output value.  lambda here is the offset pre-stretched for the tile's
 // LDS layout (see SlabGeom), already scaled to bytes.
 //
-// (theta, lambda) reaches the lanes in one of three ways (tuning.wsrc):
+// Kernels in this file (all follow the paper's "Convolution operation using a sparse operation on
+// GPGPU": output = sum over the stored (theta, lambda) entries of a row of theta * input[base +
+// lambda], with the unified number of entries per row):
+//   slab_kernel        one tile, every input channel resident, one shot
+//   slab_cc_kernel     one tile, input channels staged chunk by chunk, accumulators kept in
+//                      registers across the chunks; output-channel blocks; several samples per tile
+//   slab_async_kernel  pointwise layers: persistent workgroups, two tile buffers, producer waves
+//                      copy tile i+1 with direct-to-LDS loads while consumer waves multiply tile i
+//   slab_chunk_kernel  the same with channel chunks
+//   slab_sym_kernel / slab_symc_kernel   the same without dedicated producer waves
+//
+// (theta, lambda) reaches the lanes in one of four ways (tuning.wsrc):
 //   0  rows are staged in LDS in groups (decoding 4-bit codebook indices on the way) and read back
 //      with wave-uniform (broadcast) LDS reads, as Algorithm 3 does from shared memory;
 //   1  rows are read with scalar loads from a pre-expanded {theta32, lambda} table in global
@@ -640,7 +651,6 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int EPV = 16 / (int)sizeof(X);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
