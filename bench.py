@@ -2,7 +2,7 @@
 """Benchmark of the direct sparse convolution hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer NAME] [--no-autotune]
-                    [--report PATH]   # optional per-layer table over all five configs (PATH, PATH.txt)
+                    [--report PATH]   # optional per-layer table over all workload configs (PATH, PATH.txt)
 
 One *step* is one pass of the hot path over one batch of synthetic input: sparse_conv_forward of
 the headline layer (largest ResNet-50-shaped layer at 90 % sparsity: the stage-1 1x1 reduce,
@@ -184,7 +184,7 @@ def main():
 
     l = wl.headline_layer()
     if args.layer:
-        l = {x.name: x for c in (3, 4, 2, 5, 1) for x in wl.CONFIGS[c]()}[args.layer]
+        l = {x.name: x for c in (3, 4, 2, 5, 1, 6) for x in wl.CONFIGS[c]()}[args.layer]
     res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
                                 tuning=json.loads(args.tuning) if args.tuning else None)
 
@@ -214,7 +214,7 @@ def main():
 
     if args.report:
         rows = []
-        for cfg in (1, 2, 3, 4, 5):
+        for cfg in (1, 2, 3, 4, 5, 6):
             for lay in wl.CONFIGS[cfg]():
                 r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl)
                 p.destroy()

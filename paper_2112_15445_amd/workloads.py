@@ -160,7 +160,23 @@ def config5() -> List[Layer]:
     return _vgg(5, "i8", [0.9] * 13) + [l.replace(name=l.name + "_cb4") for l in _vgg(5, "cb4", [0.9] * 13)]
 
 
-CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+def config6() -> List[Layer]:
+    """The 1-D convolution workload (Table 8 of the paper: "CNN 1D for input 300x64", kernel sizes
+    2x1 and 3x1, sparsities 77 / 83 / 87.5 %, batch 128, float and half).  Reading taken: 300 input
+    channels (embedding width), sequence length 64, 64 output channels, the kernel running along
+    the sequence; laid out as H = 1, W = 64, R = 1, S = 2 or 3."""
+    out = []
+    for di, dtype in enumerate(("f32", "f16")):
+        for ki, k in enumerate((2, 3)):
+            for si, sp in enumerate((0.77, 0.83, 0.875)):
+                pct = ("%g" % (sp * 100)).replace(".", "p")
+                out.append(Layer(f"cnn1d_300x64_k{k}_sp{pct}" + ("_f16" if dtype == "f16" else ""),
+                                 300, 64, 1, 64, 1, k, 1, 1, 0, 0, N=128, sparsity=sp, dtype=dtype,
+                                 seed=BASE_SEED + 6000 + 100 * di + 10 * ki + si))
+    return out
+
+
+CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6}
 
 
 def headline_layer() -> Layer:

@@ -387,3 +387,23 @@ def test_full_size_layers_through_the_chunked_kernels(name, extra):
     y = G.run_gpu(plan, data["x"])
     for b in (0, l.N - 1):
         G.check(l, y[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{name} {t} sample {b}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_one_dimensional_convolution_workload(dtype):
+    """The 1-D convolution layers (300 channels, length 64, kernels 2 and 3, batch 128) at full
+    size, autotuned; the oracle checks three samples completely."""
+    import torch
+    for l in [x for x in wl.config6() if x.dtype == dtype]:
+        data = wl.prepare(l)
+        plan = G.make_plan(l, data)
+        x = G.to_device(data["x"])
+        y = torch.empty((l.N, l.D, l.P, l.Q), device="cuda", dtype=B.torch_out_dtype(plan.dtype))
+        ws = torch.empty(max(plan.workspace_size_max(l.N), 1), dtype=torch.uint8, device="cuda")
+        plan.autotune(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(),
+                      torch.cuda.current_stream().cuda_stream)
+        t = plan.get_tuning().as_dict()
+        print("case", l.name, t, flush=True)
+        out = G.run_gpu(plan, data["x"])
+        for b in (0, 77, l.N - 1):
+            G.check(l, out[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{l.name} {t} sample {b}")

@@ -58,3 +58,12 @@ def test_quantisers():
     mid = 0.5 * (cent[3] + cent[4])
     assert wl.assign_codebook(np.array([cent[5], mid]), cent).tolist() in ([5, 3], [5, 4])
     assert wl.assign_codebook(np.array([0.0]), cent).tolist() == [7]
+
+
+def test_one_dimensional_workload_shapes():
+    ls = wl.config6()
+    assert len(ls) == 12 and {l.dtype for l in ls} == {"f32", "f16"}
+    l = ls[0]
+    assert (l.C, l.D, l.H, l.W, l.R, l.S, l.N) == (300, 64, 1, 64, 1, 2, 128)
+    assert (l.P, l.Q) == (1, 63) and l.K == 600
+    assert [x.n for x in ls[:6]] == [138, 102, 75, 207, 153, 113]      # 77 / 83 / 87.5 % of 600 and 900
