@@ -13,7 +13,8 @@ rotates over a ring of input/output buffers larger than twice the 256 MB Infinit
 every launch really streams from HBM.
 
 Prints ONE JSON line: metric / value / unit (useful GFLOP/s of the layer), ms_per_step, config
-(workload and launch shape), roofline (algorithmic bytes per launch over the measured kernel time,
+(workload and launch shape), timing_spread (median / min / max of ten short cold runs and a
+cache-warm run, for context), roofline (algorithmic bytes per launch over the measured kernel time,
 against the 8 TB/s HBM peak), the dense MIOpen time of the same layer for context, and
 cpu_baseline (the CPU oracle timed on the host cores).
 """
@@ -75,6 +76,16 @@ def _time_steps(plan, xs, ys, ws, N, steps, warmup, torch):
     return wall_ms / steps, e0.elapsed_time(e1) / steps
 
 
+def _spread(plan, xs, ys, ws, N, torch, repeats=10, launches=100):
+    """Median / min / max of `repeats` short timed runs over the cold ring, and one cache-warm run
+    (a single buffer pair launched back to back): context for the headline figure."""
+    import statistics
+    vals = [_time_steps(plan, xs, ys, ws, N, launches, 5, torch)[1] for _ in range(repeats)]
+    warm = _time_steps(plan, xs[:1], ys[:1], ws, N, launches, 5, torch)[1]
+    return {"repeats": repeats, "launches_per_repeat": launches, "median_ms": statistics.median(vals),
+            "min_ms": min(vals), "max_ms": max(vals), "cache_warm_ms": warm}
+
+
 def _dense_reference_ms(l, torch, reps=30):
     """Dense MIOpen convolution of the same layer (torch conv2d), cache-warm, for context."""
     dt = {"f32": torch.float32, "f16": torch.float16}.get(l.dtype)
@@ -114,7 +125,7 @@ def _cpu_baseline(l, data, oracle, max_samples):
             "in all, includes the oracle's widening to double and its padded copy)"}
 
 
-def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuning=None):
+def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuning=None, spread=False):
     data = wl.prepare(l)
     plan = G.make_plan(l, data)
     if tuning:
@@ -140,6 +151,8 @@ def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuni
     }
     if with_dense:
         out["dense_miopen_ms"] = _dense_reference_ms(l, torch)
+    if spread:
+        out["spread"] = _spread(plan, xs, ys, ws, l.N, torch)
     return out, data, plan
 
 
@@ -186,7 +199,7 @@ def main():
     if args.layer:
         l = {x.name: x for c in (3, 4, 2, 5, 1, 6) for x in wl.CONFIGS[c]()}[args.layer]
     res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
-                                tuning=json.loads(args.tuning) if args.tuning else None)
+                                tuning=json.loads(args.tuning) if args.tuning else None, spread=True)
 
     line = {
         "metric": "useful GFLOP/s (nnz MACs) per sparse conv layer",
@@ -203,6 +216,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(l.name),
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
                      "kernel_ms": res["ms_events"]},
+        "timing_spread": res.get("spread"),
         "dense_miopen_ms": res.get("dense_miopen_ms"),
         "sparse_vs_dense_speedup": (res["dense_miopen_ms"] / res["ms_events"]
                                     if res.get("dense_miopen_ms") else None),
