@@ -222,7 +222,10 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
             Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+                if (out_off[k] >= 0) {
+                    if constexpr (DT == SC_F32) __builtin_nontemporal_store(acc[k], yd + out_off[k]);
+                    else yd[out_off[k]] = narrow<DT>(acc[k]);
+                }
         }
         return;
     }
@@ -546,7 +549,7 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, unsig
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                          : : "v"(lane_off), "s"(base), "s"(l) : "memory");
     } else {
-        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 0);
+        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 2);
         else __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 4, 0, 0);
     }
 }
