@@ -103,7 +103,7 @@ gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restri
         A v = acc[k];
 #pragma unroll
         for (int m = NSPLIT / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-        if (slice == 0 && yoff[k] >= 0) y[yoff[k]] = narrow<DT>(v);
+        if (slice == 0 && yoff[k] >= 0) store_out(y + yoff[k], narrow<DT>(v));
     }
 }
 

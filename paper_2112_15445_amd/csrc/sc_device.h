@@ -46,4 +46,20 @@ template <sc_dtype_t DT> __device__ inline typename Types<DT>::Y narrow(typename
     else return v;
 }
 
+// Output values are written once and never read back by the kernels: store them with the
+// non-temporal hint so that they do not displace the input stream from the caches.
+__device__ inline void store_out(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ inline void store_out(int32_t* p, int32_t v) { __builtin_nontemporal_store(v, p); }
+__device__ inline void store_out(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+__device__ inline void store_out(__half* p, __half v)
+{
+    __builtin_nontemporal_store(__half_as_ushort(v), reinterpret_cast<unsigned short*>(p));
+}
+__device__ inline void store_out4(int32_t* p, int32_t a, int32_t b, int32_t c, int32_t d)
+{
+    typedef int int4v __attribute__((ext_vector_type(4)));
+    int4v v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<int4v*>(p));
+}
+
 }  // namespace sc

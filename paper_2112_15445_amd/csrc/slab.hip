@@ -182,7 +182,7 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
             Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc3[k]);
+                if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc3[k]));
         }
         return;
     }
@@ -222,10 +222,7 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
             Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) {
-                    if constexpr (DT == SC_F32) __builtin_nontemporal_store(acc[k], yd + out_off[k]);
-                    else yd[out_off[k]] = narrow<DT>(acc[k]);
-                }
+                if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[k]));
         }
         return;
     }
@@ -275,7 +272,7 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
         Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
         for (int k = 0; k < VPT; ++k)
-            if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+            if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[k]));
     }
 }
 
@@ -340,10 +337,9 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
                 if constexpr (DT == SC_F16) {
                     const uint32_t lo = __half_as_ushort(__float2half(acc[k][0]));
                     const uint32_t hi = __half_as_ushort(__float2half(acc[k][1]));
-                    *reinterpret_cast<uint32_t*>(yd + out_off[k]) = lo | (hi << 16);
+                    store_out(reinterpret_cast<uint32_t*>(yd + out_off[k]), lo | (hi << 16));
                 } else {
-                    *reinterpret_cast<int4*>(yd + out_off[k]) =
-                        make_int4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+                    store_out4(yd + out_off[k], acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
                 }
             }
         }
@@ -511,7 +507,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
                     Y* yd = yb + (int64_t)(ds0 + dd) * a.y_plane;
 #pragma unroll
                     for (int k = 0; k < VPT; ++k)
-                        if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+                        if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[k]));
                 }
             }
             j0 += a.JC;
@@ -532,6 +528,8 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+// (All copies carry the non-temporal hint: the input is streamed once, and keeping it out of the
+// caches is worth 10 % of the kernel time on the HBM-bound layers.)
 // One copy instruction: BYTES (16 or 4) per lane from base + lane_off (base wave-uniform) to the
 // LDS image at dst + BYTES * lane.  HAND = true issues it as inline assembly, which keeps it out of
 // the compiler's bookkeeping: a wave that both copies tile i+1 and reads tile i would otherwise be
@@ -543,14 +541,14 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, unsig
     if constexpr (HAND) {
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
         if constexpr (BYTES == 16)
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
                          : : "v"(lane_off), "s"(base), "s"(l) : "memory");
         else
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 nt"
                          : : "v"(lane_off), "s"(base), "s"(l) : "memory");
     } else {
         if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 2);
-        else __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 4, 0, 0);
+        else __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 4, 0, 2);
     }
 }
 template <bool HAND, int BYTES>
@@ -559,14 +557,14 @@ __device__ __forceinline__ void dma16_ptr(const void* src, unsigned char* dst)
     if constexpr (HAND) {
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
         if constexpr (BYTES == 16)
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
                          : : "v"(src), "s"(l) : "memory");
         else
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off nt"
                          : : "v"(src), "s"(l) : "memory");
     } else {
-        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
-        else __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 4, 0, 0);
+        if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 2);
+        else __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 4, 0, 2);
     }
 }
 
@@ -828,7 +826,7 @@ slab_sym_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>:
             if (r == nrows - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[k]);
+                if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[k]));
             yd += a.y_plane;
         }
     }
@@ -1013,7 +1011,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
                 Y* yd = yb + (int64_t)d * a.y_plane;
 #pragma unroll
                 for (int k = 0; k < VPT; ++k)
-                    if (out_off[k] >= 0) yd[out_off[k]] = narrow<DT>(acc[r][k]);
+                    if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[r][k]));
             }
         }
     }
@@ -1128,7 +1126,8 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
 #pragma unroll
                 for (int k = 0; k < VPT; ++k) {
                     const int f = k * 64 + lane;
-                    if (f < a.TQ && q0 + f < a.Wf) yd[(int64_t)r * a.y_plane + q0 + f] = narrow<DT>(acc[r][k]);
+                    if (f < a.TQ && q0 + f < a.Wf)
+                        store_out(yd + (int64_t)r * a.y_plane + q0 + f, narrow<DT>(acc[r][k]));
                 }
             }
         }
@@ -1317,8 +1316,8 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
                 if (out_off[k] >= 0)
-                    yd[(int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k]] =
-                        narrow<DT>(acc[r][k]);
+                    store_out(yd + (int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k],
+                              narrow<DT>(acc[r][k]));
         }
     }
 }
