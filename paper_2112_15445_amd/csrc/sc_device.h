@@ -46,6 +46,14 @@ template <sc_dtype_t DT> __device__ inline typename Types<DT>::Y narrow(typename
     else return v;
 }
 
+// An input element that the kernel reads once: load it with the non-temporal hint.
+__device__ inline float load_in(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ inline int8_t load_in(const int8_t* p) { return __builtin_nontemporal_load(p); }
+__device__ inline __half load_in(const __half* p)
+{
+    return __ushort_as_half(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(p)));
+}
+
 // Output values are written once and never read back by the kernels: store them with the
 // non-temporal hint so that they do not displace the input stream from the caches.
 __device__ inline void store_out(float* p, float v) { __builtin_nontemporal_store(v, p); }

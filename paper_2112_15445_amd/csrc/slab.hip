@@ -419,7 +419,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
                 if (e < a.slab_elems) {
                     const int c = fdiv(e, a.inv_chan_pitch);
                     const int o = tab[e - c * a.chan_pitch];
-                    if (o >= 0) v[u] = xb[(int64_t)c * plane + o];
+                    if (o >= 0) v[u] = load_in(xb + (int64_t)c * plane + o);
                 }
             }
 #pragma unroll
