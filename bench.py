@@ -171,6 +171,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark, run 20 plain 256 MiB device copies (the known-size "
                          "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled against)")
+    ap.add_argument("--ragged-study", action="store_true",
+                    help="instead of the benchmark, time a few layers whose rows have uneven lengths with the "
+                         "unified table and with the ragged one (tuning.ragged), same launch shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path would shard over the batch with "
@@ -193,6 +196,30 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "20 x elementwise copy kernel, 268435456 bytes read + "
                                          "268435456 bytes written per launch"}))
+        return
+
+    if args.ragged_study:
+        import numpy as np
+        cases = [("s28_conv3x3_sp90", {"tile_p": 4, "chunk_c": 64, "wg_per_cu": 2}),
+                 ("s14_conv3x3_sp90", {"tile_p": 7, "chunk_c": 128, "tile_d": 128, "wg_per_cu": 2}),
+                 ("s28_conv3x3_s2_sp90", {"tile_p": 4, "chunk_c": 64, "wg_per_cu": 1}),
+                 ("s56_reduce1x1_sp90", {"pipeline": 1, "producers": 2, "tile_q": 256, "chunk_c": 64}),
+                 ("s14_reduce1x1_sp90", {"pipeline": 2, "tile_q": 128, "chunk_c": 128, "tile_d": 128})]
+        print("layer                  longest row / mean row   unified_us  ragged_us  ratio   launch shape")
+        for name, extra in cases:
+            l = {x.name: x for x in wl.config3()}[name]
+            data = wl.prepare(l, ragged=True)            # row lengths uniform in [0, n]
+            lens = np.diff(data["rowptr"])
+            plan = G.make_plan(l, data)
+            xs, ys = _ring(plan, data, l, torch, G, B)
+            us = []
+            for ragged in (0, 1):
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024,
+                                ragged=ragged, **extra)
+                us.append(_time_steps(plan, xs, ys, None, l.N, 300, 20, torch)[1] * 1e3)
+            print(f"{name:22s} {lens.max():8d} / {lens.mean():7.1f}       {us[0]:9.2f}  {us[1]:9.2f}  "
+                  f"{us[0] / us[1]:5.2f}x   {json.dumps(extra)}", flush=True)
+            plan.destroy()
         return
 
     l = wl.headline_layer()
@@ -239,6 +266,16 @@ def main():
         with open(args.report, "w") as f:
             json.dump(rows, f, indent=1)
         with open(args.report + ".txt", "w") as f:      # the same rows as a table
+            # per-layer choice between the sparse kernel and the dense library (the paper's main
+            # scheme, steps 3-4: compare layer times, then configure the network)
+            for cfg in sorted({r["config"] for r in rows}):
+                rs = [r for r in rows if r["config"] == cfg and r.get("dense_miopen_ms")]
+                if rs:
+                    sp = sum(r["ms_events"] for r in rs) * 1e3
+                    de = sum(r["dense_miopen_ms"] for r in rs) * 1e3
+                    di = sum(min(r["ms_events"], r["dense_miopen_ms"]) for r in rs) * 1e3
+                    f.write(f"# config {cfg}: sum over {len(rs)} layers: all sparse {sp:.1f} us, all dense {de:.1f} us, "
+                            f"faster of the two per layer {di:.1f} us\n")
             f.write("cfg layer                      dtype    n   sparse_us  alg_GB/s  hbm_frac  useful_TF  "
                     "dense_us  launch shape\n")
             for r in rows:

@@ -115,6 +115,10 @@ typedef struct {
                            accumulators of its output channels in registers across the chunks, so
                            wide tiles fit LDS even for layers with many input channels */
     int32_t tile_d;     /* SLAB with chunk_c > 0: output channels per workgroup (0 = all of them) */
+    int32_t ragged;     /* SLAB with chunk_c > 0: 1 = walk every row over its own stored entries only (the
+                           filler entries that unify the row lengths are left out of the per-chunk
+                           segments), 0 = the unified table of the method.  For measuring what the
+                           padding costs on tables whose rows differ in length */
 } sc_tuning_t;
 
 typedef struct {

@@ -182,6 +182,8 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.pipeline != 1) t.producers = 0;
     if (t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.tile_d = 0;
+    if (t.ragged < 0 || t.ragged > 1) return SC_ERR_UNSUPPORTED;
+    if (t.chunk_c == 0) t.ragged = 0;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
@@ -234,7 +236,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n == 0) t.split_n = 1;
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
-    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = 0;
+    t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = t.ragged = 0;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -275,6 +277,7 @@ static sc_status_t validate_layer(const sc_layer_t* L, sc_dtype_t dt, const floa
 // Copy of the caller's values as raw native-width elements, unified to [D][n] with rows sorted by
 // column (stable, so equal columns keep the caller's order).
 struct HostTable {
+    std::vector<int32_t> len;  // stored entries per row before unification
     std::vector<int32_t> col;
     std::vector<uint8_t> val;  // native element bytes: 4 / 2 / 1 / 1 (index)
 };
@@ -287,9 +290,11 @@ static sc_status_t unify_rows(const Plan& p, const int32_t* rowptr, const int32_
     const uint8_t* v = static_cast<const uint8_t*>(values);
     t->col.assign((size_t)D * n, 0);
     t->val.assign((size_t)D * n * wsz, 0);
+    t->len.assign((size_t)D, 0);
     std::vector<int32_t> order;
     for (int d = 0; d < D; ++d) {
         const int64_t beg = rowptr[d], len = (int64_t)rowptr[d + 1] - rowptr[d];
+        t->len[d] = (int32_t)len;
         for (int64_t k = beg; k < beg + len; ++k) {
             if (colidx[k] < 0 || colidx[k] >= K) return SC_ERR_CSR;
             if (p.dtype == SC_CB4_I8 && v[k] > 15) return SC_ERR_CSR;
@@ -365,7 +370,9 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
                     seg_off[(size_t)d * nch + ch] = (int32_t)total;
                     first_j[(size_t)d * nch + ch] = j;
                     int cnt = 0;
-                    while (j < p->n && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt; }
+                    // (ragged: the fillers, which sit behind the row's own entries, are left out)
+                    const int jend = t.ragged ? p->h_len[d] : p->n;
+                    while (j < jend && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt; }
                     total += (cnt + pad - 1) / pad * pad;
                 }
             }
@@ -401,6 +408,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     const int wsz = elem_size_w_native(p->dtype);
     p->np = (p->n + 1) / 2 * 2;
     p->h_col = std::move(tab.col);
+    p->h_len = std::move(tab.len);
     // resolve the default tuning first: it is pure host arithmetic
     // default launch shape before any autotune: the slab kernel with 16 waves per workgroup and
     // weights by scalar loads where the layer allows it, otherwise whatever the heuristic resolves

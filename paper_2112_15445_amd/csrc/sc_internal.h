@@ -59,6 +59,7 @@ struct Plan {
     int64_t true_nnz = 0;
     int ex = 4, ey = 4;             // bytes per input / output element
     std::vector<int32_t> h_col;     // [D*n] unified table, columns ascending per row
+    std::vector<int32_t> h_len;     // [D] stored entries of every row before unification
     int32_t* d_col = nullptr;       // [D*n]
     void* d_theta = nullptr;        // [D*n] f32 | f16 | i8, or ceil(D*n/2) bytes of packed 4-bit indices
     int32_t* d_lam = nullptr;       // [D*n] canonical offsets (elements into one padded sample)

@@ -858,8 +858,12 @@ expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict_
     const int d = (int)(i / n), j = (int)(i - (int64_t)d * n);
     const int ch = ((col[i] & 0x7fffffff) / RS) / CC;
     const int l = lam[i];
-    const int64_t dst = (int64_t)seg_off[(int64_t)d * nch + ch] + (j - first_j[(int64_t)d * nch + ch]);
-    out[dst] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
+    const int64_t si = (int64_t)d * nch + ch;
+    const int k = j - first_j[si];
+    // (a segment built without the fillers is shorter than the entries that map to its chunk: the
+    // fillers behind it are dropped; one that lands on a padding slot is a zero weight either way)
+    if (k >= seg_off[si + 1] - seg_off[si]) return;
+    out[(int64_t)seg_off[si] + k] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
 }
 
 sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream)

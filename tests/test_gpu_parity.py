@@ -407,3 +407,31 @@ def test_one_dimensional_convolution_workload(dtype):
         out = G.run_gpu(plan, data["x"])
         for b in (0, 77, l.N - 1):
             G.check(l, out[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{l.name} {t} sample {b}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_ragged_table_option_matches_the_unified_result(dtype):
+    """Rows of different lengths walked over their own entries only (tuning.ragged = 1, the filler
+    entries left out of the per-chunk segments) through the three chunked kernels: the result is
+    the oracle's, as for the unified table."""
+    for l in (wl.Layer("rag3x3", 20, 36, 14, 14, 3, 3, 2, 2, 1, 1, N=5, sparsity=0.7, dtype=dtype, seed=21),
+              wl.Layer("rag1x1", 48, 24, 16, 16, 1, 1, 1, 1, 0, 0, N=9, sparsity=0.6, dtype=dtype, seed=22)):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        ran = 0
+        for extra in ({"chunk_c": 6, "tile_p": 4, "tile_d": 16}, {"chunk_c": 16, "tile_p": 2, "sub_batch": 2},
+                      {"chunk_c": 16, "pipeline": 1, "tile_q": 128, "producers": 1},
+                      {"chunk_c": 12, "pipeline": 2, "tile_q": 64, "tile_d": 8}):
+            for ragged in (0, 1):
+                try:
+                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=512,
+                                    ragged=ragged, **extra)
+                except B.SparseConvError as e:
+                    assert e.status == 4
+                    continue
+                t = plan.get_tuning().as_dict()
+                assert t["ragged"] == ragged
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+                ran += 1
+        assert ran >= 4
