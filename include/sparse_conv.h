@@ -119,6 +119,10 @@ typedef struct {
                            filler entries that unify the row lengths are left out of the per-chunk
                            segments), 0 = the unified table of the method.  For measuring what the
                            padding costs on tables whose rows differ in length */
+    int32_t pack;       /* SLAB with pipeline = 0 and chunk_c > 0, SC_F16 / SC_I8, one sample per workgroup:
+                           1 = every lane owns the 2 (f16) or 4 (i8) adjacent positions of one 32-bit word
+                           of the staged tile, so one LDS read feeds that many multiply-adds (at most 8
+                           positions per lane); 0 = one position per LDS read */
 } sc_tuning_t;
 
 typedef struct {

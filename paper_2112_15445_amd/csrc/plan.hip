@@ -69,7 +69,7 @@ static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
 static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int producers,
-                          int chunk_c, int tile_d, int samples, int lds_budget, SlabGeom* g)
+                          int chunk_c, int tile_d, int samples, int pack, int lds_budget, SlabGeom* g)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -92,6 +92,15 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.F = o.TP * o.Qs;
     if (o.F > kWave * kMaxVpt) return false;
     o.vpt = (o.F + kWave - 1) / kWave;
+    o.pack = 1;
+    if (pack) {
+        // packed positions: chunked forms, 16- or 8-bit activations, one sample per workgroup;
+        // a lane owns `pack` adjacent positions per 32-bit word, at most 8 positions
+        if (chunk_c <= 0 || samples > 1 || (p.dtype != SC_F16 && p.dtype != SC_I8)) return false;
+        o.pack = 4 / p.ex;
+        o.vpt = (o.F + kWave * o.pack - 1) / (kWave * o.pack);
+        if (o.vpt * o.pack > 8) return false;
+    }
     o.nwaves = wg_threads / kWave;
     o.CC = chunk_c > 0 ? std::min(chunk_c, L.C) : L.C;
     o.nchunks = (L.C + o.CC - 1) / o.CC;
@@ -105,7 +114,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if ((!pw && pipeline >= 1) || wsrc != 1 || p.dtype == SC_CB4_I8 || p.n == 0) return false;
         const int ncons = o.nwaves - (pipeline == 1 ? producers : 0);
         if (ncons < 1) return false;
-        if (pipeline != 1 && o.vpt > 4) return false;
+        if (pipeline != 1 && o.vpt * o.pack > (pack ? 8 : 4)) return false;
         o.rpw = (o.DTW + ncons - 1) / ncons;
         if (o.rpw > kMaxRowsPerWave) return false;
     }
@@ -115,7 +124,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
         o.ns = samples;
     }
-    const int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * p.ex;
+    const int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);
     // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
@@ -161,6 +170,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.dmab = o.vec ? 16 : ((pw && (o.Wf % epd == 0) && (o.TQ % epd == 0)) ? 4 : 0);
     if (pipeline == 1 && !o.vec) return false;
     if (pipeline == 2 && o.dmab == 0) return false;
+    if (pack && pipeline >= 1 && o.dmab == 0) return false;      // whole words per row and tile
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -184,6 +194,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.chunk_c == 0) t.tile_d = 0;
     if (t.ragged < 0 || t.ragged > 1) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.ragged = 0;
+    if (t.pack < 0 || t.pack > 1) return SC_ERR_UNSUPPORTED;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
@@ -203,16 +214,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
@@ -237,6 +248,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
     t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = t.ragged = 0;
+    if (t.pack) return SC_ERR_UNSUPPORTED;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -688,6 +700,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     const bool pw = is_pointwise(p.L);
+    const bool packable = p.dtype == SC_F16 || p.dtype == SC_I8;   // tuning.pack applies
     if (pw && p.dtype != SC_CB4_I8) {
         for (int threads : {512, 768, 1024}) {
             for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
@@ -737,6 +750,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.chunk_c = cc;
                 t.tile_d = td;
                 push(t);
+                if (packable) { t.pack = 1; push(t); t.tile_q = 2 * tq; push(t); }
             }
         }
     }
@@ -757,6 +771,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.chunk_c = cc;
                 t.tile_d = td;
                 push(t);
+                if (packable) { t.pack = 1; push(t); }
             }
         }
     }
@@ -850,6 +865,29 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_q = p.Q;
                     t.chunk_c = cc;
                     t.tile_d = td;
+                    push(t);
+                }
+            }
+        }
+    }
+    // 16- and 8-bit activations: the chunked one-shot form with packed positions (one LDS read per
+    // 2 or 4 positions), tiles of up to 8 positions per lane
+    if ((p.dtype == SC_F16 || p.dtype == SC_I8) && p.n > 0) {
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
+            if (cc > p.L.C && cc != 16) continue;
+            for (int td : {0, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                for (int tile : {2, 4, 7, 8, 14, 16, 28}) {
+                    sc_tuning_t t{};
+                    t.variant = SC_VARIANT_SLAB;
+                    t.wsrc = 1;
+                    t.wg_per_cu = wpc;
+                    t.wg_threads = 1024;
+                    t.tile_p = pw ? 1 : tile;
+                    t.tile_q = pw ? 32 * tile : p.Q;     // pointwise: 64 .. 512 (and 224, 896 -> clipped by the fit)
+                    t.chunk_c = cc;
+                    t.tile_d = td;
+                    t.pack = 1;
                     push(t);
                 }
             }

@@ -132,6 +132,45 @@ __device__ inline void load_pair(int* o, const int2* __restrict__ wl32, __amdgpu
     }
 }
 
+// One (theta, lambda) entry applied to one slot of a lane.  E = 1: the slot is one position.
+// E > 1: the slot is a 32-bit word of E adjacent positions (2 halves or 4 bytes), so one LDS read
+// feeds E multiply-adds.
+template <sc_dtype_t DT, int E>
+__device__ __forceinline__ void mac_slot(typename Types<DT>::A (&acc)[E], typename Types<DT>::WL w,
+                                         const unsigned char* p)
+{
+    using X = typename Types<DT>::X;
+    if constexpr (E == 1) {
+        acc[0] += w * widen<DT>(*reinterpret_cast<const X*>(p));
+    } else {
+        // (the word is aligned only when lambda is a multiple of E elements; memcpy leaves that open)
+        uint32_t xd;
+        __builtin_memcpy(&xd, p, 4);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if constexpr (DT == SC_F16)
+                acc[e] += w * __half2float(__ushort_as_half((unsigned short)(xd >> (16 * e))));
+            else
+                acc[e] += w * (int32_t)(int8_t)(xd >> (8 * e));
+        }
+    }
+}
+
+// The E results of a slot leave as one store: 2 halves as one 32-bit word, 4 int32 as 16 bytes.
+template <sc_dtype_t DT, int E>
+__device__ __forceinline__ void store_slot(typename Types<DT>::Y* yp, const typename Types<DT>::A (&acc)[E])
+{
+    if constexpr (E == 1) {
+        store_out(yp, narrow<DT>(acc[0]));
+    } else if constexpr (DT == SC_F16) {
+        const uint32_t lo = __half_as_ushort(__float2half(acc[0]));
+        const uint32_t hi = __half_as_ushort(__float2half(acc[1]));
+        store_out(reinterpret_cast<uint32_t*>(yp), lo | (hi << 16));
+    } else {
+        store_out4(yp, acc[0], acc[1], acc[2], acc[3]);
+    }
+}
+
 // Rows d = first, first + stride, ... of the layer over the tile resident at lane_base: for every
 // stored entry gather slab[position + lambda] for the lane's VPT positions and accumulate; one
 // store per output.  Groups are fetched one ahead of the group being multiplied.
@@ -892,7 +931,7 @@ struct ChunkArgs {
     int64_t x_sample_stride, y_plane;
 };
 
-template <sc_dtype_t DT, int VPT, int RPW>
+template <sc_dtype_t DT, int VPT, int RPW, int E>
 __global__ void
 slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                   const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const ChunkArgs a)
@@ -952,7 +991,10 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     }
 
     // ---------------------------------------------------------------------- consumer waves
-    A acc[RPW][VPT];
+    // E > 1 (packed positions): slot k of a lane is the 32-bit word of positions
+    // (k * 64 + lane) * E .. + E - 1; rows and tiles are whole words, so a word is valid or not as one
+    static_assert(E == 1 || E * (int)sizeof(X) == 4, "packed positions: 32-bit words");
+    A acc[RPW][VPT][E];
     int out_off[VPT];
     int it = 0;
     for (int u = first; u < units; u += step) {
@@ -960,17 +1002,19 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         decode(u, b, q0, dt);
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            const int f = k * 64 + lane;
+            const int f = (k * 64 + lane) * E;
             out_off[k] = (f < a.TQ && q0 + f < a.Wf) ? q0 + f : -1;
         }
 #pragma unroll
         for (int r = 0; r < RPW; ++r)
 #pragma unroll
-            for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+            for (int k = 0; k < VPT; ++k)
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[r][k][e] = A(0);
         const int d0 = dt * a.DTW;
         const int dend = min(a.D, d0 + a.DTW);
         for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
-            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * E * (int)sizeof(X);
             __syncthreads();  // A
             // one segment per row and chunk, multiplied 8 entries at a time with no software
             // prefetch (the gathers of a group are then waited for one by one, and the other
@@ -987,7 +1031,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
                         const unsigned char* pj = lane_base + lam;
 #pragma unroll
                         for (int k = 0; k < VPT; ++k)
-                            acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                            mac_slot<DT, E>(acc[r][k], w, pj + k * 64 * E * (int)sizeof(X));
                     };
                     const int2* seg = wlc + s0;
                     int e = 0;
@@ -1015,7 +1059,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
                 Y* yd = yb + (int64_t)d * a.y_plane;
 #pragma unroll
                 for (int k = 0; k < VPT; ++k)
-                    if (out_off[k] >= 0) store_out(yd + out_off[k], narrow<DT>(acc[r][k]));
+                    if (out_off[k] >= 0) store_slot<DT, E>(yd + out_off[k], acc[r][k]);
             }
         }
     }
@@ -1032,7 +1076,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
 // registers from the first chunk of a tile to the last and stores after the last.  The weight
 // table holds one segment per (row, chunk), padded with zero weights to whole 8-entry groups.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT>
+template <sc_dtype_t DT, int VPT, int E>
 __global__ void
 slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                  const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const ChunkArgs a)
@@ -1045,6 +1089,7 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     typedef const int32_t __attribute__((address_space(4)))* ci_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int RPW = kMaxRowsPerWave;
+    static_assert(E == 1 || E * (int)sizeof(X) == 4, "packed positions: 32-bit words");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -1088,11 +1133,13 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const int base_rows = dcnt / nwaves, extra = dcnt - base_rows * nwaves;
         const int row0 = d0 + wave * base_rows + min(wave, extra);
         const int nrows = base_rows + (wave < extra ? 1 : 0);
-        A acc[RPW][VPT];
+        A acc[RPW][VPT][E];     // E > 1: slot k is the word of positions (k * 64 + lane) * E .. + E - 1
 #pragma unroll
         for (int r = 0; r < RPW; ++r)
 #pragma unroll
-            for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+            for (int k = 0; k < VPT; ++k)
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[r][k][e] = A(0);
         for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
             __syncthreads();      // item (u, ch) is complete in buffer it&1; the other buffer is free
             {
@@ -1100,7 +1147,7 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
                 if (chn == a.nchunks) { chn = 0; un = u + step; }
                 if (un < units) issue(un, chn, (it + 1) & 1);
             }
-            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (int)sizeof(X);
+            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * E * (int)sizeof(X);
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
                 if (r < nrows) {
@@ -1114,7 +1161,7 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
                             const unsigned char* pj = lane_base + c[2 * i + 1];
 #pragma unroll
                             for (int k = 0; k < VPT; ++k)
-                                acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                                mac_slot<DT, E>(acc[r][k], w, pj + k * 64 * E * (int)sizeof(X));
                         }
                     }
                 }
@@ -1129,21 +1176,21 @@ slab_symc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
             if (r < nrows) {
 #pragma unroll
                 for (int k = 0; k < VPT; ++k) {
-                    const int f = k * 64 + lane;
+                    const int f = (k * 64 + lane) * E;
                     if (f < a.TQ && q0 + f < a.Wf)
-                        store_out(yd + (int64_t)r * a.y_plane + q0 + f, narrow<DT>(acc[r][k]));
+                        store_slot<DT, E>(yd + (int64_t)r * a.y_plane + q0 + f, acc[r][k]);
                 }
             }
         }
     }
 }
 
-template <sc_dtype_t DT, int VPT>
+template <sc_dtype_t DT, int VPT, int E = 1>
 static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_symc_kernel<DT, VPT>;
+    auto kernel = slab_symc_kernel<DT, VPT, E>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1171,7 +1218,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS>
+template <sc_dtype_t DT, int VPT, bool MS, int E>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1212,18 +1259,24 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const float inv_nsw = 1.0f / (float)a.nsw;
     const X* xb = x + (int64_t)b * a.x_sample_stride;
 
-    int out_off[VPT];
+    // E > 1 (packed positions): slot k of a lane is the 32-bit word of positions
+    // (k * 64 + lane) * E .. + E - 1 of the flat tile
+    static_assert(E == 1 || (!MS && E * (int)sizeof(X) == 4), "packed positions: one sample, 32-bit words");
+    int out_off[VPT][E];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const int f = MS ? lane : k * 64 + lane;
-        const int tp = fdiv(f, a.inv_Qs);
-        const int tq = f - tp * a.Qs;
-        const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
-        out_off[k] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int f = MS ? lane : (k * 64 + lane) * E + e;
+            const int tp = fdiv(f, a.inv_Qs);
+            const int tq = f - tp * a.Qs;
+            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
+            out_off[k][e] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
+        }
     }
     const int img_elems = a.CC * a.chan_pitch;                       // one sample's chunk image
-    const int koff = MS ? img_elems * (int)sizeof(X) : 64 * (int)sizeof(X);
-    const unsigned char* lane_base = lds + lane * (int)sizeof(X);
+    const int koff = MS ? img_elems * (int)sizeof(X) : 64 * E * (int)sizeof(X);
+    const unsigned char* lane_base = lds + lane * E * (int)sizeof(X);
 
     // Offset of every element of one staged channel image inside the input plane, or -1 where the
     // image shows zero padding / lies outside the plane: computed once, so that staging a chunk
@@ -1249,11 +1302,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int nrows = base_rows + (wave < extra ? 1 : 0);
     const ci_t segs = (ci_t)seg_off;
 
-    A acc[RPW][VPT];
+    A acc[RPW][VPT][E];
 #pragma unroll
     for (int r = 0; r < RPW; ++r)
 #pragma unroll
-        for (int k = 0; k < VPT; ++k) acc[r][k] = A(0);
+        for (int k = 0; k < VPT; ++k)
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[r][k][e] = A(0);
 
     for (int ch = 0; ch < a.nchunks; ++ch) {
         const int c0 = ch * a.CC;
@@ -1293,8 +1348,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                     const WL w = weight_from_bits<DT>(wbits);
                     const unsigned char* pj = lane_base + lam;
 #pragma unroll
-                    for (int k = 0; k < VPT; ++k)
-                        acc[r][k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * koff));
+                    for (int k = 0; k < VPT; ++k) mac_slot<DT, E>(acc[r][k], w, pj + k * koff);
                 };
                 const int2* seg = wlc + s0;
                 int e = 0;
@@ -1319,20 +1373,22 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         if (r < nrows) {
 #pragma unroll
             for (int k = 0; k < VPT; ++k)
-                if (out_off[k] >= 0)
-                    store_out(yd + (int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k],
-                              narrow<DT>(acc[r][k]));
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (out_off[k][e] >= 0)
+                        store_out(yd + (int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
+                                  narrow<DT>(acc[r][k][e]));
         }
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS>
+template <sc_dtype_t DT, int VPT, bool MS, int E = 1>
 static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                  hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1356,6 +1412,21 @@ static sc_status_t launch_cc(const Plan& p, const SlabArgs& a, const void* x, vo
         }
         return SC_ERR_UNSUPPORTED;
     }
+    if constexpr (DT == SC_F16 || DT == SC_I8) {
+        constexpr int E = 4 / (int)sizeof(typename Types<DT>::X);
+        if (p.geom.pack == E) {
+            switch (p.geom.vpt) {
+                case 1: return launch_cc_one<DT, 1, false, E>(p, a, x, y, grid, stream);
+                case 2: return launch_cc_one<DT, 2, false, E>(p, a, x, y, grid, stream);
+            }
+            if constexpr (E == 2) {
+                if (p.geom.vpt == 3) return launch_cc_one<DT, 3, false, E>(p, a, x, y, grid, stream);
+                if (p.geom.vpt == 4) return launch_cc_one<DT, 4, false, E>(p, a, x, y, grid, stream);
+            }
+            return SC_ERR_UNSUPPORTED;
+        }
+    }
+    if (p.geom.pack != 1) return SC_ERR_UNSUPPORTED;
     switch (p.geom.vpt) {
         case 1: return launch_cc_one<DT, 1, false>(p, a, x, y, grid, stream);
         case 2: return launch_cc_one<DT, 2, false>(p, a, x, y, grid, stream);
@@ -1365,12 +1436,12 @@ static sc_status_t launch_cc(const Plan& p, const SlabArgs& a, const void* x, vo
     return SC_ERR_UNSUPPORTED;
 }
 
-template <sc_dtype_t DT, int VPT, int RPW>
+template <sc_dtype_t DT, int VPT, int RPW, int E = 1>
 static sc_status_t launch_chunk_one(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_chunk_kernel<DT, VPT, RPW>;
+    auto kernel = slab_chunk_kernel<DT, VPT, RPW, E>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1385,18 +1456,18 @@ static sc_status_t launch_chunk_one(const Plan& p, const ChunkArgs& a, const voi
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
-template <sc_dtype_t DT, int VPT>
+template <sc_dtype_t DT, int VPT, int E = 1>
 static sc_status_t launch_chunk_rpw(const Plan& p, const ChunkArgs& a, const void* x, void* y, hipStream_t stream)
 {
     switch (p.geom.rpw) {
-        case 1: return launch_chunk_one<DT, VPT, 1>(p, a, x, y, stream);
-        case 2: return launch_chunk_one<DT, VPT, 2>(p, a, x, y, stream);
-        case 3: return launch_chunk_one<DT, VPT, 3>(p, a, x, y, stream);
-        case 4: return launch_chunk_one<DT, VPT, 4>(p, a, x, y, stream);
-        case 5: return launch_chunk_one<DT, VPT, 5>(p, a, x, y, stream);
-        case 6: return launch_chunk_one<DT, VPT, 6>(p, a, x, y, stream);
-        case 7: return launch_chunk_one<DT, VPT, 7>(p, a, x, y, stream);
-        case 8: return launch_chunk_one<DT, VPT, 8>(p, a, x, y, stream);
+        case 1: return launch_chunk_one<DT, VPT, 1, E>(p, a, x, y, stream);
+        case 2: return launch_chunk_one<DT, VPT, 2, E>(p, a, x, y, stream);
+        case 3: return launch_chunk_one<DT, VPT, 3, E>(p, a, x, y, stream);
+        case 4: return launch_chunk_one<DT, VPT, 4, E>(p, a, x, y, stream);
+        case 5: return launch_chunk_one<DT, VPT, 5, E>(p, a, x, y, stream);
+        case 6: return launch_chunk_one<DT, VPT, 6, E>(p, a, x, y, stream);
+        case 7: return launch_chunk_one<DT, VPT, 7, E>(p, a, x, y, stream);
+        case 8: return launch_chunk_one<DT, VPT, 8, E>(p, a, x, y, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }
@@ -1414,6 +1485,24 @@ static sc_status_t launch_chunk(const Plan& p, const void* x, void* y, int N, hi
     a.x_sample_stride = (int64_t)p.L.C * g.Wf;
     a.y_plane = (int64_t)g.Qf;
     if ((int64_t)N * g.tiles_q * g.ndt >= (1 << 19)) return SC_ERR_UNSUPPORTED;
+    if constexpr (DT == SC_F16 || DT == SC_I8) {
+        constexpr int E = 4 / (int)sizeof(typename Types<DT>::X);
+        if (g.pack == E) {
+            // a lane stores the E results of a word at once: y aligned like such a store
+            if (reinterpret_cast<uintptr_t>(y) % (E * sizeof(typename Types<DT>::Y)) != 0) return SC_ERR_UNSUPPORTED;
+            const bool sym = p.tuning.pipeline == 2;
+            switch (g.vpt) {
+                case 1: return sym ? launch_symc_one<DT, 1, E>(p, a, x, y, stream) : launch_chunk_rpw<DT, 1, E>(p, a, x, y, stream);
+                case 2: return sym ? launch_symc_one<DT, 2, E>(p, a, x, y, stream) : launch_chunk_rpw<DT, 2, E>(p, a, x, y, stream);
+            }
+            if constexpr (E == 2) {
+                if (g.vpt == 3) return sym ? launch_symc_one<DT, 3, E>(p, a, x, y, stream) : launch_chunk_rpw<DT, 3, E>(p, a, x, y, stream);
+                if (g.vpt == 4) return sym ? launch_symc_one<DT, 4, E>(p, a, x, y, stream) : launch_chunk_rpw<DT, 4, E>(p, a, x, y, stream);
+            }
+            return SC_ERR_UNSUPPORTED;
+        }
+    }
+    if (g.pack != 1) return SC_ERR_UNSUPPORTED;
     if (p.tuning.pipeline == 2) {
         switch (g.vpt) {
             case 1: return launch_symc_one<DT, 1>(p, a, x, y, stream);

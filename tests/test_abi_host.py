@@ -41,17 +41,17 @@ def test_struct_layouts_match_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "sparse_conv.h"\n'
-        'int main(void) { printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(sc_layer_t), sizeof(sc_tuning_t), '
-        'sizeof(sc_plan_info_t), offsetof(sc_plan_info_t, tuning), offsetof(sc_tuning_t, ragged), '
+        'int main(void) { printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(sc_layer_t), sizeof(sc_tuning_t), '
+        'sizeof(sc_plan_info_t), offsetof(sc_plan_info_t, tuning), offsetof(sc_tuning_t, ragged), offsetof(sc_tuning_t, pack), '
         'offsetof(sc_plan_info_t, weight_bytes)); return 0; }\n')
     exe = tmp_path / "sizes"
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     subprocess.check_call(["gcc", "-I", os.path.join(root, "include"), str(src), "-o", str(exe)])
     c = [int(v) for v in subprocess.check_output([str(exe)]).split()]
     assert c == [ctypes.sizeof(B.sc_layer_t), ctypes.sizeof(B.sc_tuning_t), ctypes.sizeof(B.sc_plan_info_t),
-                 B.sc_plan_info_t.tuning.offset, B.sc_tuning_t.ragged.offset,
+                 B.sc_plan_info_t.tuning.offset, B.sc_tuning_t.ragged.offset, B.sc_tuning_t.pack.offset,
                  B.sc_plan_info_t.weight_bytes.offset]
-    assert ctypes.sizeof(B.sc_layer_t) == 40 and ctypes.sizeof(B.sc_tuning_t) == 13 * 4
+    assert ctypes.sizeof(B.sc_layer_t) == 40 and ctypes.sizeof(B.sc_tuning_t) == 14 * 4
 
 
 def _expect(status, fn, *a, **k):

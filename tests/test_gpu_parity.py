@@ -33,6 +33,15 @@ def _both_variants(plan):
                                                 "tile_q": 16, "sub_batch": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 128, "tile_p": 4,
                                                 "tile_q": 8, "sub_batch": 3}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 256, "pack": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
+                                                "tile_q": 1000, "pack": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 64, "tile_d": 3, "wg_threads": 64, "tile_p": 5,
+                                                "tile_q": 37, "pack": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "chunk_c": 5,
+                                                "tile_q": 128, "pack": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "chunk_c": 7,
+                                                "tile_q": 64, "tile_d": 5, "pack": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
@@ -435,3 +444,49 @@ def test_ragged_table_option_matches_the_unified_result(dtype):
                 G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
                 ran += 1
         assert ran >= 4
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+def test_packed_positions_in_the_chunked_one_shot_kernel(dtype):
+    """tuning.pack = 1: a lane owns the 2 (f16) or 4 (i8) adjacent positions of one 32-bit word of the
+    staged tile.  Filter taps make the word start at any element (odd offsets), tiles end in the
+    middle of a word, stride phases and padding are in play, and tiles of 1..4 words per lane."""
+    for l, tunings in (
+            (wl.Layer("pk3x3", 20, 24, 28, 28, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.8, dtype=dtype, seed=31),
+             [{"tile_p": 4, "chunk_c": 8}, {"tile_p": 7, "chunk_c": 20, "tile_d": 8}, {"tile_p": 16, "chunk_c": 4},
+              {"tile_p": 2, "chunk_c": 16, "wg_per_cu": 3}]),
+            (wl.Layer("pk3x3s2", 12, 10, 29, 27, 3, 3, 2, 2, 1, 1, N=2, sparsity=0.7, dtype=dtype, seed=32),
+             [{"tile_p": 4, "chunk_c": 5}, {"tile_p": 14, "chunk_c": 12}]),
+            (wl.Layer("pk1x1", 96, 40, 14, 14, 1, 1, 1, 1, 0, 0, N=5, sparsity=0.9, dtype=dtype, seed=33),
+             [{"tile_q": 64, "chunk_c": 32}, {"tile_q": 200, "chunk_c": 16, "tile_d": 16}, {"tile_q": 512, "chunk_c": 64}]),
+            (wl.Layer("pk5x1", 9, 6, 40, 7, 5, 1, 1, 1, 2, 0, N=2, sparsity=0.5, dtype=dtype, seed=34),
+             [{"tile_p": 9, "chunk_c": 4}])):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=512, pack=1, **extra)
+            t = plan.get_tuning().as_dict()
+            assert t["pack"] == 1
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+    # the pipelined chunked kernels of the pointwise layers (rows and tiles are whole words there)
+    l = wl.Layer("pk1x1p", 72, 50, 20, 28, 1, 1, 1, 1, 0, 0, N=4, sparsity=0.8, dtype=dtype, seed=36)
+    data = wl.prepare(l, ragged=True)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    for extra in ({"pipeline": 1, "tile_q": 128, "chunk_c": 16, "producers": 1},
+                  {"pipeline": 1, "tile_q": 512, "chunk_c": 24, "tile_d": 32, "producers": 2},
+                  {"pipeline": 2, "tile_q": 256, "chunk_c": 32}, {"pipeline": 2, "tile_q": 64, "chunk_c": 9, "tile_d": 24},
+                  {"pipeline": 2, "tile_q": 384, "chunk_c": 16, "ragged": 1}):
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, pack=1, **extra)
+        t = plan.get_tuning().as_dict()
+        assert t["pack"] == 1 and t["pipeline"] == extra["pipeline"]
+        print("case", l.name, dtype, t, flush=True)
+        G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+    # not for 32-bit activations
+    l = wl.Layer("pkf32", 8, 8, 8, 8, 1, 1, 1, 1, 0, 0, N=2, sparsity=0.5, dtype="f32", seed=35)
+    plan = G.make_plan(l, wl.prepare(l))
+    for extra in ({"chunk_c": 4}, ):
+        with pytest.raises(B.SparseConvError):
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=1, **extra)
