@@ -124,9 +124,17 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
         o.ns = samples;
     }
-    const int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
+    int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
+    // packed positions read aligned 32-bit words only (unaligned LDS reads are several times
+    // slower): unless every lambda is a whole number of words (pointwise layer, even channel
+    // pitch), LDS holds `pack` images of the chunk, image s shifted by s elements, and an entry
+    // with lambda = s (mod pack) reads image s at lambda - s
+    o.copies = 1;
+    if (o.pack > 1 && pipeline == 0 && !(pw && o.chan_pitch % o.pack == 0)) o.copies = o.pack;
+    slab = (int64_t)o.copies * round_up((int)std::min<int64_t>(slab, kMaxLdsBytes), 16);
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);
+    o.copy_bytes = o.slab_bytes / o.copies;
     // weight stage: as many (theta, lambda) pairs as the budget allows, within [512, 4096]
     const int64_t total = (int64_t)L.D * p.n;
     int64_t cap = (lds_budget - o.slab_bytes - 64 - round_up(o.chan_pitch * 4, 16)) / 8;
@@ -875,7 +883,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     if ((p.dtype == SC_F16 || p.dtype == SC_I8) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
             if (cc > p.L.C && cc != 16) continue;
-            for (int td : {0, 64, 128}) {
+            for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 for (int tile : {2, 4, 7, 8, 14, 16, 28}) {
                     sc_tuning_t t{};

@@ -48,6 +48,7 @@ struct SlabArgs {
     int nsw, Qs, sub_pitch, chan_pitch, F;
     int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod, dmab;
     int CC, nchunks, DTW, ndt;           // channel-chunked one-shot form
+    int copies, copy_bytes;              // packed positions: shifted images of a chunk
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -133,8 +134,8 @@ __device__ inline void load_pair(int* o, const int2* __restrict__ wl32, __amdgpu
 }
 
 // One (theta, lambda) entry applied to one slot of a lane.  E = 1: the slot is one position.
-// E > 1: the slot is a 32-bit word of E adjacent positions (2 halves or 4 bytes), so one LDS read
-// feeds E multiply-adds.
+// E > 1: the slot is an aligned 32-bit word of E adjacent positions (2 halves or 4 bytes), so one
+// LDS read feeds E multiply-adds.
 template <sc_dtype_t DT, int E>
 __device__ __forceinline__ void mac_slot(typename Types<DT>::A (&acc)[E], typename Types<DT>::WL w,
                                          const unsigned char* p)
@@ -143,9 +144,7 @@ __device__ __forceinline__ void mac_slot(typename Types<DT>::A (&acc)[E], typena
     if constexpr (E == 1) {
         acc[0] += w * widen<DT>(*reinterpret_cast<const X*>(p));
     } else {
-        // (the word is aligned only when lambda is a multiple of E elements; memcpy leaves that open)
-        uint32_t xd;
-        __builtin_memcpy(&xd, p, 4);
+        const uint32_t xd = *reinterpret_cast<const uint32_t*>(p);
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             if constexpr (DT == SC_F16)
@@ -890,7 +889,7 @@ __global__ void __launch_bounds__(256)
 expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict__ lam,
                       const int32_t* __restrict__ col, const int32_t* __restrict__ seg_off,
                       const int32_t* __restrict__ first_j, int2* __restrict__ out, int D, int n,
-                      int RS, int CC, int nch)
+                      int RS, int CC, int nch, int copies, int ex, int copy_bytes)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)D * n) return;
@@ -902,7 +901,13 @@ expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict_
     // (a segment built without the fillers is shorter than the entries that map to its chunk: the
     // fillers behind it are dropped; one that lands on a padding slot is a zero weight either way)
     if (k >= seg_off[si + 1] - seg_off[si]) return;
-    out[(int64_t)seg_off[si] + k] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), l & 0x7fffffff);
+    int lb = l & 0x7fffffff;
+    if (copies > 1) {
+        // shifted images: an entry s elements past a word boundary reads image s one word-aligned
+        const int el = lb / ex, sh = el % copies;
+        lb = (el - sh) * ex + sh * copy_bytes;
+    }
+    out[(int64_t)seg_off[si] + k] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), lb);
 }
 
 sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream)
@@ -914,7 +919,7 @@ sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t tot
 #define SC_EXPANDC(DT)                                                                             \
     hipLaunchKernelGGL(expand_chunked_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
                        p.d_lam_slab, p.d_col, p.d_seg_off, p.d_first_j, p.d_wlc, p.L.D, p.n,       \
-                       p.L.R * p.L.S, g.CC, g.nchunks)
+                       p.L.R * p.L.S, g.CC, g.nchunks, g.copies, p.ex, g.copy_bytes)
     switch (p.dtype) {
         case SC_F32: SC_EXPANDC(SC_F32); break;
         case SC_F16: SC_EXPANDC(SC_F16); break;
@@ -1231,6 +1236,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     typedef const int32_t __attribute__((address_space(4)))* ci_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int RPW = kMaxRowsPerWave;
+    constexpr int kStageLoads = 4;    // global loads a thread has in flight while staging
     X* slab = reinterpret_cast<X*>(lds);
 
     const int tid = threadIdx.x;
@@ -1319,10 +1325,10 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         if (MS && b + sm >= a.N) break;
         const X* xc = xb + (int64_t)sm * a.x_sample_stride + (int64_t)c0 * plane;
         X* simg = slab + sm * img_elems;
-        for (int e0 = tid; e0 < elems; e0 += 4 * nthreads) {
-            X v[4];
+        for (int e0 = tid; e0 < elems; e0 += kStageLoads * nthreads) {
+            X v[kStageLoads];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kStageLoads; ++u) {
                 const int e = e0 + u * nthreads;
                 v[u] = X(0);
                 if (e < elems) {
@@ -1332,9 +1338,19 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kStageLoads; ++u) {
                 const int e = e0 + u * nthreads;
-                if (e < elems) simg[e] = v[u];
+                if (e < elems) {
+                    simg[e] = v[u];
+                    if constexpr (E > 1) {
+                        // shifted images for the word-aligned packed reads: image s holds element e at e - s
+                        if (a.copies > 1) {
+#pragma unroll
+                            for (int sh = 1; sh < E; ++sh)
+                                if (e >= sh) *reinterpret_cast<X*>(lds + sh * a.copy_bytes + (e - sh) * (int)sizeof(X)) = v[u];
+                        }
+                    }
+                }
             }
         }
         }
@@ -1736,6 +1752,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.y_plane = (int64_t)g.Pf * g.Qf;
     if (p.tuning.chunk_c > 0) {
         a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt;
+        a.copies = g.copies; a.copy_bytes = g.copy_bytes;
         a.inv_ndt = 1.0f / (float)g.ndt;
         const int64_t gridc = (int64_t)((N + g.ns - 1) / g.ns) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
