@@ -111,7 +111,9 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         // chunked form: pointwise layers, pipelined, weights by scalar loads; every consumer wave
         // keeps the accumulators of its rows in registers across the chunks of a tile
         // (pipeline 1 / 2: pointwise layers only; the one-shot chunked form takes any layer)
-        if ((!pw && pipeline >= 1) || wsrc != 1 || p.dtype == SC_CB4_I8 || p.n == 0) return false;
+        // (weights by scalar loads; the one-shot chunked form also takes them one entry per lane)
+        if ((!pw && pipeline >= 1) || !(wsrc == 1 || (wsrc == 3 && pipeline == 0 && !pack)) ||
+            p.dtype == SC_CB4_I8 || p.n == 0) return false;
         const int ncons = o.nwaves - (pipeline == 1 ? producers : 0);
         if (ncons < 1) return false;
         if (pipeline != 1 && o.vpt * o.pack > (pack ? 8 : 4)) return false;
@@ -831,6 +833,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.chunk_c = cc;
                     t.tile_d = td;
                     push(t);
+                    t.wsrc = 3;
+                    push(t);
                 }
             }
         }
@@ -853,6 +857,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_d = td;
                     t.sub_batch = ns;
                     push(t);
+                    t.wsrc = 3;
+                    push(t);
                 }
             }
         }
@@ -873,6 +879,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_q = p.Q;
                     t.chunk_c = cc;
                     t.tile_d = td;
+                    push(t);
+                    t.wsrc = 3;
                     push(t);
                 }
             }

@@ -1223,7 +1223,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1354,6 +1354,18 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             }
         }
         }
+        // LANES (tuning.wsrc = 3): lane j of the wave holds entry j of the segment being multiplied,
+        // loaded by one coalesced vector load and fetched one batch of 64 entries ahead (vector
+        // loads have their own counter, so they can be in flight across the gathers), and every
+        // entry is broadcast with two v_readlane.  For tables too large for the scalar cache.
+        int2 cur2 = make_int2(0, 0);
+        if constexpr (LANES) {
+            if (nrows > 0) {
+                const int si = drow0 * a.nchunks + ch;
+                const int s0 = segs[si], len = segs[si + 1] - s0;
+                if (lane < len) cur2 = wlc[s0 + lane];
+            }
+        }
         __syncthreads();                  // chunk staged
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
@@ -1366,6 +1378,28 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
                     for (int k = 0; k < VPT; ++k) mac_slot<DT, E>(acc[r][k], w, pj + k * koff);
                 };
+                if constexpr (LANES) {
+                    for (int c0 = 0; c0 < len || c0 == 0; c0 += 64) {
+                        const int cnt = min(64, len - c0);
+                        // next batch: of this segment, or the first of the wave's next row
+                        int2 nxt2 = make_int2(0, 0);
+                        if (c0 + 64 < len) {
+                            if (c0 + 64 + lane < len) nxt2 = wlc[s0 + c0 + 64 + lane];
+                        } else if (r + 1 < nrows) {
+                            const int sn = segs[si + a.nchunks], lenn = segs[si + a.nchunks + 1] - sn;
+                            if (lane < lenn) nxt2 = wlc[sn + lane];
+                        }
+                        int j = 0;
+                        for (; j + 8 <= cnt; j += 8) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i)
+                                mac(__builtin_amdgcn_readlane(cur2.x, j + i), __builtin_amdgcn_readlane(cur2.y, j + i));
+                        }
+                        for (; j < cnt; ++j) mac(__builtin_amdgcn_readlane(cur2.x, j), __builtin_amdgcn_readlane(cur2.y, j));
+                        cur2 = nxt2;
+                    }
+                    continue;
+                }
                 const int2* seg = wlc + s0;
                 int e = 0;
                 for (; e + 8 <= len; e += 8) {
@@ -1398,13 +1432,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E = 1>
-static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
-                                 hipStream_t stream)
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES>
+static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                               hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1415,6 +1449,16 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
                        static_cast<const X*>(x), static_cast<Y*>(y), p.d_wlc, p.d_seg_off, a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int VPT, bool MS, int E = 1>
+static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
+                                 hipStream_t stream)
+{
+    if constexpr (E == 1) {
+        if (p.tuning.wsrc == 3) return launch_cc_w<DT, VPT, MS, E, true>(p, a, x, y, grid, stream);
+    }
+    return launch_cc_w<DT, VPT, MS, E, false>(p, a, x, y, grid, stream);
 }
 
 template <sc_dtype_t DT>

@@ -33,6 +33,11 @@ def _both_variants(plan):
                                                 "tile_q": 16, "sub_batch": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 128, "tile_p": 4,
                                                 "tile_q": 8, "sub_batch": 3}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 3, "chunk_c": 2, "wg_threads": 256}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 3, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
+                                                "tile_q": 1000}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 3, "chunk_c": 3, "tile_d": 4, "wg_threads": 256, "tile_p": 3,
+                                                "tile_q": 16, "sub_batch": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 256, "pack": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
                                                 "tile_q": 1000, "pack": 1}),
@@ -490,3 +495,24 @@ def test_packed_positions_in_the_chunked_one_shot_kernel(dtype):
     for extra in ({"chunk_c": 4}, ):
         with pytest.raises(B.SparseConvError):
             plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=1, **extra)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_lane_distributed_weights_in_the_chunked_one_shot_kernel(dtype):
+    """tuning.wsrc = 3 with chunk_c > 0: segments longer than one batch of 64 entries, empty segments,
+    rows of uneven length (with and without the fillers), one and several samples per workgroup."""
+    for l, tunings in (
+            (wl.Layer("ln1x1", 320, 40, 7, 7, 1, 1, 1, 1, 0, 0, N=6, sparsity=0.3, dtype=dtype, seed=41),
+             [{"chunk_c": 160, "tile_q": 49, "sub_batch": 4}, {"chunk_c": 100, "tile_q": 49, "tile_d": 16, "sub_batch": 2},
+              {"chunk_c": 64, "tile_q": 49, "ragged": 1}]),
+            (wl.Layer("ln3x3", 24, 20, 14, 14, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.5, dtype=dtype, seed=42),
+             [{"chunk_c": 24, "tile_p": 7}, {"chunk_c": 5, "tile_p": 4, "tile_d": 8}, {"chunk_c": 12, "tile_p": 14, "ragged": 1}])):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=3, wg_threads=512, wg_per_cu=1, **extra)
+            t = plan.get_tuning().as_dict()
+            assert t["wsrc"] == 3 and t["chunk_c"] > 0
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
