@@ -1223,7 +1223,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1287,9 +1287,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // Offset of every element of one staged channel image inside the input plane, or -1 where the
     // image shows zero padding / lies outside the plane: computed once, so that staging a chunk
     // costs one division, one table read and one load per element.
+    // (FLAT: a pointwise layer with one tile per plane -- the image of a chunk is one contiguous,
+    // 16-byte aligned block of the input and is copied as such, no table)
     int* tab = reinterpret_cast<int*>(lds + a.slab_bytes);
     const int plane = a.Hf * a.Wf;
-    for (int rem = tid; rem < a.chan_pitch; rem += nthreads) {
+    for (int rem = tid; rem < (FLAT ? 0 : a.chan_pitch); rem += nthreads) {
         const int sub = fdiv(rem, a.inv_sub_pitch);
         const int rem2 = rem - sub * a.sub_pitch;
         const int i = fdiv(rem2, a.inv_Qs);
@@ -1325,6 +1327,26 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         if (MS && b + sm >= a.N) break;
         const X* xc = xb + (int64_t)sm * a.x_sample_stride + (int64_t)c0 * plane;
         X* simg = slab + sm * img_elems;
+        if constexpr (FLAT) {
+            constexpr int EPV = 16 / (int)sizeof(X);
+            const uint4v* src = reinterpret_cast<const uint4v*>(xc);
+            uint4v* dst = reinterpret_cast<uint4v*>(simg);
+            const int nvec = elems / EPV;                       // elems * sizeof(X) is a multiple of 16
+            for (int i0 = tid; i0 < nvec; i0 += kStageLoads * nthreads) {
+                uint4v v[kStageLoads];
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < nvec) v[u] = src[i];
+                }
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < nvec) dst[i] = v[u];
+                }
+            }
+            continue;
+        }
         for (int e0 = tid; e0 < elems; e0 += kStageLoads * nthreads) {
             X v[kStageLoads];
 #pragma unroll
@@ -1432,13 +1454,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT>
 static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1456,9 +1478,16 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
                                  hipStream_t stream)
 {
     if constexpr (E == 1) {
-        if (p.tuning.wsrc == 3) return launch_cc_w<DT, VPT, MS, E, true>(p, a, x, y, grid, stream);
+        if (p.tuning.wsrc == 3) return launch_cc_w<DT, VPT, MS, E, true, false>(p, a, x, y, grid, stream);
+        // pointwise layer, one tile per plane, chunk images that are whole 16-byte aligned blocks
+        // of the input: staged as a plain copy
+        const SlabGeom& g = p.geom;
+        const int64_t chunk_bytes = (int64_t)g.CC * g.chan_pitch * p.ex;
+        if (g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
+            ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
+            return launch_cc_w<DT, VPT, MS, E, false, true>(p, a, x, y, grid, stream);
     }
-    return launch_cc_w<DT, VPT, MS, E, false>(p, a, x, y, grid, stream);
+    return launch_cc_w<DT, VPT, MS, E, false, false>(p, a, x, y, grid, stream);
 }
 
 template <sc_dtype_t DT>

@@ -516,3 +516,25 @@ def test_lane_distributed_weights_in_the_chunked_one_shot_kernel(dtype):
             assert t["wsrc"] == 3 and t["chunk_c"] > 0
             print("case", l.name, dtype, t, flush=True)
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_pointwise_whole_plane_tiles_staged_as_a_plain_copy(dtype):
+    """Pointwise layer, one tile per plane, chunk images that are 16-byte aligned blocks of the input:
+    the chunked one-shot kernel copies them with 16-byte loads.  7x7 and 14x14 planes, a last chunk
+    with fewer channels, one and several samples per workgroup, a batch that does not divide."""
+    for l, tunings in (
+            (wl.Layer("flat7", 72, 24, 7, 7, 1, 1, 1, 1, 0, 0, N=5, sparsity=0.8, dtype=dtype, seed=51),
+             [{"chunk_c": 16, "tile_q": 49}, {"chunk_c": 32, "tile_q": 49, "sub_batch": 2},
+              {"chunk_c": 16, "tile_q": 49, "sub_batch": 4, "tile_d": 8}]),
+            (wl.Layer("flat14", 40, 20, 14, 14, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.7, dtype=dtype, seed=52),
+             [{"chunk_c": 8, "tile_q": 196}, {"chunk_c": 40, "tile_q": 256, "tile_d": 8}])):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=512, wg_per_cu=1, **extra)
+            t = plan.get_tuning().as_dict()
+            assert t["tile_q"] == l.H * l.W and t["chunk_c"] == extra["chunk_c"]
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
