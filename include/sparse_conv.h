@@ -109,8 +109,8 @@ typedef struct {
                            most 4 positions per lane and 8 rows per wave.  0 = one tile per workgroup */
     int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
     int32_t chunk_c;    /* SLAB: input channels per LDS buffer (0 = all of them); with pipeline = 0 for any
-                           layer shape (wsrc = 1, at most 4 positions per lane and 8 rows per wave), with
-                           pipeline = 1 or 2 for pointwise layers.  With
+                           layer shape (wsrc = 1 or 3, at most 4 positions per lane and 8 rows per wave), with
+                           pipeline = 1 or 2 for pointwise layers (wsrc = 1).  With
                            chunk_c < C a tile is multiplied chunk by chunk, each wave keeping the
                            accumulators of its output channels in registers across the chunks, so
                            wide tiles fit LDS even for layers with many input channels */
@@ -119,10 +119,12 @@ typedef struct {
                            filler entries that unify the row lengths are left out of the per-chunk
                            segments), 0 = the unified table of the method.  For measuring what the
                            padding costs on tables whose rows differ in length */
-    int32_t pack;       /* SLAB with pipeline = 0 and chunk_c > 0, SC_F16 / SC_I8, one sample per workgroup:
+    int32_t pack;       /* SLAB with chunk_c > 0 and wsrc = 1, SC_F16 / SC_I8, one sample per workgroup:
                            1 = every lane owns the 2 (f16) or 4 (i8) adjacent positions of one 32-bit word
                            of the staged tile, so one LDS read feeds that many multiply-adds (at most 8
-                           positions per lane); 0 = one position per LDS read */
+                           positions per lane; with pipeline = 0 on a layer that is not pointwise LDS then
+                           holds 2 / 4 shifted images of each chunk); 0 = one position per LDS read.
+                           With pipeline = 1 or 2 y must be 4-byte (f16) / 16-byte (i8) aligned */
 } sc_tuning_t;
 
 typedef struct {

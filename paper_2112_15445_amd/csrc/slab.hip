@@ -22,6 +22,13 @@
 //   slab_chunk_kernel  the same with channel chunks
 //   slab_sym_kernel / slab_symc_kernel   the same without dedicated producer waves
 //
+// 16- and 8-bit activations can be multiplied as packed positions (tuning.pack; always in
+// slab_async_kernel with scalar-load weights): a lane owns the 2 or 4 adjacent positions of one
+// aligned 32-bit LDS word, so one LDS read feeds 2 or 4 multiply-adds.  Where filter taps would
+// put the word off a word boundary (any layer that is not pointwise) slab_cc_kernel keeps 2 or 4
+// images of the chunk in LDS, image s shifted by s elements, and the segment table points every
+// entry at the image in which its word is aligned.
+//
 // (theta, lambda) reaches the lanes in one of four ways (tuning.wsrc):
 //   0  rows are staged in LDS in groups (decoding 4-bit codebook indices on the way) and read back
 //      with wave-uniform (broadcast) LDS reads, as Algorithm 3 does from shared memory;
