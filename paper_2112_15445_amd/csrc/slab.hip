@@ -56,6 +56,7 @@ struct SlabArgs {
     int slab_elems, slab_bytes, wcap, DS, JC, vec, np, nprod, dmab;
     int CC, nchunks, DTW, ndt;           // channel-chunked one-shot form
     int copies, copy_bytes;              // packed positions: shifted images of a chunk
+    int SR;                              // rows of one channel image
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -1230,7 +1231,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1295,10 +1296,25 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // image shows zero padding / lies outside the plane: computed once, so that staging a chunk
     // costs one division, one table read and one load per element.
     // (FLAT: a pointwise layer with one tile per plane -- the image of a chunk is one contiguous,
-    // 16-byte aligned block of the input and is copied as such, no table)
+    // 16-byte aligned block of the input and is copied as such, no table.
+    // ROWB > 0: unit strides and a tile as wide as the plane -- every row of a channel image is a
+    // whole row of the input between the padding columns, and those rows are contiguous in memory:
+    // they are copied with ROWB-byte loads, two index divisions per load instead of one per
+    // element, no table.  The padding is written once, here: no later store touches it.)
+    static_assert(ROWB == 0 || (!MS && !FLAT && ROWB % (int)sizeof(X) == 0), "row runs: one sample, whole elements");
     int* tab = reinterpret_cast<int*>(lds + a.slab_bytes);
     const int plane = a.Hf * a.Wf;
-    for (int rem = tid; rem < (FLAT ? 0 : a.chan_pitch); rem += nthreads) {
+    if constexpr (ROWB > 0) {
+        uint4v* z = reinterpret_cast<uint4v*>(lds);
+        for (int i = tid; i < (a.slab_bytes >> 4); i += nthreads) z[i] = uint4v{0u, 0u, 0u, 0u};
+    }
+    constexpr int RV = ROWB > 0 ? ROWB / (int)sizeof(X) : 1;        // elements per load
+    const int rlo = max(row0, 0);
+    const int rcnt = min(row0 + a.SR, a.Hf) - rlo;                  // input rows under the tile (>= 1)
+    const int vpr = a.Wf / RV;                                       // loads per row
+    const int per_c = rcnt * vpr;                                    // loads per channel
+    const float inv_per_c = 1.0f / (float)per_c, inv_vpr = 1.0f / (float)vpr;
+    for (int rem = tid; rem < ((FLAT || ROWB > 0) ? 0 : a.chan_pitch); rem += nthreads) {
         const int sub = fdiv(rem, a.inv_sub_pitch);
         const int rem2 = rem - sub * a.sub_pitch;
         const int i = fdiv(rem2, a.inv_Qs);
@@ -1350,6 +1366,45 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                 for (int u = 0; u < kStageLoads; ++u) {
                     const int i = i0 + u * nthreads;
                     if (i < nvec) dst[i] = v[u];
+                }
+            }
+            continue;
+        }
+        if constexpr (ROWB > 0) {
+            struct alignas(ROWB) Vec { X e[RV]; };
+            const int nvec = min(a.CC, a.C - c0) * per_c;
+            for (int i0 = tid; i0 < nvec; i0 += kStageLoads * nthreads) {
+                Vec v[kStageLoads];
+                int dsti[kStageLoads];
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < nvec) {
+                        const int c = fdiv(i, inv_per_c);
+                        const int r2 = i - c * per_c;
+                        const int ir = fdiv(r2, inv_vpr);
+                        const int vv = r2 - ir * vpr;
+                        v[u] = *reinterpret_cast<const Vec*>(xc + (int64_t)c * plane + (rlo + ir) * a.Wf + vv * RV);
+                        dsti[u] = c * a.chan_pitch + (rlo - row0 + ir) * a.Qs + a.pad_w + vv * RV;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < nvec) {
+#pragma unroll
+                        for (int j = 0; j < RV; ++j) {
+                            simg[dsti[u] + j] = v[u].e[j];
+                            if constexpr (E > 1) {
+                                if (a.copies > 1) {
+#pragma unroll
+                                    for (int sh = 1; sh < E; ++sh)
+                                        if (dsti[u] + j >= sh)
+                                            *reinterpret_cast<X*>(lds + sh * a.copy_bytes + (dsti[u] + j - sh) * (int)sizeof(X)) = v[u].e[j];
+                                }
+                            }
+                        }
+                    }
                 }
             }
             continue;
@@ -1461,13 +1516,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0>
 static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1478,6 +1533,21 @@ static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, 
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(p.tuning.wg_threads), p.geom.lds_bytes, stream,
                        static_cast<const X*>(x), static_cast<Y*>(y), p.d_wlc, p.d_seg_off, a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+// Bytes per load of the row-run staging this layer, tile and pointer allow (0: stage by table):
+// unit strides, a tile as wide as the plane, rows that are a whole number of such loads.
+static int row_run_bytes(const Plan& p, const void* x)
+{
+    const SlabGeom& g = p.geom;
+    if (p.L.stride_h != 1 || p.L.stride_w != 1 || g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1) return 0;
+    if (g.Hf == 1) return 0;                                      // flattened pointwise layers
+    if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return 0;
+    const int row_bytes = g.Wf * p.ex;
+    for (int b : {16, 8, 4})
+        if (b > p.ex && row_bytes % b == 0) return b;
+    return 0;
 }
 
 template <sc_dtype_t DT, int VPT, bool MS, int E = 1>
@@ -1493,6 +1563,16 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
         if (g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
             ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
             return launch_cc_w<DT, VPT, MS, E, false, true>(p, a, x, y, grid, stream);
+    }
+    if constexpr (!MS) {
+        switch (row_run_bytes(p, x)) {
+            case 16: return launch_cc_w<DT, VPT, MS, E, false, false, 16>(p, a, x, y, grid, stream);
+            case 8: return launch_cc_w<DT, VPT, MS, E, false, false, 8>(p, a, x, y, grid, stream);
+            case 4:
+                if constexpr (sizeof(typename Types<DT>::X) < 4)
+                    return launch_cc_w<DT, VPT, MS, E, false, false, 4>(p, a, x, y, grid, stream);
+                break;
+        }
     }
     return launch_cc_w<DT, VPT, MS, E, false, false>(p, a, x, y, grid, stream);
 }
@@ -1832,7 +1912,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.y_plane = (int64_t)g.Pf * g.Qf;
     if (p.tuning.chunk_c > 0) {
         a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt;
-        a.copies = g.copies; a.copy_bytes = g.copy_bytes;
+        a.copies = g.copies; a.copy_bytes = g.copy_bytes; a.SR = g.SR;
         a.inv_ndt = 1.0f / (float)g.ndt;
         const int64_t gridc = (int64_t)((N + g.ns - 1) / g.ns) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;

@@ -538,3 +538,32 @@ def test_pointwise_whole_plane_tiles_staged_as_a_plain_copy(dtype):
             assert t["tile_q"] == l.H * l.W and t["chunk_c"] == extra["chunk_c"]
             print("case", l.name, dtype, t, flush=True)
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_full_width_tiles_staged_by_row_runs(dtype):
+    """Unit strides and tiles as wide as the plane: the chunked one-shot kernel copies whole input rows
+    with 4-, 8- or 16-byte loads and writes the zero padding once.  Widths that give each load size
+    (and one that gives none), paddings 0..2, tiles that end below the plane, packed positions."""
+    shapes = [("rr56", 12, 10, 13, 56, 3, 3, 1, 1), ("rr24", 10, 12, 9, 24, 3, 3, 1, 1), ("rr20", 9, 8, 11, 20, 5, 5, 2, 2),
+              ("rr12", 16, 6, 12, 12, 3, 3, 0, 0), ("rr8", 20, 9, 8, 8, 1, 3, 0, 1), ("rr14", 7, 5, 14, 14, 3, 3, 1, 1),
+              ("rr10", 6, 5, 10, 10, 3, 3, 2, 1)]
+    for name, C, D, H, W, R, S, ph, pw in shapes:
+        l = wl.Layer(name, C, D, H, W, R, S, 1, 1, ph, pw, N=3, sparsity=0.6, dtype=dtype, seed=61)
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        ran = 0
+        for extra in ({"tile_p": 4, "chunk_c": 3}, {"tile_p": 3, "chunk_c": 64, "tile_d": 4},
+                      {"tile_p": 5, "chunk_c": 4, "pack": 1}, {"tile_p": 8, "chunk_c": 2, "pack": 1, "tile_d": 3}):
+            try:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=256, wg_per_cu=1,
+                                tile_q=10000, **extra)
+            except B.SparseConvError as e:
+                assert e.status == 4 and extra.get("pack") and dtype == "f32"    # packing: 16- and 8-bit only
+                continue
+            t = plan.get_tuning().as_dict()
+            print("case", name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} {t}")
+            ran += 1
+        assert ran >= 2
