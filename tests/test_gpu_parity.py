@@ -567,3 +567,28 @@ def test_full_width_tiles_staged_by_row_runs(dtype):
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} {t}")
             ran += 1
         assert ran >= 2
+
+
+@pytest.mark.parametrize("name,extra", [
+    ("s56_conv3x3_sp80", {"tile_p": 7, "chunk_c": 64, "wg_per_cu": 1, "pack": 1}),
+    ("s28_conv3x3_sp80", {"tile_p": 7, "chunk_c": 128, "tile_d": 64, "wg_per_cu": 1, "pack": 1}),
+    ("s14_conv3x3_s2_sp90", {"tile_p": 7, "chunk_c": 64, "tile_d": 64, "wg_per_cu": 1, "pack": 1}),
+    ("s28_reduce1x1_sp80", {"pipeline": 1, "producers": 1, "tile_q": 256, "chunk_c": 128, "tile_d": 64, "pack": 1}),
+    ("s14_reduce1x1_sp90", {"pipeline": 2, "tile_q": 128, "chunk_c": 256, "tile_d": 64, "pack": 1}),
+    ("s7_reduce1x1_sp90", {"tile_q": 49, "chunk_c": 256, "tile_d": 32, "sub_batch": 2, "wg_per_cu": 1}),
+    ("s7_expand1x1_sp90", {"tile_q": 49, "chunk_c": 256, "tile_d": 64, "sub_batch": 4, "wg_per_cu": 1, "wsrc": 3}),
+])
+def test_full_size_half_precision_layers_packed_and_small_plane_forms(name, extra):
+    """Full-size ResNet-50-shaped fp16 layers (batch 32) in the launch shapes the per-layer report
+    picks: packed positions (shifted images on the 3x3 layers, row-run staging where the tile spans
+    the plane), whole-plane copies and lane-distributed weights on the 7x7 layers.  First and last
+    sample checked completely against the oracle."""
+    l = {x.name: x for x in wl.config4()}[name]
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wg_threads=1024, **{"wsrc": 1, **extra})
+    t = plan.get_tuning().as_dict()
+    assert t["chunk_c"] == extra["chunk_c"] and t["pack"] == extra.get("pack", 0)
+    y = G.run_gpu(plan, data["x"])
+    for b in (0, l.N - 1):
+        G.check(l, y[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{name} {t} sample {b}")
