@@ -48,7 +48,7 @@ def _ring(plan, data, l, torch, G, B):
     """Input/output buffer ring > 2x the Infinity Cache (at least 2 pairs)."""
     inf = plan.info()
     x0 = G.to_device(data["x"])
-    ybytes = l.N * l.D * inf.P * inf.Q * (2 if l.dtype == "f16" else 4)
+    ybytes = l.N * l.D * inf.P * inf.Q * (2 if l.dtype in ("f16", "cb4h") else 4)
     per = x0.numel() * x0.element_size() + ybytes
     R = max(2, min(16, int(2 * INFINITY_CACHE_BYTES // per) + 1))
     xs = [x0] + [x0.clone() for _ in range(R - 1)]
@@ -88,7 +88,7 @@ def _spread(plan, xs, ys, ws, N, torch, repeats=10, launches=100):
 
 def _dense_reference_ms(l, torch, reps=30):
     """Dense MIOpen convolution of the same layer (torch conv2d), cache-warm, for context."""
-    dt = {"f32": torch.float32, "f16": torch.float16}.get(l.dtype)
+    dt = {"f32": torch.float32, "f16": torch.float16, "cb4h": torch.float16}.get(l.dtype)
     if dt is None:
         return None
     x = torch.empty((l.N, l.C, l.H, l.W), dtype=dt, device="cuda").uniform_(-1, 1)
@@ -224,7 +224,7 @@ def main():
 
     l = wl.headline_layer()
     if args.layer:
-        l = {x.name: x for c in (3, 4, 2, 5, 1, 6) for x in wl.CONFIGS[c]()}[args.layer]
+        l = {x.name: x for c in (3, 4, 2, 5, 1, 6, 7) for x in wl.CONFIGS[c]()}[args.layer]
     res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
                                 tuning=json.loads(args.tuning) if args.tuning else None, spread=True)
 
@@ -255,7 +255,7 @@ def main():
 
     if args.report:
         rows = []
-        for cfg in (1, 2, 3, 4, 5, 6):
+        for cfg in (1, 2, 3, 4, 5, 6, 7):
             for lay in wl.CONFIGS[cfg]():
                 r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl)
                 p.destroy()

@@ -60,8 +60,10 @@ typedef enum {
  *   SC_F16     f16 x f16 -> f32 -> f16 (one rounding at the store)
  *   SC_I8      i8  x i8  -> i32 -> i32 (exact; the per-channel scales are carried, not applied)
  *   SC_CB4_I8  4-bit index into a 16-entry i8 codebook x i8 -> i32 -> i32 (the paper's non-linear,
- *              cluster-based quantisation: each stored weight is a centroid index) */
-typedef enum { SC_F32 = 0, SC_F16 = 1, SC_I8 = 2, SC_CB4_I8 = 3 } sc_dtype_t;
+ *              cluster-based quantisation: each stored weight is a centroid index)
+ *   SC_CB4_F16 4-bit index into a 16-entry f16 codebook x f16 -> f32 -> f16 (the paper's 4b/16b
+ *              configuration: 16 centroids in sixteen-bit format, half-precision activations) */
+typedef enum { SC_F32 = 0, SC_F16 = 1, SC_I8 = 2, SC_CB4_I8 = 3, SC_CB4_F16 = 4 } sc_dtype_t;
 
 /* Layer geometry.  Weights are D rows (output channels) by K = C*R*S columns, a column being the
  * filter tap (c, r, s) flattened as (c*R + r)*S + s (PyTorch's weight.view(D, -1)). */
@@ -145,9 +147,9 @@ typedef struct {
 /* Build a plan from CSR weights (host arrays).
  *   rowptr  [D+1]  rowptr[0] = 0, non-decreasing; nnz = rowptr[D]
  *   colidx  [nnz]  each in [0, C*R*S); any order within a row; duplicates add up
- *   values  [nnz]  f32 (SC_F32), IEEE half bits (SC_F16), i8 (SC_I8), u8 index < 16 (SC_CB4_I8)
+ *   values  [nnz]  f32 (SC_F32), IEEE half bits (SC_F16), i8 (SC_I8), u8 index < 16 (SC_CB4_I8, SC_CB4_F16)
  *   scales  [D]    per-output-channel dequantisation scale, required for SC_I8 / SC_CB4_I8, else NULL
- *   codebook[16]   i8 centroids, required for SC_CB4_I8, else NULL
+ *   codebook[16]   centroids, i8 (SC_CB4_I8) or IEEE half bits (SC_CB4_F16); required for those, else NULL
  * Rows are padded to n = max row length with zero-valued entries that repeat the row's last column
  * (column 0 for an empty row); then a device pass stretches every column to its input offset.
  * Errors: SC_ERR_NULL, SC_ERR_SHAPE, SC_ERR_CSR, SC_ERR_UNSUPPORTED, SC_ERR_RANGE, SC_ERR_OOM, SC_ERR_HIP.

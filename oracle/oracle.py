@@ -62,6 +62,8 @@ def _load():
         getattr(lib, name).restype = None
     lib.oracle_decode_codebook.argtypes = [vp, sz, vp, vp]
     lib.oracle_decode_codebook.restype = None
+    lib.oracle_decode_codebook_f64.argtypes = [vp, sz, vp, vp]
+    lib.oracle_decode_codebook_f64.restype = None
     _lib = lib
     return lib
 
@@ -127,7 +129,8 @@ def sparse_conv_steps(x: np.ndarray, rowptr: np.ndarray, colidx: np.ndarray, val
                       codebook: Optional[np.ndarray] = None) -> Dict[str, object]:
     """Run the four steps of the sparse method and return every intermediate.
 
-    values: fp32/fp16 weights, int8 weights, or (with ``codebook``) uint8 centroid indices.
+    values: fp32/fp16 weights, int8 weights, or (with ``codebook``: int8 centroids for integer
+    activations, floating-point centroids otherwise) uint8 centroid indices.
     Returns dict(n, col [D,n], theta [D,n], lam [D,n] int64, xp [N,C,Hp,Wp], y [N,D,P,Q]) with y in
     the accumulator type (float64 or int32).
     """
@@ -146,13 +149,22 @@ def sparse_conv_steps(x: np.ndarray, rowptr: np.ndarray, colidx: np.ndarray, val
     X_size = C * Hp * Wp
     integer = _is_int(x)
 
-    if codebook is not None:
+    if codebook is not None and integer:
         idx = np.ascontiguousarray(values, dtype=np.uint8)
         assert idx.size == 0 or idx.max() < 16
         cb = np.ascontiguousarray(codebook, dtype=np.int32)
         assert cb.shape == (16,)
         vals = np.empty(idx.shape[0], dtype=np.int32)
         lib.oracle_decode_codebook(_p(idx), idx.shape[0], _p(cb), _p(vals))
+    elif codebook is not None:
+        # sixteen-bit centroids with floating-point activations (the 4b/16b configuration of the
+        # quantisation-results table): the same index -> centroid mapping, centroid values exact
+        idx = np.ascontiguousarray(values, dtype=np.uint8)
+        assert idx.size == 0 or idx.max() < 16
+        cb = np.ascontiguousarray(codebook, dtype=np.float64)
+        assert cb.shape == (16,)
+        vals = np.empty(idx.shape[0], dtype=np.float64)
+        lib.oracle_decode_codebook_f64(_p(idx), idx.shape[0], _p(cb), _p(vals))
     elif integer:
         vals = np.ascontiguousarray(values, dtype=np.int32)
     else:

@@ -170,3 +170,9 @@ void oracle_decode_codebook(const uint8_t* idx, size_t count, const int32_t* cod
 {
     for (size_t i = 0; i < count; ++i) out[i] = codebook[idx[i]];
 }
+
+/* the same with centroids kept in a floating-point format (sixteen-bit in the paper's 4b/16b runs) */
+void oracle_decode_codebook_f64(const uint8_t* idx, size_t count, const double* codebook, double* out)
+{
+    for (size_t i = 0; i < count; ++i) out[i] = codebook[idx[i]];
+}

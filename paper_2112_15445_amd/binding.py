@@ -20,8 +20,8 @@ SC_OK = 0
 STATUS_NAMES = {0: "SC_OK", 1: "SC_ERR_NULL", 2: "SC_ERR_SHAPE", 3: "SC_ERR_CSR",
                 4: "SC_ERR_UNSUPPORTED", 5: "SC_ERR_RANGE", 6: "SC_ERR_OOM", 7: "SC_ERR_WORKSPACE",
                 8: "SC_ERR_HIP"}
-SC_F32, SC_F16, SC_I8, SC_CB4_I8 = 0, 1, 2, 3
-DTYPES = {"f32": SC_F32, "f16": SC_F16, "i8": SC_I8, "cb4": SC_CB4_I8}
+SC_F32, SC_F16, SC_I8, SC_CB4_I8, SC_CB4_F16 = 0, 1, 2, 3, 4
+DTYPES = {"f32": SC_F32, "f16": SC_F16, "i8": SC_I8, "cb4": SC_CB4_I8, "cb4h": SC_CB4_F16}
 SC_VARIANT_AUTO, SC_VARIANT_GATHER, SC_VARIANT_SLAB = 0, 1, 2
 
 # every symbol include/sparse_conv.h declares
@@ -120,7 +120,8 @@ def _hp(a: Optional[np.ndarray]):
     return None if a is None else ctypes.c_void_p(a.ctypes.data)
 
 
-_VALUE_NP = {SC_F32: np.float32, SC_F16: np.float16, SC_I8: np.int8, SC_CB4_I8: np.uint8}
+_VALUE_NP = {SC_F32: np.float32, SC_F16: np.float16, SC_I8: np.int8, SC_CB4_I8: np.uint8, SC_CB4_F16: np.uint8}
+_CODEBOOK_NP = {SC_CB4_I8: np.int8, SC_CB4_F16: np.float16}
 
 
 def make_layer(C, D, H, W, R, S, stride=(1, 1), pad=(0, 0)) -> sc_layer_t:
@@ -143,7 +144,7 @@ class Plan:
         ci = _host(colidx, np.int32)
         va = _host(values, _VALUE_NP.get(dtype, np.uint8))
         sc_ = _host(scales, np.float32)
-        cb = _host(codebook, np.int8)
+        cb = _host(codebook, _CODEBOOK_NP.get(dtype, np.int8))
         out = ctypes.c_void_p()
         st = lib().sparse_conv_plan_create_csr(ctypes.byref(layer), dtype, _hp(rp), _hp(ci), _hp(va),
                                                _hp(sc_), _hp(cb), ctypes.c_void_p(stream),
@@ -157,7 +158,7 @@ class Plan:
         ci = _host(colidx, np.int32)
         va = _host(values, _VALUE_NP.get(dtype, np.uint8))
         sc_ = _host(scales, np.float32)
-        cb = _host(codebook, np.int8)
+        cb = _host(codebook, _CODEBOOK_NP.get(dtype, np.int8))
         out = ctypes.c_void_p()
         st = lib().sparse_conv_plan_create_ell(ctypes.byref(layer), dtype, n, _hp(ci), _hp(va),
                                                _hp(sc_), _hp(cb), ctypes.c_void_p(stream),
@@ -242,7 +243,8 @@ class Plan:
 # -------------------------------------------------------------------------------------------------
 def torch_out_dtype(dtype: int):
     import torch
-    return {SC_F32: torch.float32, SC_F16: torch.float16, SC_I8: torch.int32, SC_CB4_I8: torch.int32}[dtype]
+    return {SC_F32: torch.float32, SC_F16: torch.float16, SC_I8: torch.int32, SC_CB4_I8: torch.int32,
+            SC_CB4_F16: torch.float16}[dtype]
 
 
 def forward_torch(plan: Plan, x, y=None, workspace=None):

@@ -44,7 +44,7 @@ pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp, int64_t total, int
 template <sc_dtype_t DT, int VPT, int NSPLIT>
 __global__ void __launch_bounds__(256)
 gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restrict__ theta,
-              const int32_t* __restrict__ lam, const int8_t* __restrict__ codebook,
+              const int32_t* __restrict__ lam, const void* __restrict__ codebook,
               typename Types<DT>::Y* __restrict__ y, int64_t total_pos, int D, int n, int PQ, int Q,
               int s_h, int s_w, int Wp, int64_t X_size)
 {
@@ -52,7 +52,7 @@ gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restri
     using WL = typename Types<DT>::WL;
     __shared__ WL theta_s[kRowChunk];
     __shared__ int32_t lam_s[kRowChunk];
-    __shared__ int8_t cb_s[16];
+    __shared__ __attribute__((aligned(4))) unsigned char cb_s[32];
     constexpr int SLOTS = 256 / NSPLIT;
 
     const int d = blockIdx.y;
@@ -60,8 +60,8 @@ gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restri
     const int slot = threadIdx.x / NSPLIT;
     const int64_t g0 = (int64_t)blockIdx.x * (SLOTS * VPT) + slot;
 
-    if constexpr (DT == SC_CB4_I8) {
-        if (threadIdx.x < 16) cb_s[threadIdx.x] = codebook[threadIdx.x];
+    if constexpr (kCodebook<DT>) {
+        if (threadIdx.x < kCodebookBytes<DT>) cb_s[threadIdx.x] = static_cast<const unsigned char*>(codebook)[threadIdx.x];
     }
     // positions past the end re-read position 0; their results are not stored
     const typename Types<DT>::X* xs[VPT];
@@ -179,6 +179,7 @@ sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws
         case SC_F16: return launch_gather_t<SC_F16>(p, x, y, N, ws, stream);
         case SC_I8: return launch_gather_t<SC_I8>(p, x, y, N, ws, stream);
         case SC_CB4_I8: return launch_gather_t<SC_CB4_I8>(p, x, y, N, ws, stream);
+        case SC_CB4_F16: return launch_gather_t<SC_CB4_F16>(p, x, y, N, ws, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }

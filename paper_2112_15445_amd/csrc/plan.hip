@@ -13,8 +13,11 @@
 
 namespace sc {
 
-int elem_size_x(sc_dtype_t dt) { return dt == SC_F32 ? 4 : dt == SC_F16 ? 2 : 1; }
-int elem_size_y(sc_dtype_t dt) { return dt == SC_F16 ? 2 : 4; }
+static bool is_codebook(sc_dtype_t dt) { return dt == SC_CB4_I8 || dt == SC_CB4_F16; }   // 4-bit indices
+static int codebook_bytes(sc_dtype_t dt) { return dt == SC_CB4_F16 ? 32 : 16; }
+int elem_size_x(sc_dtype_t dt) { return dt == SC_F32 ? 4 : (dt == SC_F16 || dt == SC_CB4_F16) ? 2 : 1; }
+int elem_size_y(sc_dtype_t dt) { return (dt == SC_F16 || dt == SC_CB4_F16) ? 2 : 4; }
+// bytes of one weight as the caller passes it (clustered variants: one index per byte)
 static int elem_size_w_native(sc_dtype_t dt) { return dt == SC_F32 ? 4 : dt == SC_F16 ? 2 : 1; }
 
 // ------------------------------------------------------------------------------------------------
@@ -113,7 +116,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         // (pipeline 1 / 2: pointwise layers only; the one-shot chunked form takes any layer)
         // (weights by scalar loads; the one-shot chunked form also takes them one entry per lane)
         if ((!pw && pipeline >= 1) || !(wsrc == 1 || (wsrc == 3 && pipeline == 0 && !pack)) ||
-            p.dtype == SC_CB4_I8 || p.n == 0) return false;
+            is_codebook(p.dtype) || p.n == 0) return false;
         const int ncons = o.nwaves - (pipeline == 1 ? producers : 0);
         if (ncons < 1) return false;
         if (pipeline != 1 && o.vpt * o.pack > (pack ? 8 : 4)) return false;
@@ -196,7 +199,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.wg_threads == 0) t.wg_threads = 256;
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
     if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc != 0 && p.dtype == SC_CB4_I8) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
+    if (t.wsrc != 0 && is_codebook(p.dtype)) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
     if (t.pipeline < 0 || t.pipeline > 2) return SC_ERR_UNSUPPORTED;
     if (t.pipeline == 1 && t.producers == 0) t.producers = 2;
     if (t.pipeline != 1) t.producers = 0;
@@ -271,7 +274,7 @@ static sc_status_t validate_layer(const sc_layer_t* L, sc_dtype_t dt, const floa
                                   const void* codebook, Plan* p)
 {
     if (!L) return SC_ERR_NULL;
-    if (dt != SC_F32 && dt != SC_F16 && dt != SC_I8 && dt != SC_CB4_I8) return SC_ERR_UNSUPPORTED;
+    if (dt != SC_F32 && dt != SC_F16 && dt != SC_I8 && dt != SC_CB4_I8 && dt != SC_CB4_F16) return SC_ERR_UNSUPPORTED;
     if (L->C <= 0 || L->D <= 0 || L->H <= 0 || L->W <= 0 || L->R <= 0 || L->S <= 0 ||
         L->stride_h <= 0 || L->stride_w <= 0 || L->pad_h < 0 || L->pad_w < 0)
         return SC_ERR_SHAPE;
@@ -283,7 +286,7 @@ static sc_status_t validate_layer(const sc_layer_t* L, sc_dtype_t dt, const floa
     const int64_t Y_size = (int64_t)L->D * P * Q;
     if (K >= (1ll << 31) || X_size >= (1ll << 31) || Y_size >= (1ll << 31)) return SC_ERR_RANGE;
     if ((dt == SC_I8 || dt == SC_CB4_I8) && !scales) return SC_ERR_UNSUPPORTED;
-    if (dt == SC_CB4_I8 && !codebook) return SC_ERR_UNSUPPORTED;
+    if (is_codebook(dt) && !codebook) return SC_ERR_UNSUPPORTED;
     p->L = *L;
     p->dtype = dt;
     p->Hp = (int)Hp;
@@ -319,7 +322,7 @@ static sc_status_t unify_rows(const Plan& p, const int32_t* rowptr, const int32_
         t->len[d] = (int32_t)len;
         for (int64_t k = beg; k < beg + len; ++k) {
             if (colidx[k] < 0 || colidx[k] >= K) return SC_ERR_CSR;
-            if (p.dtype == SC_CB4_I8 && v[k] > 15) return SC_ERR_CSR;
+            if (is_codebook(p.dtype) && v[k] > 15) return SC_ERR_CSR;
         }
         order.resize((size_t)len);
         std::iota(order.begin(), order.end(), 0);
@@ -333,7 +336,7 @@ static sc_status_t unify_rows(const Plan& p, const int32_t* rowptr, const int32_
             } else {
                 // filler: explicit zero "marked non-zero", at the row's last (largest) column
                 t->col[o] = len > 0 ? (t->col[(size_t)d * n + len - 1] & 0x7fffffff) : 0;
-                if (p.dtype == SC_CB4_I8) t->col[o] |= (int32_t)0x80000000;  // weight must read as 0
+                if (is_codebook(p.dtype)) t->col[o] |= (int32_t)0x80000000;  // weight must read as 0
             }
         }
     }
@@ -438,7 +441,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     SlabGeom g{};
     sc_tuning_t want{};
     want.wg_threads = 1024;
-    want.wsrc = p->dtype == SC_CB4_I8 ? 0 : 1;
+    want.wsrc = is_codebook(p->dtype) ? 0 : 1;
     sc_status_t st = resolve_tuning(*p, want, &t, &g);
     if (st != SC_OK) st = resolve_tuning(*p, sc_tuning_t{}, &t, &g);
     if (st != SC_OK) return st;
@@ -446,7 +449,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     std::vector<uint8_t> packed;
     const uint8_t* theta_src = tab.val.data();
     size_t theta_bytes = cnt * wsz;
-    if (p->dtype == SC_CB4_I8) {
+    if (is_codebook(p->dtype)) {
         // two 4-bit indices per byte, even entry in the low nibble, over the flat [D*n] table
         packed.assign((cnt + 1) / 2, 0);
         for (size_t i = 0; i < cnt; ++i) packed[i / 2] |= (uint8_t)((tab.val[i] & 15) << ((i & 1) * 4));
@@ -459,7 +462,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
         if ((e = hipMalloc((void**)&p->d_lam, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc((void**)&p->d_lam_slab, cnt * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMalloc(&p->d_theta, theta_bytes)) != hipSuccess) return hip_status(e);
-        if (p->dtype != SC_CB4_I8) {
+        if (!is_codebook(p->dtype)) {
             // expanded {theta32, lambda} table plus 8 zeroed entries of slack: the symmetric kernel
             // reads whole 8-entry groups and the last one of a row may reach past the row
             const size_t wl_bytes = ((size_t)p->L.D * p->np + 8) * 8;
@@ -476,9 +479,10 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
         if ((e = hipMemcpyAsync(p->d_scales, scales, (size_t)p->L.D * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return hip_status(e);
     }
-    if (p->dtype == SC_CB4_I8) {
-        if ((e = hipMalloc((void**)&p->d_codebook, 16)) != hipSuccess) return hip_status(e);
-        if ((e = hipMemcpyAsync(p->d_codebook, codebook, 16, hipMemcpyHostToDevice, stream)) != hipSuccess)
+    if (is_codebook(p->dtype)) {
+        const size_t cbb = (size_t)codebook_bytes(p->dtype);
+        if ((e = hipMalloc((void**)&p->d_codebook, cbb)) != hipSuccess) return hip_status(e);
+        if ((e = hipMemcpyAsync(p->d_codebook, codebook, cbb, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return hip_status(e);
     }
     // canonical offsets into one padded sample
@@ -617,7 +621,7 @@ sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t
     info->act_bytes_per_sample = (int64_t)p->L.C * p->L.H * p->L.W * p->ex + (int64_t)p->L.D * p->P * p->Q * p->ey;
     const int64_t cnt = (int64_t)p->L.D * p->n;
     int64_t wb = cnt * 4;  // offsets
-    wb += p->dtype == SC_CB4_I8 ? (cnt + 1) / 2 + 16 : cnt * elem_size_w_native(p->dtype);
+    wb += is_codebook(p->dtype) ? (cnt + 1) / 2 + codebook_bytes(p->dtype) : cnt * elem_size_w_native(p->dtype);
     if (p->d_scales) wb += (int64_t)p->L.D * 4;
     info->weight_bytes = wb;
     info->tuning = p->tuning;
@@ -711,7 +715,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     }
     const bool pw = is_pointwise(p.L);
     const bool packable = p.dtype == SC_F16 || p.dtype == SC_I8;   // tuning.pack applies
-    if (pw && p.dtype != SC_CB4_I8) {
+    if (pw && !is_codebook(p.dtype)) {
         for (int threads : {512, 768, 1024}) {
             for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
               for (int wsrc : {1, 3}) for (int np_ : {1, 2, 4}) {
@@ -729,7 +733,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
-    if (pw && p.dtype != SC_CB4_I8) {
+    if (pw && !is_codebook(p.dtype)) {
         for (int threads : {512, 768, 1024}) {
             for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
                 sc_tuning_t t{};
@@ -744,7 +748,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
-    if (pw && p.dtype != SC_CB4_I8) {
+    if (pw && !is_codebook(p.dtype)) {
         for (int tq : {64, 128, 256}) for (int cc : {32, 64, 128, 256, 512}) {
             if (cc >= p.L.C) continue;
             for (int td : {0, 32, 64, 128}) {
@@ -764,7 +768,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
-    if (pw && p.dtype != SC_CB4_I8) {
+    if (pw && !is_codebook(p.dtype)) {
         for (int np_ : {1, 2}) for (int tq : {128, 192, 256, 384, 512}) for (int cc : {16, 32, 64, 128, 256}) {
             if (cc >= p.L.C) continue;
             for (int td : {0, 64, 128}) {
@@ -786,7 +790,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     for (int wsrc : {0, 1, 2, 3}) {
-        if (wsrc != 0 && p.dtype == SC_CB4_I8) continue;
+        if (wsrc != 0 && is_codebook(p.dtype)) continue;
         for (int wpc : {1, 2, 3, 4}) {
             for (int threads : {256, 512, 1024}) {
                 if (pw) {
@@ -817,7 +821,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     }
     // channel-chunked one-shot form on pointwise layers: for planes too small or too oddly sized
     // for the persistent forms
-    if (pw && p.dtype != SC_CB4_I8 && p.n > 0) {
+    if (pw && !is_codebook(p.dtype) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {32, 64, 128, 256}) {
             if (cc >= p.L.C) continue;
             for (int td : {0, 64, 128}) {
@@ -840,7 +844,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     // the same with several samples per workgroup, for planes of at most one wave of positions
-    if (p.dtype != SC_CB4_I8 && p.n > 0 && p.P * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 64) {
+    if (!is_codebook(p.dtype) && p.n > 0 && p.P * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 64) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
             if (cc >= p.L.C) continue;
             for (int td : {0, 32, 64, 128}) {
@@ -864,7 +868,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     // channel-chunked one-shot form (any layer shape): tiles several output rows high
-    if (!pw && p.dtype != SC_CB4_I8 && p.n > 0) {
+    if (!pw && !is_codebook(p.dtype) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128}) {
             if (cc >= p.L.C) continue;
             for (int td : {0, 64, 128}) {

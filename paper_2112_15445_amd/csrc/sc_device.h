@@ -15,14 +15,18 @@ template <> struct Types<SC_F32> { using X = float; using Y = float; using A = f
 template <> struct Types<SC_F16> { using X = __half; using Y = __half; using A = float; using WL = float; };
 template <> struct Types<SC_I8> { using X = int8_t; using Y = int32_t; using A = int32_t; using WL = int32_t; };
 template <> struct Types<SC_CB4_I8> { using X = int8_t; using Y = int32_t; using A = int32_t; using WL = int32_t; };
+template <> struct Types<SC_CB4_F16> { using X = __half; using Y = __half; using A = float; using WL = float; };
+
+template <sc_dtype_t DT> constexpr bool kHalfActs = DT == SC_F16 || DT == SC_CB4_F16;   // f16 in, f32 acc, f16 out
+template <sc_dtype_t DT> constexpr bool kCodebook = DT == SC_CB4_I8 || DT == SC_CB4_F16; // weights are 4-bit indices
 
 // Weight i of the flat [D*n] table, widened to the accumulator type.  For the 4-bit codebook
 // variant the table holds two indices per byte (even entry in the low nibble) and the value is
-// looked up in the 16-entry codebook the workgroup keeps in LDS; bit 31 of the entry's offset
-// marks a zero-valued filler of a padded row.
+// looked up in the 16-entry codebook (i8 or f16 centroids) the workgroup keeps in LDS; bit 31 of
+// the entry's offset marks a zero-valued filler of a padded row.
 template <sc_dtype_t DT>
 __device__ inline typename Types<DT>::WL load_weight(const void* theta, int64_t i, int lam,
-                                                     const int8_t* cb_lds)
+                                                     const void* cb_lds)
 {
     if constexpr (DT == SC_F32) return static_cast<const float*>(theta)[i];
     else if constexpr (DT == SC_F16) return __half2float(static_cast<const __half*>(theta)[i]);
@@ -30,19 +34,23 @@ __device__ inline typename Types<DT>::WL load_weight(const void* theta, int64_t 
     else {
         const uint8_t byte = static_cast<const uint8_t*>(theta)[i >> 1];
         const int idx = (byte >> ((i & 1) * 4)) & 15;
-        return lam < 0 ? 0 : (int32_t)cb_lds[idx];
+        if constexpr (DT == SC_CB4_I8) return lam < 0 ? 0 : (int32_t) static_cast<const int8_t*>(cb_lds)[idx];
+        else return lam < 0 ? 0.0f : __half2float(static_cast<const __half*>(cb_lds)[idx]);
     }
 }
 
+// Bytes of the 16-entry codebook of a clustered variant.
+template <sc_dtype_t DT> constexpr int kCodebookBytes = DT == SC_CB4_F16 ? 32 : 16;
+
 template <sc_dtype_t DT> __device__ inline typename Types<DT>::A widen(typename Types<DT>::X v)
 {
-    if constexpr (DT == SC_F16) return __half2float(v);
+    if constexpr (kHalfActs<DT>) return __half2float(v);
     else return (typename Types<DT>::A)v;
 }
 
 template <sc_dtype_t DT> __device__ inline typename Types<DT>::Y narrow(typename Types<DT>::A v)
 {
-    if constexpr (DT == SC_F16) return __float2half_rn(v);
+    if constexpr (kHalfActs<DT>) return __float2half_rn(v);
     else return v;
 }
 

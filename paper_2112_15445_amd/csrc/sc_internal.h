@@ -71,7 +71,7 @@ struct Plan {
     int32_t* d_first_j = nullptr;   // [D*nchunks] index within its row of a segment's first entry
     int2* d_wl32 = nullptr;         // [D*np] {theta widened to 32 bits, slab byte offset} for scalar loads
     float* d_scales = nullptr;      // [D]
-    int8_t* d_codebook = nullptr;   // [16]
+    void* d_codebook = nullptr;     // [16] i8 or f16 centroids
     sc_tuning_t tuning{};
     SlabGeom geom{};
     int last_N = 0;

@@ -67,12 +67,12 @@ __device__ inline int fdiv(int e, float inv) { return (int)(((float)e + 0.5f) * 
 
 template <sc_dtype_t DT> __device__ inline int weight_bits(typename Types<DT>::WL w)
 {
-    if constexpr (DT == SC_F32 || DT == SC_F16) return __float_as_int(w);
+    if constexpr (DT == SC_F32 || kHalfActs<DT>) return __float_as_int(w);
     else return w;
 }
 template <sc_dtype_t DT> __device__ inline typename Types<DT>::WL weight_from_bits(int b)
 {
-    if constexpr (DT == SC_F32 || DT == SC_F16) return __int_as_float(b);
+    if constexpr (DT == SC_F32 || kHalfActs<DT>) return __int_as_float(b);
     else return b;
 }
 
@@ -396,7 +396,7 @@ template <sc_dtype_t DT, int VPT, int WSRC>
 __global__ void
 slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
             const void* __restrict__ theta, const int32_t* __restrict__ lam,
-            const int2* __restrict__ wl32, const int8_t* __restrict__ codebook, const SlabArgs a)
+            const int2* __restrict__ wl32, const void* __restrict__ codebook, const SlabArgs a)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
@@ -405,7 +405,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     X* slab = reinterpret_cast<X*>(lds);
     int2* wst = reinterpret_cast<int2*>(lds + a.slab_bytes);
-    int8_t* cb_s = reinterpret_cast<int8_t*>(lds + a.slab_bytes + a.wcap * 8);
+    unsigned char* cb_s = lds + a.slab_bytes + a.wcap * 8;
 
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
@@ -475,8 +475,8 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
             }
         }
     }
-    if constexpr (DT == SC_CB4_I8) {
-        if (tid < 16) cb_s[tid] = codebook[tid];
+    if constexpr (kCodebook<DT>) {
+        if (tid < kCodebookBytes<DT>) cb_s[tid] = static_cast<const unsigned char*>(codebook)[tid];
     }
 
     // ---------------------------------------------------------------- per-lane output bookkeeping
@@ -1859,7 +1859,7 @@ template <sc_dtype_t DT>
 static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                              hipStream_t stream)
 {
-    if constexpr (DT != SC_CB4_I8) {
+    if constexpr (!kCodebook<DT>) {
         if (p.tuning.pipeline == 2) {
             // as for pipeline 1: an unaligned x takes the one-shot kernel
             if (a.dmab) return launch_sym<DT>(p, a, x, y, stream);
@@ -1872,7 +1872,7 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
         if (p.tuning.wsrc == 2) return launch_vpt<DT, 2>(p, a, x, y, grid, stream);
         if (p.tuning.wsrc == 3) return launch_vpt<DT, 3>(p, a, x, y, grid, stream);
     }
-    if constexpr (DT != SC_CB4_I8) {
+    if constexpr (!kCodebook<DT>) {
         if (p.tuning.wsrc == 1) return launch_vpt<DT, 1>(p, a, x, y, grid, stream);
     }
     return launch_vpt<DT, 0>(p, a, x, y, grid, stream);
@@ -1928,6 +1928,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
         case SC_F16: return launch_dt<SC_F16>(p, a, x, y, (int)grid64, stream);
         case SC_I8: return launch_dt<SC_I8>(p, a, x, y, (int)grid64, stream);
         case SC_CB4_I8: return launch_dt<SC_CB4_I8>(p, a, x, y, (int)grid64, stream);
+        case SC_CB4_F16: return launch_dt<SC_CB4_F16>(p, a, x, y, (int)grid64, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }

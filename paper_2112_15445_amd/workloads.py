@@ -15,7 +15,9 @@ the paper's GPU-results subsection, which are not available offline):
   * int8: symmetric, per-output-channel weight scale ``max|w| / 127``, per-tensor activation
     scale ``max|x| / 127``;
   * 4-bit codebook: 16 centroids at the N(0, 0.05) quantiles ``(k + 1/2) / 16`` quantised to
-    int8, every kept weight mapped to the nearest centroid (ties to the lower index).
+    int8, every kept weight mapped to the nearest centroid (ties to the lower index);
+  * 4-bit codebook with sixteen-bit centroids (the paper's 4b/16b configuration): the same 16
+    centroids and the same assignment, the centroids rounded to fp16, activations fp16.
 """
 from __future__ import annotations
 
@@ -44,7 +46,7 @@ class Layer:
     pad_w: int = 1
     N: int = 1
     sparsity: float = 0.9
-    dtype: str = "f32"          # f32 | f16 | i8 | cb4
+    dtype: str = "f32"          # f32 | f16 | i8 | cb4 | cb4h
     seed: int = BASE_SEED
 
     @property
@@ -78,7 +80,8 @@ class Layer:
 
     def elem_sizes(self) -> Tuple[float, int, float]:
         """(e_x, e_y, e_w) in bytes for this layer's dtype."""
-        return {"f32": (4, 4, 4.0), "f16": (2, 2, 2.0), "i8": (1, 4, 1.0), "cb4": (1, 4, 0.5)}[self.dtype]
+        return {"f32": (4, 4, 4.0), "f16": (2, 2, 2.0), "i8": (1, 4, 1.0), "cb4": (1, 4, 0.5),
+                "cb4h": (2, 2, 0.5)}[self.dtype]
 
     def algorithmic_bytes(self) -> float:
         """Bytes the method must move once: input + output + stored weights and offsets."""
@@ -89,6 +92,8 @@ class Layer:
             b += self.D * 4
         if self.dtype == "cb4":
             b += 16
+        if self.dtype == "cb4h":
+            b += 32
         return float(b)
 
     def replace(self, **kw) -> "Layer":
@@ -176,7 +181,13 @@ def config6() -> List[Layer]:
     return out
 
 
-CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6}
+def config7() -> List[Layer]:
+    """The paper's 4b/16b quantisation on the VGG-16-shaped stack at 90 %: weights as 4-bit indices
+    into 16 sixteen-bit centroids, half-precision activations (its quantisation-results table)."""
+    return [l.replace(name=l.name + "_cb4h") for l in _vgg(7, "cb4h", [0.9] * 13)]
+
+
+CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}
 
 
 def headline_layer() -> Layer:
@@ -282,7 +293,7 @@ def prepare(layer: Layer, N: Optional[int] = None, n: Optional[int] = None, ragg
     """Everything both sides need for one layer, in the dtype the layer names.
 
     Returns a dict with rowptr, colidx, values (f32 | f16 | i8 | u8 indices), x (f32 | f16 | i8),
-    scales (f32[D] or None), codebook (i8[16] or None), x_scale (float or None).
+    scales (f32[D] or None), codebook (i8[16] | f16[16] or None), x_scale (float or None).
     """
     rowptr, colidx, w = draw_weights_csr(layer, n=n, ragged=ragged)
     x = draw_input(layer, N)
@@ -302,6 +313,10 @@ def prepare(layer: Layer, N: Optional[int] = None, n: Optional[int] = None, ragg
         xq, xs = quantise_activations_int8(x)
         out.update(values=idx, scales=np.full(layer.D, sc, dtype=np.float32), codebook=cb, x=xq,
                    x_scale=xs)
+    elif layer.dtype == "cb4h":
+        cent, _, _ = codebook16()
+        idx = assign_codebook(w, cent)
+        out.update(values=idx, codebook=cent.astype(np.float16), x=x.astype(np.float16))
     else:
         raise ValueError(layer.dtype)
     return out

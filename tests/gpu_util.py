@@ -7,8 +7,8 @@ import oracle
 from paper_2112_15445_amd import binding as B
 from paper_2112_15445_amd import workloads as wl
 
-TOL = {"f32": 1e-5, "f16": 2e-2, "i8": 0.0, "cb4": 0.0}   # max|y - ref| / max|ref|, per layer
-NP_OUT = {"f32": np.float32, "f16": np.float16, "i8": np.int32, "cb4": np.int32}
+TOL = {"f32": 1e-5, "f16": 2e-2, "i8": 0.0, "cb4": 0.0, "cb4h": 2e-2}   # max|y - ref| / max|ref|, per layer
+NP_OUT = {"f32": np.float32, "f16": np.float16, "i8": np.int32, "cb4": np.int32, "cb4h": np.float16}
 
 
 def layer_desc(l: wl.Layer):

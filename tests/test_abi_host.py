@@ -87,6 +87,10 @@ def test_create_rejects_bad_arguments_on_the_host():
             scales=np.ones(2, np.float32))                                                      # no codebook
     _expect(3, mk, _layer(), B.SC_CB4_I8, GOOD["rowptr"], GOOD["colidx"], np.array([1, 16], np.uint8),
             scales=np.ones(2, np.float32), codebook=np.zeros(16, np.int8))                      # index > 15
+    _expect(4, mk, _layer(), B.SC_CB4_F16, GOOD["rowptr"], GOOD["colidx"], np.array([1, 2], np.uint8))  # no codebook
+    _expect(3, mk, _layer(), B.SC_CB4_F16, GOOD["rowptr"], GOOD["colidx"], np.array([1, 16], np.uint8),
+            codebook=np.zeros(16, np.float16))                                                  # index > 15
+    _expect(4, mk, _layer(), 5, GOOD["rowptr"], GOOD["colidx"], GOOD["values"])                 # unknown dtype
     _expect(5, mk, _layer(C=70000, H=200, W=200), B.SC_F32, **GOOD)                             # >= 2^31 elements
     _expect(2, B.Plan.create_ell, _layer(), B.SC_F32, -1, GOOD["colidx"], GOOD["values"])
     _expect(1, B.Plan.create_ell, _layer(), B.SC_F32, 1, None, GOOD["values"])

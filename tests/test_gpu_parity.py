@@ -11,7 +11,7 @@ import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
-DT = ["f32", "f16", "i8", "cb4"]
+DT = ["f32", "f16", "i8", "cb4", "cb4h"]
 
 
 def _both_variants(plan):
@@ -153,7 +153,7 @@ def test_all_zero_table_gives_zero_output(dtype):
         assert y.shape == (2, 4, 6, 6) and not np.any(y), label
 
 
-@pytest.mark.parametrize("dtype", ["f32", "cb4"])
+@pytest.mark.parametrize("dtype", ["f32", "cb4", "cb4h"])
 def test_long_rows_are_chunked(dtype):
     """n larger than one LDS weight stage / one gather row chunk (dense 3x3 over 160 channels)."""
     l = wl.Layer("long", 160, 6, 6, 6, 3, 3, 1, 1, 1, 1, N=1, sparsity=0.0, dtype=dtype, seed=5)
@@ -325,7 +325,7 @@ def test_autotune_installs_a_valid_tuning():
     assert plan.info().grid_size > 0
 
 
-@pytest.mark.parametrize("cfg,dtype", [(2, "f32"), (5, "i8"), (5, "cb4")])
+@pytest.mark.parametrize("cfg,dtype", [(2, "f32"), (5, "i8"), (5, "cb4"), (7, "cb4h")])
 def test_vgg_stack_layers_at_reduced_batch(cfg, dtype):
     layers = [l for l in wl.CONFIGS[cfg]() if l.dtype == dtype]
     assert len(layers) == 13

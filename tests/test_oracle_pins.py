@@ -317,6 +317,26 @@ def test_codebook_path_equals_int8_path_after_host_decode():
     assert np.array_equal(y_cb, _brute_sparse(x, rowptr, colidx, cb[idx], R, S, stride, pad))
 
 
+def test_sixteen_bit_codebook_path_equals_the_half_path_after_host_decode():
+    """4-bit indices into 16 fp16 centroids with fp16 activations (the 4b/16b configuration): the
+    same result as the fp16 path run on the decoded weights, and as the dense definition (torch
+    float64 conv2d on the decoded dense tensor), rounded once to fp16."""
+    rng = np.random.default_rng(61)
+    x, w, stride, pad = _rand_layer(rng, C=5, D=4)
+    x16 = x.astype(np.float16)
+    D, C, R, S = w.shape
+    rowptr, colidx, _ = _prune(rng, w, 0.5)
+    idx = rng.integers(0, 16, size=colidx.shape[0]).astype(np.uint8)
+    cb = np.sort(rng.normal(0, 0.05, size=16)).astype(np.float16)
+    y_cb = oracle.sparse_conv(x16, rowptr, colidx, idx, R, S, stride, pad, codebook=cb, out_dtype=np.float16)
+    y_h = oracle.sparse_conv(x16, rowptr, colidx, cb[idx], R, S, stride, pad, out_dtype=np.float16)
+    assert y_cb.dtype == np.float16 and np.array_equal(y_cb, y_h)
+    wd = oracle.dense_from_csr(rowptr, colidx, cb[idx].astype(np.float64), D, C, R, S)
+    t = torch.nn.functional.conv2d(torch.from_numpy(x16.astype(np.float64)), torch.from_numpy(wd),
+                                   stride=stride, padding=pad).numpy()
+    assert np.array_equal(y_cb, t.astype(np.float16))
+
+
 def test_fp16_operands_single_rounding():
     rng = np.random.default_rng(70)
     x, w, stride, pad = _rand_layer(rng, C=4, D=3)
