@@ -210,6 +210,23 @@ sc_status_t sparse_conv_plan_num_candidates(const sparse_conv_plan_t* plan, int3
 sc_status_t sparse_conv_plan_candidate(const sparse_conv_plan_t* plan, int32_t index,
                                        sc_tuning_t* tuning);
 
+/* Plan-time helper, host only: the paper's linear fixed-point quantiser (section "Quantisation",
+ * the mapping q = mu + sigma * round((x - mu) / sigma) with mu = 0 and a power-of-two step):
+ *     m         = saturate_at * max |x|                  (saturate_at = 1: no saturation; the paper
+ *                                                         saturates activations at 0.99)
+ *     int_bits  = ceil(log2(m)),  frac_bits = total_bits - int_bits - 1,  sigma = 2^-frac_bits
+ *     code      = round(clip(x, -m, m) / sigma)           nearest, ties to even
+ * saturated to the two's-complement range [-2^(total_bits-1), 2^(total_bits-1) - 1]; the quantised
+ * value is sigma * code.  One sigma for the whole array (per tensor), so the codes of a weight
+ * tensor and of an activation tensor feed SC_I8 directly, with 2^-frac_bits as the scale.
+ *   x      [count] host f32, finite          codes [count] host i8
+ *   total_bits 2..8                          saturate_at in (0, 1]
+ *   *frac_bits receives frac_bits (may be negative or exceed total_bits; all-zero input: total_bits - 1)
+ * Errors: SC_ERR_NULL (x or codes NULL with count > 0, frac_bits NULL), SC_ERR_UNSUPPORTED
+ * (total_bits or saturate_at out of range), SC_ERR_RANGE (a non-finite element). */
+sc_status_t sparse_conv_quantize_pow2(const float* x, size_t count, int32_t total_bits,
+                                      float saturate_at, int8_t* codes, int32_t* frac_bits);
+
 const char* sparse_conv_status_string(sc_status_t status);
 
 #ifdef __cplusplus

@@ -13,6 +13,7 @@ gathers and accumulates one output pixel at a time.
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 import subprocess
 from typing import Dict, Optional, Tuple
@@ -198,3 +199,31 @@ def sparse_conv(x, rowptr, colidx, values, R, S, stride=(1, 1), pad=(0, 0), code
     """Direct sparse convolution; result rounded once to ``out_dtype`` (default: accumulator type)."""
     y = sparse_conv_steps(x, rowptr, colidx, values, R, S, stride, pad, codebook)["y"]
     return y if out_dtype is None else _round_out(y, out_dtype)
+
+
+def quantise_pow2(x: np.ndarray, total_bits: int = 8, saturate_at: float = 1.0) -> Tuple[np.ndarray, int]:
+    """The paper's linear fixed-point quantiser (section "Quantisation": q = sigma * round(x / sigma)
+    with mu = 0, sigma = 2^-frac_bits, int_bits = ceil(log2 max|x|), frac_bits = total_bits -
+    int_bits - 1), per tensor.  Returns (integer codes round(x / sigma) as int8, frac_bits).
+
+    Readings taken where the text is silent: "round" is round-to-nearest with ties to even; codes
+    saturate to the two's-complement range of total_bits (a maximum that is an exact power of two
+    would otherwise need one more bit); the activation saturation threshold (0.99 in the paper's
+    experiments) scales the maximum before int_bits is taken and clips the data to it; an all-zero
+    tensor gets int_bits = 0.
+    """
+    xd = np.asarray(x, dtype=np.float64)
+    assert np.all(np.isfinite(xd)) and 2 <= total_bits <= 8 and 0.0 < saturate_at <= 1.0
+    m = float(saturate_at) * (float(np.max(np.abs(xd))) if xd.size else 0.0)
+    int_bits = int(math.ceil(math.log2(m))) if m > 0.0 else 0
+    # log2 of an exact power of two is exact in IEEE double; guard the neighbours against a last-bit error
+    if m > 0.0:
+        while 2.0 ** int_bits < m:
+            int_bits += 1
+        while 2.0 ** (int_bits - 1) >= m:
+            int_bits -= 1
+    frac_bits = total_bits - int_bits - 1
+    sigma = 2.0 ** (-frac_bits)
+    code = np.rint(np.clip(xd, -m, m) / sigma)
+    code = np.clip(code, -(2 ** (total_bits - 1)), 2 ** (total_bits - 1) - 1)
+    return code.astype(np.int8), frac_bits

@@ -30,7 +30,7 @@ EXPORTS = [
     "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning",
     "sparse_conv_plan_get_tuning", "sparse_conv_workspace_size", "sparse_conv_workspace_size_max",
     "sparse_conv_forward", "sparse_conv_plan_autotune", "sparse_conv_plan_num_candidates",
-    "sparse_conv_plan_candidate", "sparse_conv_status_string",
+    "sparse_conv_plan_candidate", "sparse_conv_quantize_pow2", "sparse_conv_status_string",
 ]
 
 
@@ -98,6 +98,7 @@ def lib() -> ctypes.CDLL:
     L.sparse_conv_plan_autotune.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.sparse_conv_plan_num_candidates.argtypes = [vp, P(i32)]
     L.sparse_conv_plan_candidate.argtypes = [vp, i32, P(sc_tuning_t)]
+    L.sparse_conv_quantize_pow2.argtypes = [vp, sz, i32, ctypes.c_float, vp, P(i32)]
     L.sparse_conv_status_string.argtypes = [ctypes.c_int]
     L.sparse_conv_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -122,6 +123,17 @@ def _hp(a: Optional[np.ndarray]):
 
 _VALUE_NP = {SC_F32: np.float32, SC_F16: np.float16, SC_I8: np.int8, SC_CB4_I8: np.uint8, SC_CB4_F16: np.uint8}
 _CODEBOOK_NP = {SC_CB4_I8: np.int8, SC_CB4_F16: np.float16}
+
+
+def quantize_pow2(x: np.ndarray, total_bits: int = 8, saturate_at: float = 1.0):
+    """sparse_conv_quantize_pow2: (codes int8 with the shape of x, frac_bits)."""
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.empty(xa.shape, dtype=np.int8)
+    fb = ctypes.c_int32(0)
+    _check(lib().sparse_conv_quantize_pow2(_hp(xa) if xa.size else None, xa.size, total_bits, saturate_at,
+                                           _hp(codes) if xa.size else None, ctypes.byref(fb)),
+           "sparse_conv_quantize_pow2")
+    return codes, int(fb.value)
 
 
 def make_layer(C, D, H, W, R, S, stride=(1, 1), pad=(0, 0)) -> sc_layer_t:

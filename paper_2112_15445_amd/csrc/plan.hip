@@ -502,6 +502,37 @@ using namespace sc;
 // ------------------------------------------------------------------------------------------------
 extern "C" {
 
+sc_status_t sparse_conv_quantize_pow2(const float* x, size_t count, int32_t total_bits, float saturate_at,
+                                      int8_t* codes, int32_t* frac_bits)
+{
+    if (!frac_bits || (count > 0 && (!x || !codes))) return SC_ERR_NULL;
+    if (total_bits < 2 || total_bits > 8 || !(saturate_at > 0.0f && saturate_at <= 1.0f)) return SC_ERR_UNSUPPORTED;
+    double amax = 0.0;
+    for (size_t i = 0; i < count; ++i) {
+        if (!std::isfinite(x[i])) return SC_ERR_RANGE;
+        amax = std::max(amax, std::fabs((double)x[i]));
+    }
+    const double m = (double)saturate_at * amax;
+    int ib = 0;
+    if (m > 0.0) {
+        // ceil(log2(m)) without a logarithm: m = f * 2^e with f in [0.5, 1)
+        int e = 0;
+        const double f = std::frexp(m, &e);
+        ib = f == 0.5 ? e - 1 : e;
+    } else {
+        ib = 0;
+    }
+    const int fb = total_bits - ib - 1;
+    *frac_bits = fb;
+    const double lo = -std::ldexp(1.0, total_bits - 1), hi = std::ldexp(1.0, total_bits - 1) - 1.0;
+    for (size_t i = 0; i < count; ++i) {
+        const double v = std::min(std::max((double)x[i], -m), m);
+        const double c = std::nearbyint(std::ldexp(v, fb));   // default rounding mode: ties to even
+        codes[i] = (int8_t)std::min(std::max(c, lo), hi);
+    }
+    return SC_OK;
+}
+
 const char* sparse_conv_status_string(sc_status_t s)
 {
     switch (s) {

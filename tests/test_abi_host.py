@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "sparse_conv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sparse_conv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(sparse_conv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -115,3 +115,34 @@ def test_product_path_has_no_cpu_fallback():
             if f.endswith((".py", ".hip", ".h")):
                 body = open(os.path.join(root, f)).read()
                 assert "import oracle" not in body and "from oracle" not in body, f
+
+
+def test_pow2_quantiser_helper_matches_the_oracle_bit_for_bit():
+    """sparse_conv_quantize_pow2 (host code of the library) against the oracle's statement of the
+    same formulas: identical codes and frac_bits over magnitudes, bit widths and saturation levels."""
+    import oracle
+    rng = np.random.default_rng(7)
+    for scale in (1e-3, 0.05, 1.0, 37.0, 1024.0):
+        x = rng.normal(0, scale, size=4000).astype(np.float32)
+        x[:8] = [0.0, scale, -scale, 0.5 * scale, 1.5 * scale, -2.5 * scale, 2.0 ** -20, -0.0]
+        for bits in (8, 5, 2):
+            for sat in (1.0, 0.99, 0.5):
+                c, f = B.quantize_pow2(x, bits, sat)
+                co, fo = oracle.quantise_pow2(x, bits, sat)
+                assert f == fo and np.array_equal(c, co), (scale, bits, sat)
+    for x in (np.array([1.0, -1.0, 0.5], np.float32), np.array([4.0], np.float32), np.zeros(5, np.float32),
+              np.zeros(0, np.float32)):
+        c, f = B.quantize_pow2(x, 8)
+        co, fo = oracle.quantise_pow2(x, 8)
+        assert f == fo and np.array_equal(c, co)
+    fb = ctypes.c_int32()
+    L = B.lib()
+    one = np.ones(1, np.float32)
+    out = np.zeros(1, np.int8)
+    p = lambda a: ctypes.c_void_p(a.ctypes.data)
+    assert L.sparse_conv_quantize_pow2(None, 1, 8, 1.0, p(out), ctypes.byref(fb)) == 1
+    assert L.sparse_conv_quantize_pow2(p(one), 1, 8, 1.0, p(out), None) == 1
+    assert L.sparse_conv_quantize_pow2(p(one), 1, 9, 1.0, p(out), ctypes.byref(fb)) == 4
+    assert L.sparse_conv_quantize_pow2(p(one), 1, 8, 0.0, p(out), ctypes.byref(fb)) == 4
+    bad = np.array([np.inf], np.float32)
+    assert L.sparse_conv_quantize_pow2(p(bad), 1, 8, 1.0, p(out), ctypes.byref(fb)) == 5

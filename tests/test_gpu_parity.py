@@ -592,3 +592,28 @@ def test_full_size_half_precision_layers_packed_and_small_plane_forms(name, extr
     y = G.run_gpu(plan, data["x"])
     for b in (0, l.N - 1):
         G.check(l, y[b:b + 1], G.oracle_out(l, data, samples=[b]), f"{name} {t} sample {b}")
+
+
+def test_power_of_two_quantised_layer_is_bit_exact():
+    """The paper's linear quantiser (per-tensor power-of-two step, activations saturated at 0.99)
+    applied by the library's plan-time helper, then the int8 path: same codes as the oracle's
+    quantiser, same int32 outputs as the oracle's convolution of those codes."""
+    import oracle
+    l = wl.Layer("pow2", 48, 40, 14, 14, 3, 3, 1, 1, 1, 1, N=4, sparsity=0.85, dtype="f32", seed=71)
+    data = wl.prepare(l)
+    wq, wf = B.quantize_pow2(data["values"], 8)
+    xq, xf = B.quantize_pow2(data["x"], 8, 0.99)
+    wo, wfo = oracle.quantise_pow2(data["values"], 8)
+    xo, xfo = oracle.quantise_pow2(data["x"], 8, 0.99)
+    assert (wf, xf) == (wfo, xfo) == (9, 7) and np.array_equal(wq, wo) and np.array_equal(xq, xo)
+    li = l.replace(dtype="i8")
+    qd = dict(data, values=wq, x=xq, scales=np.full(l.D, 2.0 ** -wf, np.float32), codebook=None)
+    ref = G.oracle_out(li, qd)
+    assert ref.dtype == np.int32 and np.any(ref)
+    plan = G.make_plan(li, qd)
+    for label in _both_variants(plan):
+        G.check(li, G.run_gpu(plan, xq), ref, label)
+    # dequantised, the result is the fp32 layer's up to the quantisation noise
+    y = ref.astype(np.float64) * 2.0 ** -(wf + xf)
+    yf = G.oracle_out(l, data).astype(np.float64)
+    assert np.max(np.abs(y - yf)) / np.max(np.abs(yf)) < 0.05

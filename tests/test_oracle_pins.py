@@ -351,6 +351,50 @@ def test_fp16_operands_single_rounding():
     assert np.array_equal(y, t.astype(np.float16))
 
 
+# ------------------------------------------------------------------ the linear fixed-point quantiser
+def test_pow2_quantiser_worked_examples():
+    """Values fixed by the paper's formulas (section "Quantisation"): int_bits = ceil(log2 max|x|),
+    frac_bits = total_bits - int_bits - 1, sigma = 2^-frac_bits, code = round(x / sigma)."""
+    # max 0.75 -> int_bits 0, frac_bits 7, sigma 1/128
+    c, f = oracle.quantise_pow2(np.array([0.3, -0.75, 0.1, 0.0]), 8)
+    assert f == 7 and c.tolist() == [38, -96, 13, 0]
+    # max 3.0 -> int_bits 2, frac_bits 5, sigma 1/32
+    c, f = oracle.quantise_pow2(np.array([3.0, -1.0, 0.015625, 2.984375]), 8)
+    assert f == 5 and c.tolist() == [96, -32, 0, 96]          # 0.5 and 95.5 are ties: to even
+    # max 0.05 -> int_bits ceil(-4.32) = -4, frac_bits 11: small tensors gain resolution
+    c, f = oracle.quantise_pow2(np.array([0.05, -0.025]), 8)
+    assert f == 11 and c.tolist() == [102, -51]
+    # a maximum that is an exact power of two needs one more bit than the formula grants: saturates
+    c, f = oracle.quantise_pow2(np.array([1.0, -1.0, 0.5]), 8)
+    assert f == 7 and c.tolist() == [127, -128, 64]
+    # fewer bits, and the all-zero tensor
+    c, f = oracle.quantise_pow2(np.array([0.9, -0.3]), 4)
+    assert f == 3 and c.tolist() == [7, -2]
+    c, f = oracle.quantise_pow2(np.zeros(3), 8)
+    assert f == 7 and c.tolist() == [0, 0, 0]
+    # saturation threshold: the maximum is scaled first (1.3 * 0.75 = 0.975 -> int_bits 0) and the data clipped to it
+    c, f = oracle.quantise_pow2(np.array([1.3, -0.2]), 8, saturate_at=0.75)
+    assert f == 7 and c.tolist() == [125, -26]                # 0.975 * 128 = 124.8, -25.6
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_pow2_quantiser_properties(seed):
+    rng = np.random.default_rng(90 + seed)
+    x = (rng.normal(0, 10.0 ** rng.integers(-3, 3), size=500)).astype(np.float32)
+    for bits in (8, 6, 3):
+        c, f = oracle.quantise_pow2(x, bits)
+        sigma = 2.0 ** -f
+        m = float(np.max(np.abs(x)))
+        assert 2.0 ** (bits - 1 - f) >= m > 2.0 ** (bits - 2 - f)          # int_bits = ceil(log2 max)
+        q = sigma * c.astype(np.float64)
+        unsat = np.abs(x.astype(np.float64)) <= sigma * (2 ** (bits - 1) - 1)
+        assert np.all(np.abs(q[unsat] - x[unsat]) <= sigma / 2)             # nearest grid point
+        assert np.all(np.diff(c[np.argsort(x, kind="stable")].astype(int)) >= 0)   # monotone
+        c2, f2 = oracle.quantise_pow2(q, bits)                              # the grid is a fixed point
+        if int(np.max(np.abs(c.astype(int)))) > 2 ** (bits - 2):           # ... while the maximum keeps its octave
+            assert f2 == f and np.array_equal(c2, c)
+
+
 # ------------------------------------------------------------------ the pins have teeth
 def test_planted_mistakes_are_caught():
     """Re-run step 4 of the oracle with deliberately wrong step-2 / step-3 results and check that
