@@ -191,7 +191,12 @@ sc_status_t sparse_conv_workspace_size(const sparse_conv_plan_t* plan, int32_t N
 sc_status_t sparse_conv_workspace_size_max(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
 
 /* Y = conv(X): x_dev [N,C,H,W] unpadded, y_dev [N,D,P,Q], both contiguous device memory in the
- * plan's storage types.  Errors: SC_ERR_NULL, SC_ERR_SHAPE (N <= 0), SC_ERR_WORKSPACE, SC_ERR_HIP. */
+ * plan's storage types, aligned to their element size.  Asynchronous on `stream`; allocates nothing.
+ * The pipelined launch shapes (tuning.pipeline = 1 or 2) copy rows with 16-byte (4-byte where the
+ * rows allow no more) direct-to-LDS loads and need x_dev aligned to that; with tuning.pack they
+ * also store 4 / 16 bytes at a time and need y_dev aligned to that: such a shape with other pointers
+ * returns SC_ERR_UNSUPPORTED and launches nothing.  Every other shape takes any pointers.
+ * Errors: SC_ERR_NULL, SC_ERR_SHAPE (N <= 0), SC_ERR_WORKSPACE, SC_ERR_UNSUPPORTED, SC_ERR_HIP. */
 sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
                                 int32_t N, void* workspace_dev, size_t workspace_bytes,
                                 void* stream);
@@ -199,6 +204,8 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
 /* Per-layer launch-shape search (the gfx950 counterpart of the paper's empirical tuning of sb_S):
  * times every candidate tuning that fits the layer on the caller's buffers (y_dev is overwritten)
  * with HIP events on `stream`, keeps the fastest, and leaves it installed.  Synchronises.
+ * Candidates that these pointers rule out (see sparse_conv_forward) are skipped, so the installed
+ * shape is valid for buffers aligned like x_dev and y_dev.
  * workspace must hold sparse_conv_workspace_size_max(plan, N). */
 sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
                                       int32_t N, void* workspace_dev, size_t workspace_bytes,

@@ -617,3 +617,36 @@ def test_power_of_two_quantised_layer_is_bit_exact():
     y = ref.astype(np.float64) * 2.0 ** -(wf + xf)
     yf = G.oracle_out(l, data).astype(np.float64)
     assert np.max(np.abs(y - yf)) / np.max(np.abs(yf)) < 0.05
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_autotune_and_forward_with_unaligned_device_pointers(dtype):
+    """x and y that start one element into their allocations: the launch shapes that need 16-byte
+    aligned rows are skipped by the autotuner (forward reports them as unsupported instead of
+    launching), and the shape it installs gives the oracle's result."""
+    import torch
+    l = wl.Layer("unal", 32, 24, 16, 16, 1, 1, 1, 1, 0, 0, N=6, sparsity=0.7, dtype=dtype, seed=81)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    x0 = G.to_device(data["x"])
+    xbuf = torch.empty(x0.numel() + 8, dtype=x0.dtype, device="cuda")
+    x = xbuf[1:1 + x0.numel()].view(x0.shape)
+    x.copy_(x0)
+    ybuf = torch.full((l.N * l.D * l.P * l.Q + 8,), 7, dtype=B.torch_out_dtype(plan.dtype), device="cuda")
+    y = ybuf[1:1 + l.N * l.D * l.P * l.Q].view(l.N, l.D, l.P, l.Q)
+    assert x.data_ptr() % 16 != 0 and y.data_ptr() % 16 != 0
+    ws = torch.empty(max(plan.workspace_size_max(l.N), 16), dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    plan.autotune(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), st)
+    t = plan.get_tuning().as_dict()
+    print("case unaligned", dtype, t, flush=True)
+    plan.forward(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), st)
+    torch.cuda.synchronize()
+    G.check(l, G.to_host(y), ref, f"unaligned {t}")
+    assert int(ybuf[0]) == 7 and int(ybuf[-1]) == 7          # nothing written outside y
+    # a pipelined shape asked for explicitly installs, but forward refuses these pointers
+    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=512, pipeline=2, tile_q=64, chunk_c=8)
+    with pytest.raises(B.SparseConvError) as e:
+        plan.forward(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), st)
+    assert e.value.status == 4
