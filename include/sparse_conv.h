@@ -121,12 +121,16 @@ typedef struct {
                            filler entries that unify the row lengths are left out of the per-chunk
                            segments), 0 = the unified table of the method.  For measuring what the
                            padding costs on tables whose rows differ in length */
-    int32_t pack;       /* SLAB with chunk_c > 0 and wsrc = 1, SC_F16 / SC_I8, one sample per workgroup:
-                           1 = every lane owns the 2 (f16) or 4 (i8) adjacent positions of one 32-bit word
-                           of the staged tile, so one LDS read feeds that many multiply-adds (at most 8
-                           positions per lane; with pipeline = 0 on a layer that is not pointwise LDS then
-                           holds 2 / 4 shifted images of each chunk); 0 = one position per LDS read.
-                           With pipeline = 1 or 2 y must be 4-byte (f16) / 16-byte (i8) aligned */
+    int32_t pack;       /* SLAB with chunk_c > 0 and wsrc = 1, one sample per workgroup: packed positions.
+                           1 (SC_F16 / SC_I8) = every lane owns the 2 / 4 adjacent positions of one 32-bit
+                           word of the staged tile; 2 (SC_F32 / SC_F16) = the 4 / 8 adjacent positions of one
+                           128-bit word.  One LDS read then feeds that many multiply-adds (at most 8
+                           positions per lane), and 128-bit LDS reads move more bytes per clock than 32-bit
+                           ones.  With pipeline = 0 on a layer whose offsets are not whole words (not
+                           pointwise) LDS holds as many shifted images of each chunk as a word has
+                           positions.  0 = one position per LDS read.  With pipeline = 1 or 2 a lane's results
+                           leave as one store and y must be aligned to it (4 bytes for pack = 1 with f16,
+                           16 bytes otherwise); pack = 2 there needs 16-byte aligned rows */
 } sc_tuning_t;
 
 typedef struct {

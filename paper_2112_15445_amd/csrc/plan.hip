@@ -97,10 +97,13 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.vpt = (o.F + kWave - 1) / kWave;
     o.pack = 1;
     if (pack) {
-        // packed positions: chunked forms, 16- or 8-bit activations, one sample per workgroup;
-        // a lane owns `pack` adjacent positions per 32-bit word, at most 8 positions
-        if (chunk_c <= 0 || samples > 1 || (p.dtype != SC_F16 && p.dtype != SC_I8)) return false;
-        o.pack = 4 / p.ex;
+        // packed positions: chunked forms, one sample per workgroup; a lane owns the adjacent
+        // positions of one 32-bit word (pack = 1: 16- or 8-bit activations) or of one 128-bit word
+        // (pack = 2: 32- or 16-bit activations), at most 8 positions
+        if (chunk_c <= 0 || samples > 1) return false;
+        if (pack == 1 && p.dtype != SC_F16 && p.dtype != SC_I8) return false;
+        if (pack == 2 && p.dtype != SC_F32 && p.dtype != SC_F16) return false;
+        o.pack = (pack == 2 ? 16 : 4) / p.ex;
         o.vpt = (o.F + kWave * o.pack - 1) / (kWave * o.pack);
         if (o.vpt * o.pack > 8) return false;
     }
@@ -184,6 +187,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (pipeline == 1 && !o.vec) return false;
     if (pipeline == 2 && o.dmab == 0) return false;
     if (pack && pipeline >= 1 && o.dmab == 0) return false;      // whole words per row and tile
+    if (pack == 2 && pipeline >= 1 && o.dmab != 16) return false;
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -207,7 +211,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.chunk_c == 0) t.tile_d = 0;
     if (t.ragged < 0 || t.ragged > 1) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.ragged = 0;
-    if (t.pack < 0 || t.pack > 1) return SC_ERR_UNSUPPORTED;
+    if (t.pack < 0 || t.pack > 2) return SC_ERR_UNSUPPORTED;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
@@ -745,7 +749,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         }
     }
     const bool pw = is_pointwise(p.L);
-    const bool packable = p.dtype == SC_F16 || p.dtype == SC_I8;   // tuning.pack applies
+    const bool packable = p.dtype == SC_F16 || p.dtype == SC_I8;   // tuning.pack = 1 applies
+    const bool wide = p.dtype == SC_F32 || p.dtype == SC_F16;      // tuning.pack = 2 applies
     if (pw && !is_codebook(p.dtype)) {
         for (int threads : {512, 768, 1024}) {
             for (int tq : {32, 64, 96, 128, 192, 256, 384, 512}) {
@@ -796,6 +801,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_d = td;
                 push(t);
                 if (packable) { t.pack = 1; push(t); t.tile_q = 2 * tq; push(t); }
+                if (wide && tq >= 128) { t.pack = 2; t.tile_q = 2 * tq; push(t); }
             }
         }
     }
@@ -817,6 +823,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_d = td;
                 push(t);
                 if (packable) { t.pack = 1; push(t); }
+                if (wide && (tq == 256 || tq == 512)) { t.pack = 2; push(t); }
             }
         }
     }
@@ -923,12 +930,13 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     }
     // 16- and 8-bit activations: the chunked one-shot form with packed positions (one LDS read per
     // 2 or 4 positions), tiles of up to 8 positions per lane
-    if ((p.dtype == SC_F16 || p.dtype == SC_I8) && p.n > 0) {
+    if ((packable || wide) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
             if (cc > p.L.C && cc != 16) continue;
             for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
-                for (int tile : {2, 4, 7, 8, 14, 16, 28}) {
+                for (int tile : {2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2}) {
+                    if ((pk == 1 && !packable) || (pk == 2 && !wide)) continue;
                     sc_tuning_t t{};
                     t.variant = SC_VARIANT_SLAB;
                     t.wsrc = 1;
@@ -938,7 +946,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_q = pw ? 32 * tile : p.Q;     // pointwise: 64 .. 512 (and 224, 896 -> clipped by the fit)
                     t.chunk_c = cc;
                     t.tile_d = td;
-                    t.pack = 1;
+                    t.pack = pk;
                     push(t);
                 }
             }

@@ -47,6 +47,13 @@ def _both_variants(plan):
                                                 "tile_q": 128, "pack": 1}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "chunk_c": 7,
                                                 "tile_q": 64, "tile_d": 5, "pack": 1}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 2, "wg_threads": 256, "pack": 2}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "chunk_c": 3, "tile_d": 4, "wg_threads": 128, "tile_p": 2,
+                                                "tile_q": 1000, "pack": 2}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 1, "wg_threads": 512, "chunk_c": 5,
+                                                "tile_q": 128, "pack": 2}),
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "chunk_c": 7,
+                                                "tile_q": 64, "tile_d": 5, "pack": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
@@ -650,3 +657,43 @@ def test_autotune_and_forward_with_unaligned_device_pointers(dtype):
     with pytest.raises(B.SparseConvError) as e:
         plan.forward(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), st)
     assert e.value.status == 4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_positions_packed_in_128_bit_words(dtype):
+    """tuning.pack = 2: a lane owns the 4 (f32) or 8 (f16) adjacent positions of one 128-bit word, read
+    with one LDS instruction.  Pointwise layers through the one-shot and both pipelined chunked
+    kernels (tiles of one and two words per lane, ragged last tile, output-channel blocks), other
+    layers through the one-shot kernel with its shifted images (odd offsets, strides, padding)."""
+    cases = (
+        (wl.Layer("w1x1", 72, 50, 20, 28, 1, 1, 1, 1, 0, 0, N=4, sparsity=0.8, dtype=dtype, seed=91),
+         [{"chunk_c": 16, "tile_q": 256}, {"chunk_c": 24, "tile_q": 512, "tile_d": 16}, {"chunk_c": 72, "tile_q": 128},
+          {"pipeline": 1, "tile_q": 256, "chunk_c": 16, "producers": 1},
+          {"pipeline": 1, "tile_q": 512, "chunk_c": 24, "tile_d": 32, "producers": 2},
+          {"pipeline": 2, "tile_q": 256, "chunk_c": 32}, {"pipeline": 2, "tile_q": 128, "chunk_c": 9, "tile_d": 24},
+          {"pipeline": 2, "tile_q": 512, "chunk_c": 16, "ragged": 1}]),
+        (wl.Layer("w3x3", 20, 24, 28, 28, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.8, dtype=dtype, seed=92),
+         [{"tile_p": 4, "chunk_c": 4}, {"tile_p": 8, "chunk_c": 5, "tile_d": 8}, {"tile_p": 2, "chunk_c": 8, "wg_per_cu": 2}]),
+        (wl.Layer("w3x3s2", 12, 10, 29, 27, 3, 3, 2, 2, 1, 1, N=2, sparsity=0.7, dtype=dtype, seed=93),
+         [{"tile_p": 4, "chunk_c": 3}, {"tile_p": 14, "chunk_c": 4}]),
+        (wl.Layer("w1x1odd", 40, 12, 7, 7, 1, 1, 1, 1, 0, 0, N=5, sparsity=0.6, dtype=dtype, seed=94),
+         [{"tile_q": 49, "chunk_c": 8}]))
+    for l, tunings in cases:
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        ran = 0
+        for extra in tunings:
+            try:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, pack=2,
+                                **{"wg_per_cu": 1, **extra})
+            except B.SparseConvError as e:
+                assert e.status == 4
+                print("does not fit", l.name, dtype, extra, flush=True)
+                continue
+            t = plan.get_tuning().as_dict()
+            assert t["pack"] == 2 and t["pipeline"] == extra.get("pipeline", 0)
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+            ran += 1
+        assert ran >= 1, l.name
