@@ -38,9 +38,10 @@ INFINITY_CACHE_BYTES = 256 << 20
 # (FETCH_SIZE / WRITE_SIZE, scaled by the same counters on a plain copy kernel); the summaries and
 # the commands that produced them are under profiles/.  Keyed by workload name; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 50319.0 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25088.0 KiB x 1.000, measured
-    # for the persistent slab kernel the autotuner picks (the other slab kernels move the same bytes)
-    "s56_reduce1x1_sp90": int((50319.0 * 2.000 + 25088.0 * 1.000) * 1024),
+    # FETCH_SIZE 50394.5 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25123.9 KiB x 1.000, measured
+    # for the persistent chunked slab kernel the autotuner picks (the other slab kernels move the same
+    # bytes to within 0.2 %)
+    "s56_reduce1x1_sp90": int((50394.5 * 2.000 + 25123.9 * 1.000) * 1024),
 }
 
 

@@ -823,7 +823,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_d = td;
                 push(t);
                 if (packable) { t.pack = 1; push(t); }
-                if (wide && (tq == 256 || tq == 512)) { t.pack = 2; push(t); }
+                if (wide && (tq == 256 || tq == 512)) { t.pack = 2; push(t); t.wg_threads = 768; push(t); }
             }
         }
     }

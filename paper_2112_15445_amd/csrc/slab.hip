@@ -1582,12 +1582,14 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
 {
     if constexpr (E == 1) {
         if (p.tuning.wsrc == 3) return launch_cc_w<DT, VPT, MS, E, true, false>(p, a, x, y, grid, stream);
+    }
+    {
         // pointwise layer, one tile per plane, chunk images that are whole 16-byte aligned blocks
-        // of the input: staged as a plain copy
+        // of the input (and, with packed positions, no shifted images): staged as a plain copy
         const SlabGeom& g = p.geom;
         const int64_t chunk_bytes = (int64_t)g.CC * g.chan_pitch * p.ex;
         if (g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
-            ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
+            g.copies == 1 && ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
             return launch_cc_w<DT, VPT, MS, E, false, true>(p, a, x, y, grid, stream);
     }
     if constexpr (!MS) {

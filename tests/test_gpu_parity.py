@@ -535,7 +535,9 @@ def test_pointwise_whole_plane_tiles_staged_as_a_plain_copy(dtype):
              [{"chunk_c": 16, "tile_q": 49}, {"chunk_c": 32, "tile_q": 49, "sub_batch": 2},
               {"chunk_c": 16, "tile_q": 49, "sub_batch": 4, "tile_d": 8}]),
             (wl.Layer("flat14", 40, 20, 14, 14, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.7, dtype=dtype, seed=52),
-             [{"chunk_c": 8, "tile_q": 196}, {"chunk_c": 40, "tile_q": 256, "tile_d": 8}])):
+             [{"chunk_c": 8, "tile_q": 196}, {"chunk_c": 40, "tile_q": 256, "tile_d": 8}] +
+             ([{"chunk_c": 8, "tile_q": 196, "pack": 2, "tile_d": 8}] if dtype == "f32" else []) +
+             ([{"chunk_c": 16, "tile_q": 196, "pack": 1}] if dtype != "f32" else []))):
         data = wl.prepare(l, ragged=True)
         ref = G.oracle_out(l, data)
         plan = G.make_plan(l, data)
