@@ -989,8 +989,18 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
     if (hipEventCreate(&e0) != hipSuccess) return SC_ERR_HIP;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SC_ERR_HIP; }
     sc_status_t st = SC_OK;
-    float best = INFINITY;
-    int best_i = -1;
+    // mean time of `reps` launches of the installed tuning (negative: a call failed, st says how)
+    auto time_launches = [&](int reps) -> float {
+        if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; return -1.0f; }
+        for (int r = 0; r < reps && st == SC_OK; ++r)
+            st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
+        if (st != SC_OK) return -1.0f;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = SC_ERR_HIP; return -1.0f; }
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = SC_ERR_HIP; return -1.0f; }
+        return ms / (float)reps;
+    };
+    std::vector<std::pair<float, int>> timed;     // (ms per launch, candidate)
     for (size_t i = 0; i < cands.size() && st == SC_OK; ++i) {
         st = sparse_conv_plan_set_tuning(plan, &cands[i], stream);
         if (st == SC_ERR_UNSUPPORTED) { st = SC_OK; continue; }
@@ -1001,22 +1011,40 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
         // need aligned x / y -- is skipped, not an error)
         if (st == SC_ERR_UNSUPPORTED) { st = SC_OK; continue; }
         if (st != SC_OK) break;
-        if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; break; }
-        st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
-        if (st != SC_OK) break;
-        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = SC_ERR_HIP; break; }
-        float ms1 = 0;
-        if (hipEventElapsedTime(&ms1, e0, e1) != hipSuccess) { st = SC_ERR_HIP; break; }
-        int reps = (int)std::min(50.0f, std::max(3.0f, 2.0f / std::max(ms1, 1e-3f)));
-        if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; break; }
-        for (int r = 0; r < reps && st == SC_OK; ++r)
+        const float ms1 = time_launches(1);
+        if (ms1 < 0) break;
+        const int reps = (int)std::min(50.0f, std::max(3.0f, 2.0f / std::max(ms1, 1e-3f)));
+        const float ms = time_launches(reps);
+        if (ms < 0) break;
+        timed.emplace_back(ms, (int)i);
+    }
+    // the few fastest are often within the noise of one short measurement: time them again, longer,
+    // and keep the best of that round
+    float best = INFINITY;
+    int best_i = -1;
+    if (st == SC_OK && !timed.empty()) {
+        std::sort(timed.begin(), timed.end());
+        const size_t finalists = std::min<size_t>(timed.size(), 4);
+        for (size_t k = 0; k < finalists && st == SC_OK; ++k) {
+            const int i = timed[k].second;
+            st = sparse_conv_plan_set_tuning(plan, &cands[i], stream);
+            if (st != SC_OK) break;
             st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
-        if (st != SC_OK) break;
-        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = SC_ERR_HIP; break; }
-        float ms = 0;
-        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = SC_ERR_HIP; break; }
-        ms /= reps;
-        if (ms < best) { best = ms; best_i = (int)i; }
+            if (st != SC_OK) break;
+            const int reps = (int)std::min(200.0f, std::max(10.0f, 8.0f / std::max(timed[k].first, 1e-3f)));
+            const float ms = time_launches(reps);
+            if (ms < 0) break;
+            timed[k].first = ms;
+            best = std::min(best, ms);
+        }
+        // These timings run on one buffer pair, which the last-level cache may hold; a caller that
+        // streams fresh activations pays DRAM instead.  Among finalists within 2 % of the fastest,
+        // take the widest tile: the longest contiguous run per channel row, the DRAM-friendly one.
+        int best_tq = -1;
+        for (size_t k = 0; k < finalists && st == SC_OK; ++k) {
+            const sc_tuning_t& c = cands[timed[k].second];
+            if (timed[k].first <= best * 1.02f && c.tile_q > best_tq) { best_tq = c.tile_q; best_i = timed[k].second; }
+        }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
