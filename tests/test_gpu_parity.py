@@ -300,6 +300,29 @@ def test_ell_entry_point_and_unsorted_duplicate_columns():
         assert np.array_equal(G.run_gpu(plan, x), ref), label
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_every_autotune_candidate_on_mid_size_layers(dtype):
+    """Layers large enough for the wide-tile, channel-chunked, packed and pipelined candidates to
+    fit (planes of 1024 and 784 positions, 96 / 160 input channels, a stride-2 layer): every
+    candidate the autotuner would time gives the oracle's result."""
+    for l in (wl.Layer("mid1x1", 96, 80, 32, 32, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.85, dtype=dtype, seed=18),
+              wl.Layer("mid3x3", 160, 48, 28, 28, 3, 3, 1, 1, 1, 1, N=2, sparsity=0.9, dtype=dtype, seed=19),
+              wl.Layer("mid3x3s2", 48, 40, 28, 28, 3, 3, 2, 2, 1, 1, N=2, sparsity=0.8, dtype=dtype, seed=20)):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        nc = plan.num_candidates()
+        kinds = set()
+        for i in range(nc):
+            t = plan.candidate(i)
+            plan.set_tuning(t)
+            d = t.as_dict()
+            kinds.add((d["variant"], d["pipeline"], d["chunk_c"] > 0, d["pack"], d["wsrc"], d["sub_batch"] > 1))
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} candidate {i} {d}")
+        print("case", l.name, dtype, nc, "candidates,", len(kinds), "kinds", flush=True)
+        assert nc >= 50 and len(kinds) >= 6
+
+
 def test_every_autotune_candidate_gives_the_same_answer():
     for l in (wl.Layer("cand3x3", 16, 24, 20, 20, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.8, seed=8),
               wl.Layer("cand1x1", 32, 40, 16, 16, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.8, seed=9)):
