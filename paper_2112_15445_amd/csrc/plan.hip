@@ -132,25 +132,13 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
         o.ns = samples;
     }
+    int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
     // packed positions read aligned 32-bit words only (unaligned LDS reads are several times
     // slower): unless every lambda is a whole number of words (pointwise layer, even channel
     // pitch), LDS holds `pack` images of the chunk, image s shifted by s elements, and an entry
     // with lambda = s (mod pack) reads image s at lambda - s
-    // (fp32 with 128-bit words needs no images: the elements an aligned word lacks come from the
-    // next lane's word by a lane shift, at the price of one lane in 64 -- 63 words per slot)
     o.copies = 1;
-    o.shift = 0;
-    if (o.pack > 1 && pipeline == 0 && !(pw && o.chan_pitch % o.pack == 0)) {
-        if (p.dtype == SC_F32 && o.pack == 4) {
-            o.shift = 1;
-            o.vpt = (o.F + 63 * o.pack - 1) / (63 * o.pack);
-            if (o.vpt * o.pack > 8) return false;
-        } else {
-            o.copies = o.pack;
-        }
-    }
-    // (the slack behind an image: lanes past the tile's positions read up to one slot further)
-    int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
+    if (o.pack > 1 && pipeline == 0 && !(pw && o.chan_pitch % o.pack == 0)) o.copies = o.pack;
     slab = (int64_t)o.copies * round_up((int)std::min<int64_t>(slab, kMaxLdsBytes), 16);
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);

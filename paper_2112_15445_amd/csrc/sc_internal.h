@@ -36,7 +36,6 @@ struct SlabGeom {
     int vpt;                   // ceil(F / 64); packed positions: 32-bit words per lane, ceil(F / (64*pack))
     int pack;                  // positions per lane and LDS read: 1, or 2 (f16) / 4 (i8) with tuning.pack
     int copies, copy_bytes;    // packed one-shot form: images of a chunk in LDS, copy s shifted by s elements
-    int shift;                 // 1: fp32 128-bit words, one image, offsets off a word boundary served by lane shifts
     int slab_bytes;            // C*chan_pitch*e_x rounded up to 16
     int wcap;                  // (theta, lambda) entries per weight stage in LDS
     int DS, JC;                // rows per stage, entries per row per stage

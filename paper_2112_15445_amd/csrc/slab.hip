@@ -141,12 +141,6 @@ __device__ inline void load_pair(int* o, const int2* __restrict__ wl32, __amdgpu
     }
 }
 
-// The value the next lane of the wave holds (lane 63 gets 0): one DPP move, wave_shl:1.
-__device__ __forceinline__ float next_lane(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false));
-}
-
 // One (theta, lambda) entry applied to one slot of a lane.  E = 1: the slot is one position.
 // E > 1: the slot is an aligned 32-bit word (2 halves or 4 bytes) or an aligned 128-bit word
 // (4 floats or 8 halves) of E adjacent positions, so one LDS read feeds E multiply-adds; the
@@ -942,12 +936,7 @@ expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict_
     // fillers behind it are dropped; one that lands on a padding slot is a zero weight either way)
     if (k >= seg_off[si + 1] - seg_off[si]) return;
     int lb = l & 0x7fffffff;
-    if (copies < 0) {
-        // lane-shifted words (-copies elements per word): the aligned word's byte offset, with the
-        // number of elements to shift by in the low bits
-        const int el = lb / ex, sh = el % (-copies);
-        lb = (el - sh) * ex | sh;
-    } else if (copies > 1) {
+    if (copies > 1) {
         // shifted images: an entry s elements past a word boundary reads image s one word-aligned
         const int el = lb / ex, sh = el % copies;
         lb = (el - sh) * ex + sh * copy_bytes;
@@ -964,7 +953,7 @@ sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t tot
 #define SC_EXPANDC(DT)                                                                             \
     hipLaunchKernelGGL(expand_chunked_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
                        p.d_lam_slab, p.d_col, p.d_seg_off, p.d_first_j, p.d_wlc, p.L.D, p.n,       \
-                       p.L.R * p.L.S, g.CC, g.nchunks, g.shift ? -g.pack : g.copies, p.ex, g.copy_bytes)
+                       p.L.R * p.L.S, g.CC, g.nchunks, g.copies, p.ex, g.copy_bytes)
     switch (p.dtype) {
         case SC_F32: SC_EXPANDC(SC_F32); break;
         case SC_F16: SC_EXPANDC(SC_F16); break;
@@ -1268,7 +1257,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB, bool SHF>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1313,27 +1302,20 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // E > 1 (packed positions): slot k of a lane is the 32-bit word of positions
     // (k * 64 + lane) * E .. + E - 1 of the flat tile
     static_assert(E == 1 || (!MS && (E * (int)sizeof(X) == 4 || E * (int)sizeof(X) == 16)), "packed positions: one sample, 32- or 128-bit words");
-    // SHF (fp32, 128-bit words, offsets that are not whole words): every read is the aligned word
-    // at or below the wanted one, and the 1..3 missing elements come from the next lane's word by a
-    // wave-wide lane shift.  Lanes 0..62 own words, lane 63 only reads the word that lane 62 needs
-    // from its right (it is lane 0's word of the next slot): 63 words per slot.
-    static_assert(!SHF || (DT == SC_F32 && E == 4 && !MS && !LANES && !FLAT), "lane-shifted words: fp32, 128 bits");
-    constexpr int WPS = SHF ? 63 : 64;                               // words (owner lanes) per slot
     int out_off[VPT][E];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            const int f = MS ? lane : (k * WPS + lane) * E + e;
+            const int f = MS ? lane : (k * 64 + lane) * E + e;
             const int tp = fdiv(f, a.inv_Qs);
             const int tq = f - tp * a.Qs;
-            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N) &&
-                            (!SHF || lane < 63);
+            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
             out_off[k][e] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
         }
     }
     const int img_elems = a.CC * a.chan_pitch;                       // one sample's chunk image
-    const int koff = MS ? img_elems * (int)sizeof(X) : WPS * E * (int)sizeof(X);
+    const int koff = MS ? img_elems * (int)sizeof(X) : 64 * E * (int)sizeof(X);
     const unsigned char* lane_base = lds + lane * E * (int)sizeof(X);
 
     // Offset of every element of one staged channel image inside the input plane, or -1 where the
@@ -1502,30 +1484,9 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                 const int s0 = segs[si], len = segs[si + 1] - s0;     // even
                 auto mac = [&](int wbits, int lam) {
                     const WL w = weight_from_bits<DT>(wbits);
-                    if constexpr (SHF) {
-                        // lam = byte offset of the aligned word | elements to shift by (0..3)
-                        const unsigned char* pj = lane_base + (lam & ~15);
-                        const int sh = lam & 3;
+                    const unsigned char* pj = lane_base + lam;
 #pragma unroll
-                        for (int k = 0; k < VPT; ++k) {
-                            const uint4v q = *reinterpret_cast<const uint4v*>(pj + k * koff);
-                            const float a0 = __uint_as_float(q.x), a1 = __uint_as_float(q.y);
-                            const float a2 = __uint_as_float(q.z), a3 = __uint_as_float(q.w);
-                            if (sh == 0) {
-                                acc[r][k][0] += w * a0; acc[r][k][1] += w * a1; acc[r][k][2] += w * a2; acc[r][k][3] += w * a3;
-                            } else if (sh == 1) {
-                                acc[r][k][0] += w * a1; acc[r][k][1] += w * a2; acc[r][k][2] += w * a3; acc[r][k][3] += w * next_lane(a0);
-                            } else if (sh == 2) {
-                                acc[r][k][0] += w * a2; acc[r][k][1] += w * a3; acc[r][k][2] += w * next_lane(a0); acc[r][k][3] += w * next_lane(a1);
-                            } else {
-                                acc[r][k][0] += w * a3; acc[r][k][1] += w * next_lane(a0); acc[r][k][2] += w * next_lane(a1); acc[r][k][3] += w * next_lane(a2);
-                            }
-                        }
-                    } else {
-                        const unsigned char* pj = lane_base + lam;
-#pragma unroll
-                        for (int k = 0; k < VPT; ++k) mac_slot<DT, E>(acc[r][k], w, pj + k * koff);
-                    }
+                    for (int k = 0; k < VPT; ++k) mac_slot<DT, E>(acc[r][k], w, pj + k * koff);
                 };
                 if constexpr (LANES) {
                     for (int c0 = 0; c0 < len || c0 == 0; c0 += 64) {
@@ -1581,13 +1542,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0, bool SHF = false>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0>
 static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB, SHF>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1628,20 +1589,9 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
         const SlabGeom& g = p.geom;
         const int64_t chunk_bytes = (int64_t)g.CC * g.chan_pitch * p.ex;
         if (g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
-            g.copies == 1 && !g.shift && ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 &&
-            reinterpret_cast<uintptr_t>(x) % 16 == 0)
+            g.copies == 1 && ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
             return launch_cc_w<DT, VPT, MS, E, false, true>(p, a, x, y, grid, stream);
     }
-    if constexpr (DT == SC_F32 && E == 4 && !MS) {
-        if (p.geom.shift) {
-            switch (row_run_bytes(p, x)) {
-                case 16: return launch_cc_w<DT, VPT, MS, E, false, false, 16, true>(p, a, x, y, grid, stream);
-                case 8: return launch_cc_w<DT, VPT, MS, E, false, false, 8, true>(p, a, x, y, grid, stream);
-            }
-            return launch_cc_w<DT, VPT, MS, E, false, false, 0, true>(p, a, x, y, grid, stream);
-        }
-    }
-    if (p.geom.shift) return SC_ERR_UNSUPPORTED;
     if constexpr (!MS) {
         switch (row_run_bytes(p, x)) {
             case 16: return launch_cc_w<DT, VPT, MS, E, false, false, 16>(p, a, x, y, grid, stream);
