@@ -160,8 +160,8 @@ __device__ __forceinline__ void mac_slot(typename Types<DT>::A (&acc)[E], typena
         for (int e = 0; e < E; ++e) {
             if constexpr (DT == SC_F16)
                 acc[e] += w * __half2float(__ushort_as_half((unsigned short)(xd >> (16 * e))));
-            else
-                acc[e] += w * (int32_t)(int8_t)(xd >> (8 * e));
+            else   // one 4-way int8 dot product with the weight in byte e and zeros elsewhere: no unpacking
+                acc[e] = __builtin_amdgcn_sdot4((int)xd, (w & 0xff) << (8 * e), acc[e], false);
         }
     } else {
         const uint4v xq = *reinterpret_cast<const uint4v*>(p);
@@ -380,8 +380,8 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
             for (int e = 0; e < E; ++e) {
                 if constexpr (DT == SC_F16)
                     acc[k][e] += w * __half2float(__ushort_as_half((unsigned short)(xd >> (16 * e))));
-                else
-                    acc[k][e] += w * (int32_t)(int8_t)(xd >> (8 * e));
+                else   // 4-way int8 dot product, weight in byte e, zeros elsewhere
+                    acc[k][e] = __builtin_amdgcn_sdot4((int)xd, (w & 0xff) << (8 * e), acc[k][e], false);
             }
         }
     };
