@@ -95,7 +95,7 @@ gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restri
             const WL w = theta_s[j];
             const int l = lam_s[j];
 #pragma unroll
-            for (int k = 0; k < VPT; ++k) acc[k] += w * widen<DT>(xs[k][l]);
+            for (int k = 0; k < VPT; ++k) mac1<DT>(acc[k], w, xs[k][l]);
         }
     }
 #pragma unroll

@@ -48,6 +48,15 @@ template <sc_dtype_t DT> __device__ inline typename Types<DT>::A widen(typename 
     else return (typename Types<DT>::A)v;
 }
 
+// acc += w * x for one gathered element.  The integer variants multiply 8-bit values: the 24-bit
+// multiply-add runs at the full rate, the generic 32-bit integer multiply at a quarter of it.
+template <sc_dtype_t DT>
+__device__ __forceinline__ void mac1(typename Types<DT>::A& acc, typename Types<DT>::WL w, typename Types<DT>::X x)
+{
+    if constexpr (DT == SC_I8 || DT == SC_CB4_I8) acc += __mul24(w, (int)x);
+    else acc += w * widen<DT>(x);
+}
+
 template <sc_dtype_t DT> __device__ inline typename Types<DT>::Y narrow(typename Types<DT>::A v)
 {
     if constexpr (kHalfActs<DT>) return __float2half_rn(v);

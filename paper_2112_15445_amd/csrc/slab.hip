@@ -153,7 +153,7 @@ __device__ __forceinline__ void mac_slot(typename Types<DT>::A (&acc)[E], typena
     constexpr int SB = E * (int)sizeof(X);      // bytes per slot
     static_assert(E == 1 || SB == 4 || (SB == 16 && sizeof(X) >= 2), "slot: one element, 32 or 128 bits");
     if constexpr (E == 1) {
-        acc[0] += w * widen<DT>(*reinterpret_cast<const X*>(p));
+        mac1<DT>(acc[0], w, *reinterpret_cast<const X*>(p));
     } else if constexpr (SB == 4) {
         const uint32_t xd = *reinterpret_cast<const uint32_t*>(p);
 #pragma unroll
@@ -241,7 +241,7 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
                     const unsigned char* pj = lane_base + __builtin_amdgcn_readlane(cur2.y, j);
 #pragma unroll
                     for (int k = 0; k < VPT; ++k)
-                        acc3[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                        mac1<DT>(acc3[k], w, *reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
                 };
                 int j = 0;
                 for (; j + 8 <= cnt; j += 8) {
@@ -267,7 +267,7 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
         const unsigned char* pj = lane_base + lam;
 #pragma unroll
         for (int k = 0; k < VPT; ++k)
-            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+            mac1<DT>(acc[k], w, *reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
     };
     if constexpr (WSRC == 1) {
         // Scalar loads, 8 entries at a time, through the constant address space and with no
@@ -572,7 +572,7 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
                         const unsigned char* pj = lane_base + e.y;
 #pragma unroll
                         for (int k = 0; k < VPT; ++k)
-                            acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                            mac1<DT>(acc[k], w, *reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
                     }
                 }
                 if (j0 + jc >= a.n) {
@@ -875,7 +875,7 @@ slab_sym_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>:
                 const unsigned char* pj = lane_base + lam;
 #pragma unroll
                 for (int k = 0; k < VPT; ++k)
-                    acc[k] += w * widen<DT>(*reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
+                    mac1<DT>(acc[k], w, *reinterpret_cast<const X*>(pj + k * 64 * (int)sizeof(X)));
             };
             for (int g = 0; g < ng; ++g) {
                 // no software prefetch on purpose: with nothing else pending on the scalar/LDS
