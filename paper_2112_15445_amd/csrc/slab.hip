@@ -1323,10 +1323,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // costs one division, one table read and one load per element.
     // (FLAT: a pointwise layer with one tile per plane -- the image of a chunk is one contiguous,
     // 16-byte aligned block of the input and is copied as such, no table.
-    // ROWB > 0: unit strides and a tile as wide as the plane -- every row of a channel image is a
-    // whole row of the input between the padding columns, and those rows are contiguous in memory:
-    // they are copied with ROWB-byte loads, two index divisions per load instead of one per
-    // element, no table.  The padding is written once, here: no later store touches it.)
+    // ROWB > 0: unit strides (or strides of two with both phases in use) and a tile as wide as the
+    // plane -- the rows of a channel image are whole rows of the input (split by parity into the
+    // phase images when the stride is two), and those rows are contiguous in memory: they are
+    // copied with ROWB-byte loads, two index divisions per load instead of one per element, no
+    // table.  The padding is written once, here: no later store touches it.)
     static_assert(ROWB == 0 || (!MS && !FLAT && ROWB % (int)sizeof(X) == 0), "row runs: one sample, whole elements");
     int* tab = reinterpret_cast<int*>(lds + a.slab_bytes);
     const int plane = a.Hf * a.Wf;
@@ -1336,7 +1337,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
     constexpr int RV = ROWB > 0 ? ROWB / (int)sizeof(X) : 1;        // elements per load
     const int rlo = max(row0, 0);
-    const int rcnt = min(row0 + a.SR, a.Hf) - rlo;                  // input rows under the tile (>= 1)
+    const int rcnt = min(row0 + a.SR * a.s_h, a.Hf) - rlo;          // input rows under the tile (>= 1)
     const int vpr = a.Wf / RV;                                       // loads per row
     const int per_c = rcnt * vpr;                                    // loads per channel
     const float inv_per_c = 1.0f / (float)per_c, inv_vpr = 1.0f / (float)vpr;
@@ -1401,7 +1402,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             const int nvec = min(a.CC, a.C - c0) * per_c;
             for (int i0 = tid; i0 < nvec; i0 += kStageLoads * nthreads) {
                 Vec v[kStageLoads];
-                int dsti[kStageLoads];
+                int dsti[kStageLoads], tc0[kStageLoads];
 #pragma unroll
                 for (int u = 0; u < kStageLoads; ++u) {
                     const int i = i0 + u * nthreads;
@@ -1411,7 +1412,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                         const int ir = fdiv(r2, inv_vpr);
                         const int vv = r2 - ir * vpr;
                         v[u] = *reinterpret_cast<const Vec*>(xc + (int64_t)c * plane + (rlo + ir) * a.Wf + vv * RV);
-                        dsti[u] = c * a.chan_pitch + (rlo - row0 + ir) * a.Qs + a.pad_w + vv * RV;
+                        // unit strides: the row goes to image row t_r behind the left padding;
+                        // strides of two: to row t_r / 2 of the phase image of its parity, and its
+                        // elements alternate between the two column phases
+                        const int t_r = rlo - row0 + ir;
+                        tc0[u] = a.pad_w + vv * RV;
+                        dsti[u] = a.s_h == 1 ? c * a.chan_pitch + t_r * a.Qs + tc0[u]
+                                             : c * a.chan_pitch + (t_r & 1) * 2 * a.sub_pitch + (t_r >> 1) * a.Qs;
                     }
                 }
 #pragma unroll
@@ -1420,13 +1427,15 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                     if (i < nvec) {
 #pragma unroll
                         for (int j = 0; j < RV; ++j) {
-                            simg[dsti[u] + j] = v[u].e[j];
+                            const int t_c = tc0[u] + j;
+                            const int dst = a.s_h == 1 ? dsti[u] + j : dsti[u] + (t_c & 1) * a.sub_pitch + (t_c >> 1);
+                            simg[dst] = v[u].e[j];
                             if constexpr (E > 1) {
                                 if (a.copies > 1) {
 #pragma unroll
                                     for (int sh = 1; sh < E; ++sh)
-                                        if (dsti[u] + j >= sh)
-                                            *reinterpret_cast<X*>(lds + sh * a.copy_bytes + (dsti[u] + j - sh) * (int)sizeof(X)) = v[u].e[j];
+                                        if (dst >= sh)
+                                            *reinterpret_cast<X*>(lds + sh * a.copy_bytes + (dst - sh) * (int)sizeof(X)) = v[u].e[j];
                                 }
                             }
                         }
@@ -1566,9 +1575,16 @@ static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, 
 static int row_run_bytes(const Plan& p, const void* x)
 {
     const SlabGeom& g = p.geom;
-    if (p.L.stride_h != 1 || p.L.stride_w != 1 || g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1) return 0;
+    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1) return 0;
     if (g.Hf == 1) return 0;                                      // flattened pointwise layers
-    if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
+    if (p.L.stride_h == 1 && p.L.stride_w == 1) {
+        if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
+    } else if (p.L.stride_h == 2 && p.L.stride_w == 2) {
+        // both row and both column phases staged, and every input column inside a phase image
+        if (g.nsh != 2 || g.nsw != 2 || p.L.pad_w + g.Wf > 2 * g.Qs) return 0;
+    } else {
+        return 0;
+    }
     if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return 0;
     const int row_bytes = g.Wf * p.ex;
     for (int b : {16, 8, 4})

@@ -577,11 +577,14 @@ def test_full_width_tiles_staged_by_row_runs(dtype):
     """Unit strides and tiles as wide as the plane: the chunked one-shot kernel copies whole input rows
     with 4-, 8- or 16-byte loads and writes the zero padding once.  Widths that give each load size
     (and one that gives none), paddings 0..2, tiles that end below the plane, packed positions."""
-    shapes = [("rr56", 12, 10, 13, 56, 3, 3, 1, 1), ("rr24", 10, 12, 9, 24, 3, 3, 1, 1), ("rr20", 9, 8, 11, 20, 5, 5, 2, 2),
-              ("rr12", 16, 6, 12, 12, 3, 3, 0, 0), ("rr8", 20, 9, 8, 8, 1, 3, 0, 1), ("rr14", 7, 5, 14, 14, 3, 3, 1, 1),
-              ("rr10", 6, 5, 10, 10, 3, 3, 2, 1)]
-    for name, C, D, H, W, R, S, ph, pw in shapes:
-        l = wl.Layer(name, C, D, H, W, R, S, 1, 1, ph, pw, N=3, sparsity=0.6, dtype=dtype, seed=61)
+    shapes = [("rr56", 12, 10, 13, 56, 3, 3, 1, 1, 1), ("rr24", 10, 12, 9, 24, 3, 3, 1, 1, 1), ("rr20", 9, 8, 11, 20, 5, 5, 2, 2, 1),
+              ("rr12", 16, 6, 12, 12, 3, 3, 0, 0, 1), ("rr8", 20, 9, 8, 8, 1, 3, 0, 1, 1), ("rr14", 7, 5, 14, 14, 3, 3, 1, 1, 1),
+              ("rr10", 6, 5, 10, 10, 3, 3, 2, 1, 1),
+              # strides of two: rows and columns split by parity into the four phase images
+              ("rs56", 10, 8, 30, 56, 3, 3, 1, 1, 2), ("rs24", 12, 10, 17, 24, 3, 3, 0, 0, 2), ("rs16", 8, 6, 16, 16, 2, 2, 0, 0, 2),
+              ("rs20", 6, 7, 19, 20, 5, 5, 2, 2, 2), ("rs12", 9, 5, 12, 12, 3, 3, 1, 1, 2)]
+    for name, C, D, H, W, R, S, ph, pw, st in shapes:
+        l = wl.Layer(name, C, D, H, W, R, S, st, st, ph, pw, N=3, sparsity=0.6, dtype=dtype, seed=61)
         data = wl.prepare(l, ragged=True)
         ref = G.oracle_out(l, data)
         plan = G.make_plan(l, data)
