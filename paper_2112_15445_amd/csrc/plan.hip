@@ -100,7 +100,8 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         // packed positions: chunked forms, one sample per workgroup; a lane owns the adjacent
         // positions of one 32-bit word (pack = 1: 16- or 8-bit activations) or of one 128-bit word
         // (pack = 2: 32- or 16-bit activations), at most 8 positions
-        if (chunk_c <= 0 || samples > 1) return false;
+        // (128-bit words also in the producer/consumer kernel without channel chunks)
+        if (samples > 1 || (chunk_c <= 0 && !(pack == 2 && pipeline == 1 && wsrc == 1))) return false;
         if (pack == 1 && p.dtype != SC_F16 && p.dtype != SC_I8) return false;
         if (pack == 2 && p.dtype != SC_F32 && p.dtype != SC_F16) return false;
         o.pack = (pack == 2 ? 16 : 4) / p.ex;
@@ -765,6 +766,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 t.tile_p = 1;
                 t.tile_q = tq;
                 push(t);
+                if (wide && wsrc == 1 && tq >= 256) { t.pack = 2; push(t); }
               }
             }
         }

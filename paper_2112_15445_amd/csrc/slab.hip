@@ -348,14 +348,15 @@ __device__ inline void stream_rows(const int2* __restrict__ wl32, __amdgpu_buffe
     }
 }
 
-// Scalar-load row stream for 16- and 8-bit activations of pointwise layers, positions packed by
-// the dword: lane l owns the E = 2 (fp16) or 4 (int8) adjacent positions (k*64 + l)*E .. +E-1, so
-// one ds_read_b32 feeds E multiply-adds and the outputs of a lane leave as one 4- or 16-byte
-// store.  Needs 4-byte aligned channel rows (tile width and plane size multiples of E), which the
-// direct-to-LDS forms guarantee.  out_off[k] is the element offset of the lane's first position
-// of dword k inside the output plane, or -1.  Same loop shape as the unpacked stream: 8 entries
-// per scalar load, no software prefetch, tail pairs from one over-reaching load.
-template <sc_dtype_t DT, int VW>
+// Scalar-load row stream of pointwise layers with packed positions: lane l owns the E adjacent
+// positions (k*64 + l)*E .. +E-1 of slot k -- one 32-bit word (E = 2 halves / 4 bytes) or one
+// 128-bit word (E = 4 floats / 8 halves) -- so one LDS read feeds E multiply-adds and the outputs of
+// a lane leave as one 4- or 16-byte store.  Needs channel rows that are whole words (tile width
+// and plane size multiples of E), which the direct-to-LDS forms guarantee.  out_off[k] is the
+// element offset of the lane's first position of slot k inside the output plane, or -1.  Same loop
+// shape as the unpacked stream: 8 entries per scalar load, no software prefetch, tail pairs from
+// one over-reaching load.
+template <sc_dtype_t DT, int VW, int E>
 __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const unsigned char* lane_base,
                                           typename Types<DT>::Y* yb, const int (&out_off)[VW], int first,
                                           int stride, int D, int np, int64_t y_plane)
@@ -364,8 +365,8 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
     using Y = typename Types<DT>::Y;
     using A = typename Types<DT>::A;
     using WL = typename Types<DT>::WL;
-    static_assert(DT == SC_F16 || DT == SC_I8, "packed positions: 16- or 8-bit activations");
-    constexpr int E = 4 / (int)sizeof(X);
+    constexpr int SB = E * (int)sizeof(X);       // bytes per slot
+    static_assert(SB == 4 || SB == 16, "packed positions: 32- or 128-bit words");
     typedef const int16v __attribute__((address_space(4)))* c16_t;
     const int ng = np >> 3;
     const int tail = (np & 7) >> 1;
@@ -374,16 +375,7 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
         const WL w = weight_from_bits<DT>(wbits);
         const unsigned char* pj = lane_base + lam;
 #pragma unroll
-        for (int k = 0; k < VW; ++k) {
-            const uint32_t xd = *reinterpret_cast<const uint32_t*>(pj + k * 256);
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                if constexpr (DT == SC_F16)
-                    acc[k][e] += w * __half2float(__ushort_as_half((unsigned short)(xd >> (16 * e))));
-                else   // 4-way int8 dot product, weight in byte e, zeros elsewhere
-                    acc[k][e] = __builtin_amdgcn_sdot4((int)xd, (w & 0xff) << (8 * e), acc[k][e], false);
-            }
-        }
+        for (int k = 0; k < VW; ++k) mac_slot<DT, E>(acc[k], w, pj + k * 64 * SB);
     };
     for (int d = first; d < D; d += stride) {
         const int2* prow = wl32 + (int64_t)d * np;
@@ -404,17 +396,8 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
         }
         Y* yd = yb + (int64_t)d * y_plane;
 #pragma unroll
-        for (int k = 0; k < VW; ++k) {
-            if (out_off[k] >= 0) {
-                if constexpr (DT == SC_F16) {
-                    const uint32_t lo = __half_as_ushort(__float2half(acc[k][0]));
-                    const uint32_t hi = __half_as_ushort(__float2half(acc[k][1]));
-                    store_out(reinterpret_cast<uint32_t*>(yd + out_off[k]), lo | (hi << 16));
-                } else {
-                    store_out4(yd + out_off[k], acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
-                }
-            }
-        }
+        for (int k = 0; k < VW; ++k)
+            if (out_off[k] >= 0) store_slot<DT, E>(yd + out_off[k], acc[k]);
     }
 }
 
@@ -716,7 +699,7 @@ dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int p
 // LDS contents is never stored.
 // ------------------------------------------------------------------------------------------------
 
-template <sc_dtype_t DT, int VPT, int WSRC>
+template <sc_dtype_t DT, int VPT, int WSRC, int E>
 __global__ void
 slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                   const int2* __restrict__ wl32, const SlabArgs a)
@@ -769,10 +752,10 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     for (int t = first; t < total; t += step, ++it) {
         const int b = fdiv(t, a.inv_tiles);
         const int q0 = (t - b * tiles) * a.TQ;
-        // 16- and 8-bit activations with scalar-load weights: positions packed by the dword (VPT
-        // then counts dwords per lane); otherwise lane l owns positions l, l + 64, ...
-        constexpr bool kPacked = DT != SC_F32 && WSRC == 1;
-        constexpr int E = kPacked ? 4 / (int)sizeof(X) : 1;
+        // E > 1 (scalar-load weights): positions packed by the 32- or 128-bit word (VPT then
+        // counts words per lane); otherwise lane l owns positions l, l + 64, ...
+        constexpr bool kPacked = E > 1;
+        static_assert(!kPacked || WSRC == 1, "packed positions: scalar-load weights");
         int out_off[VPT];
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
@@ -780,10 +763,10 @@ slab_async_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
             out_off[k] = (f < a.TQ && q0 + f < a.Qf) ? q0 + f : -1;
         }
         Y* yb = y + (int64_t)b * a.D * a.y_plane;
-        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * (kPacked ? 4 : (int)sizeof(X));
+        const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * E * (int)sizeof(X);
         __syncthreads();  // A
         if constexpr (kPacked)
-            stream_rows_packed<DT, VPT>(wl32, lane_base, yb, out_off, wave, ncons, a.D, a.np, a.y_plane);
+            stream_rows_packed<DT, VPT, E>(wl32, lane_base, yb, out_off, wave, ncons, a.D, a.np, a.y_plane);
         else
             stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, ncons, a.D, a.n, a.np, a.y_plane);
         __syncthreads();  // B
@@ -1829,13 +1812,13 @@ static sc_status_t launch_vpt(const Plan& p, const SlabArgs& a, const void* x, v
     return SC_ERR_UNSUPPORTED;
 }
 
-template <sc_dtype_t DT, int VPT, int WSRC>
+template <sc_dtype_t DT, int VPT, int WSRC, int E = 1>
 static sc_status_t launch_async_one(const Plan& p, const SlabArgs& a, const void* x, void* y,
                                     hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_async_kernel<DT, VPT, WSRC>;
+    auto kernel = slab_async_kernel<DT, VPT, WSRC, E>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1853,14 +1836,26 @@ static sc_status_t launch_async_one(const Plan& p, const SlabArgs& a, const void
 template <sc_dtype_t DT, int WSRC>
 static sc_status_t launch_async_w(const Plan& p, const SlabArgs& a, const void* x, void* y, hipStream_t stream)
 {
+    if constexpr ((DT == SC_F32 || DT == SC_F16) && WSRC == 1) {
+        // tuning.pack = 2: positions packed by the 128-bit word, 16-byte stores
+        constexpr int EW = 16 / (int)sizeof(typename Types<DT>::X);
+        if (p.geom.pack == EW) {
+            if (p.geom.vpt == 1) return launch_async_one<DT, 1, WSRC, EW>(p, a, x, y, stream);
+            if constexpr (EW == 4) {
+                if (p.geom.vpt == 2) return launch_async_one<DT, 2, WSRC, EW>(p, a, x, y, stream);
+            }
+            return SC_ERR_UNSUPPORTED;
+        }
+    }
+    if (p.geom.pack != 1) return SC_ERR_UNSUPPORTED;
     if constexpr (DT != SC_F32 && WSRC == 1) {
         // positions packed by the dword: the kernel's count is dwords per lane
-        const int per_dword = 4 / p.ex;
-        switch ((p.geom.TQ + 64 * per_dword - 1) / (64 * per_dword)) {
-            case 1: return launch_async_one<DT, 1, WSRC>(p, a, x, y, stream);
-            case 2: return launch_async_one<DT, 2, WSRC>(p, a, x, y, stream);
-            case 3: return launch_async_one<DT, 3, WSRC>(p, a, x, y, stream);
-            case 4: return launch_async_one<DT, 4, WSRC>(p, a, x, y, stream);
+        constexpr int E = 4 / (int)sizeof(typename Types<DT>::X);
+        switch ((p.geom.TQ + 64 * E - 1) / (64 * E)) {
+            case 1: return launch_async_one<DT, 1, WSRC, E>(p, a, x, y, stream);
+            case 2: return launch_async_one<DT, 2, WSRC, E>(p, a, x, y, stream);
+            case 3: return launch_async_one<DT, 3, WSRC, E>(p, a, x, y, stream);
+            case 4: return launch_async_one<DT, 4, WSRC, E>(p, a, x, y, stream);
         }
         return SC_ERR_UNSUPPORTED;
     }

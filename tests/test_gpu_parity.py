@@ -696,6 +696,7 @@ def test_positions_packed_in_128_bit_words(dtype):
     cases = (
         (wl.Layer("w1x1", 72, 50, 20, 28, 1, 1, 1, 1, 0, 0, N=4, sparsity=0.8, dtype=dtype, seed=91),
          [{"chunk_c": 16, "tile_q": 256}, {"chunk_c": 24, "tile_q": 512, "tile_d": 16}, {"chunk_c": 72, "tile_q": 128},
+          {"pipeline": 1, "tile_q": 256, "producers": 1}, {"pipeline": 1, "tile_q": 512, "producers": 2},
           {"pipeline": 1, "tile_q": 256, "chunk_c": 16, "producers": 1},
           {"pipeline": 1, "tile_q": 512, "chunk_c": 24, "tile_d": 32, "producers": 2},
           {"pipeline": 2, "tile_q": 256, "chunk_c": 32}, {"pipeline": 2, "tile_q": 128, "chunk_c": 9, "tile_d": 24},
