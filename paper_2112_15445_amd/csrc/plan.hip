@@ -101,7 +101,9 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         // positions of one 32-bit word (pack = 1: 16- or 8-bit activations) or of one 128-bit word
         // (pack = 2: 32- or 16-bit activations), at most 8 positions
         // (128-bit words also in the producer/consumer kernel without channel chunks)
-        if (samples > 1 || (chunk_c <= 0 && !(pack == 2 && pipeline == 1 && wsrc == 1))) return false;
+        // and in the full-channel one-shot kernel on pointwise layers whose tiles are whole words)
+        if (samples > 1 || (chunk_c <= 0 && !(pack == 2 && wsrc == 1 && (pipeline == 1 || (pipeline == 0 && pw)))))
+            return false;
         if (pack == 1 && p.dtype != SC_F16 && p.dtype != SC_I8) return false;
         if (pack == 2 && p.dtype != SC_F32 && p.dtype != SC_F16) return false;
         o.pack = (pack == 2 ? 16 : 4) / p.ex;
@@ -189,6 +191,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (pipeline == 2 && o.dmab == 0) return false;
     if (pack && pipeline >= 1 && o.dmab == 0) return false;      // whole words per row and tile
     if (pack == 2 && pipeline >= 1 && o.dmab != 16) return false;
+    if (pack == 2 && pipeline == 0 && chunk_c <= 0 && (o.chan_pitch % o.pack != 0 || o.Wf % o.pack != 0)) return false;
     o.inv_chan_pitch = 1.0f / (float)o.chan_pitch;
     o.inv_sub_pitch = 1.0f / (float)o.sub_pitch;
     o.inv_Qs = 1.0f / (float)o.Qs;
@@ -843,6 +846,7 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                         t.tile_p = 1;
                         t.tile_q = tq;
                         push(t);
+                        if (wide && wsrc == 1 && tq >= 256) { t.pack = 2; push(t); }
                     }
                 } else {
                     for (int tp : {1, 2, 3, 4, 6, 7, 8, 14, 16}) {

@@ -401,7 +401,7 @@ __device__ inline void stream_rows_packed(const int2* __restrict__ wl32, const u
     }
 }
 
-template <sc_dtype_t DT, int VPT, int WSRC>
+template <sc_dtype_t DT, int VPT, int WSRC, int E>
 __global__ void
 slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
             const void* __restrict__ theta, const int32_t* __restrict__ lam,
@@ -489,25 +489,33 @@ slab_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* 
     }
 
     // ---------------------------------------------------------------- per-lane output bookkeeping
+    // (E > 1, pointwise layers with scalar-load weights: slot k of a lane is the 128-bit word of
+    // positions (k * 64 + lane) * E .. + E - 1; tile widths are whole words, so a word is valid or
+    // not as one)
+    static_assert(E == 1 || WSRC == 1, "packed positions: scalar-load weights");
     int out_off[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const int f = k * 64 + lane;
+        const int f = (k * 64 + lane) * E;
         const int tp = fdiv(f, a.inv_Qs);
         const int tq = f - tp * a.Qs;
         const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf;
         out_off[k] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
     }
     Y* yb = y + (int64_t)b * a.D * a.y_plane;
-    const unsigned char* lane_base = lds + lane * (int)sizeof(X);
+    const unsigned char* lane_base = lds + lane * E * (int)sizeof(X);
 
     if constexpr (WSRC != 0) {
         // ------------------------------------------------------------ weights straight from global
         // memory (scalar loads or wave-uniform vector loads), no weight stage in LDS
         __syncthreads();  // slab complete
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<int2*>(wl32), 0, (int)((int64_t)a.D * a.np * 8), 0x00020000);
-        stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, nwaves, a.D, a.n, a.np, a.y_plane);
+        if constexpr (E > 1) {
+            stream_rows_packed<DT, VPT, E>(wl32, lane_base, yb, out_off, wave, nwaves, a.D, a.np, a.y_plane);
+        } else {
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<int2*>(wl32), 0, (int)((int64_t)a.D * a.np * 8), 0x00020000);
+            stream_rows<DT, VPT, WSRC>(wl32, rsrc, lane_base, yb, out_off, wave, nwaves, a.D, a.n, a.np, a.y_plane);
+        }
         return;
     }
 
@@ -1774,13 +1782,13 @@ sc_status_t expand_weights(const Plan& p, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
-template <sc_dtype_t DT, int VPT, int WSRC>
+template <sc_dtype_t DT, int VPT, int WSRC, int E = 1>
 static sc_status_t launch_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                               hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_kernel<DT, VPT, WSRC>;
+    auto kernel = slab_kernel<DT, VPT, WSRC, E>;
     // a workgroup may use more than the default 64 KB of LDS: raise the limit once per kernel
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -1799,6 +1807,19 @@ template <sc_dtype_t DT, int WSRC>
 static sc_status_t launch_vpt(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                               hipStream_t stream)
 {
+    if constexpr ((DT == SC_F32 || DT == SC_F16) && WSRC == 1) {
+        // tuning.pack = 2 (pointwise layers): positions packed by the 128-bit word, 16-byte stores
+        constexpr int EW = 16 / (int)sizeof(typename Types<DT>::X);
+        if (p.geom.pack == EW) {
+            if (reinterpret_cast<uintptr_t>(y) % 16 != 0) return SC_ERR_UNSUPPORTED;
+            if (p.geom.vpt == 1) return launch_one<DT, 1, WSRC, EW>(p, a, x, y, grid, stream);
+            if constexpr (EW == 4) {
+                if (p.geom.vpt == 2) return launch_one<DT, 2, WSRC, EW>(p, a, x, y, grid, stream);
+            }
+            return SC_ERR_UNSUPPORTED;
+        }
+    }
+    if (p.geom.pack != 1) return SC_ERR_UNSUPPORTED;
     switch (p.geom.vpt) {
         case 1: return launch_one<DT, 1, WSRC>(p, a, x, y, grid, stream);
         case 2: return launch_one<DT, 2, WSRC>(p, a, x, y, grid, stream);

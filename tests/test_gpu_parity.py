@@ -695,7 +695,8 @@ def test_positions_packed_in_128_bit_words(dtype):
     layers through the one-shot kernel with its shifted images (odd offsets, strides, padding)."""
     cases = (
         (wl.Layer("w1x1", 72, 50, 20, 28, 1, 1, 1, 1, 0, 0, N=4, sparsity=0.8, dtype=dtype, seed=91),
-         [{"chunk_c": 16, "tile_q": 256}, {"chunk_c": 24, "tile_q": 512, "tile_d": 16}, {"chunk_c": 72, "tile_q": 128},
+         [{"tile_q": 256}, {"tile_q": 512, "wg_threads": 256}, {"tile_q": 128, "wg_per_cu": 2},
+          {"chunk_c": 16, "tile_q": 256}, {"chunk_c": 24, "tile_q": 512, "tile_d": 16}, {"chunk_c": 72, "tile_q": 128},
           {"pipeline": 1, "tile_q": 256, "producers": 1}, {"pipeline": 1, "tile_q": 512, "producers": 2},
           {"pipeline": 1, "tile_q": 256, "chunk_c": 16, "producers": 1},
           {"pipeline": 1, "tile_q": 512, "chunk_c": 24, "tile_d": 32, "producers": 2},
@@ -714,8 +715,8 @@ def test_positions_packed_in_128_bit_words(dtype):
         ran = 0
         for extra in tunings:
             try:
-                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, pack=2,
-                                **{"wg_per_cu": 1, **extra})
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=2,
+                                **{"wg_per_cu": 1, "wg_threads": 1024, **extra})
             except B.SparseConvError as e:
                 assert e.status == 4
                 print("does not fit", l.name, dtype, extra, flush=True)
