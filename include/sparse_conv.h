@@ -121,8 +121,8 @@ typedef struct {
                            filler entries that unify the row lengths are left out of the per-chunk
                            segments), 0 = the unified table of the method.  For measuring what the
                            padding costs on tables whose rows differ in length */
-    int32_t pack;       /* SLAB with chunk_c > 0 (pack = 2 also with pipeline = 1 and chunk_c = 0) and
-                           wsrc = 1, one sample per workgroup: packed positions.
+    int32_t pack;       /* SLAB with chunk_c > 0 (pack = 2 also with chunk_c = 0 on pointwise layers, pipeline
+                           0 or 1) and wsrc = 1, one sample per workgroup: packed positions.
                            1 (SC_F16 / SC_I8) = every lane owns the 2 / 4 adjacent positions of one 32-bit
                            word of the staged tile; 2 (SC_F32 / SC_F16) = the 4 / 8 adjacent positions of one
                            128-bit word.  One LDS read then feeds that many multiply-adds (at most 8
