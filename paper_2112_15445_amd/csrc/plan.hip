@@ -958,6 +958,17 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             }
         }
     }
+    // A table whose rows differ in length carries fillers (zero weights that unify the rows): when
+    // they are more than 5 % of it, every chunked shape is also tried with the fillers left out.
+    if (p.n > 0 && p.true_nnz * 100 < (int64_t)p.L.D * p.n * 95) {
+        const size_t count = out->size();
+        for (size_t k = 0; k < count; ++k) {
+            sc_tuning_t t = (*out)[k];
+            if (t.variant != SC_VARIANT_SLAB || t.chunk_c == 0) continue;
+            t.ragged = 1;
+            push(t);
+        }
+    }
 }
 
 sc_status_t sparse_conv_plan_num_candidates(const sparse_conv_plan_t* plan, int32_t* count)

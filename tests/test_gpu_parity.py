@@ -727,3 +727,25 @@ def test_positions_packed_in_128_bit_words(dtype):
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
             ran += 1
         assert ran >= 1, l.name
+
+
+def test_autotune_takes_the_ragged_table_when_rows_are_uneven():
+    """Rows with uniform lengths in [0, n] (about half of the unified table is fillers): the
+    autotuner's candidates include the chunked shapes with the fillers left out, it installs one of
+    them, and the result is the oracle's.  A table with equal rows gets no such candidates."""
+    import torch
+    l = wl.Layer("ragtune", 128, 64, 28, 28, 3, 3, 1, 1, 1, 1, N=4, sparsity=0.8, seed=95)
+    even = G.make_plan(l, wl.prepare(l))
+    assert not any(even.candidate(i).ragged for i in range(even.num_candidates()))
+    data = wl.prepare(l, ragged=True)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    assert any(plan.candidate(i).ragged for i in range(plan.num_candidates()))
+    x = G.to_device(data["x"])
+    y = torch.empty((l.N, l.D, l.P, l.Q), device="cuda")
+    ws = torch.empty(max(plan.workspace_size_max(l.N), 1), dtype=torch.uint8, device="cuda")
+    plan.autotune(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    t = plan.get_tuning().as_dict()
+    print("case ragtune", t, flush=True)
+    assert t["ragged"] == 1
+    G.check(l, G.run_gpu(plan, data["x"]), ref, str(t))
