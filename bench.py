@@ -196,6 +196,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--layer", default=None, help="layer name from config 3 (default: headline)")
+    ap.add_argument("--dtype", default=None, help="with --layer: run that layer's shape in this dtype")
     ap.add_argument("--no-autotune", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", default=None,
@@ -259,6 +260,8 @@ def main():
     l = wl.headline_layer()
     if args.layer:
         l = {x.name: x for c in (3, 4, 2, 5, 1, 6, 7) for x in wl.CONFIGS[c]()}[args.layer]
+        if args.dtype:
+            l = l.replace(dtype=args.dtype)
     res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
                                 tuning=json.loads(args.tuning) if args.tuning else None, spread=True)
 

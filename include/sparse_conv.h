@@ -92,7 +92,10 @@ typedef struct {
     int32_t sub_batch;  /* GATHER: output positions per thread that share each (theta, lambda) read
                            from LDS (the role of sb_S), 1, 2, 4 or 8.  SLAB with pipeline = 0 and
                            chunk_c > 0: samples per workgroup (0 / 1 = one; 2..4 for tiles of at most
-                           64 positions, each scalar-loaded weight then feeds that many samples) */
+                           64 positions, each scalar-loaded weight then feeds that many samples;
+                           with pack >= 1, on pointwise layers and whole-plane tiles: 2..16 samples
+                           whose planes lie end to end along the position axis of one packed tile,
+                           within pack's limit of 8 positions per lane) */
     int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
     int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
@@ -122,7 +125,8 @@ typedef struct {
                            segments), 0 = the unified table of the method.  For measuring what the
                            padding costs on tables whose rows differ in length */
     int32_t pack;       /* SLAB with chunk_c > 0 (pack = 2 also with chunk_c = 0 on pointwise layers, pipeline
-                           0 or 1) and wsrc = 1, one sample per workgroup: packed positions.
+                           0 or 1) and wsrc = 1, one sample per workgroup (pipeline = 0 on a pointwise
+                           layer: or sub_batch samples end to end in one tile): packed positions.
                            1 (SC_F16 / SC_I8) = every lane owns the 2 / 4 adjacent positions of one 32-bit
                            word of the staged tile; 2 (SC_F32 / SC_F16) = the 4 / 8 adjacent positions of one
                            128-bit word.  One LDS read then feeds that many multiply-adds (at most 8

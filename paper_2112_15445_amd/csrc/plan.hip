@@ -93,6 +93,21 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.sub_pitch = o.SR * o.Qs;
     o.chan_pitch = o.nsh * o.nsw * o.sub_pitch;
     o.F = o.TP * o.Qs;
+    o.fs = 1;
+    if (samples > 1 && pack) {
+        // small planes of a pointwise layer: the planes of `samples` consecutive samples laid end to
+        // end form the tile's position axis (channel-major in LDS like any pointwise tile), so that
+        // the lanes and the wide words of the packed forms fill up where one plane is smaller than
+        // a wave.  The channel pitch is a whole number of words: no shifted images.
+        if (!pw || pipeline != 0 || chunk_c <= 0 || wsrc != 1 || o.tiles_q != 1 || samples > 16) return false;
+        const int words = (pack == 2 ? 16 : 4) / p.ex;
+        o.fs = samples;
+        o.F = samples * o.Qf;
+        o.Qs = o.F;
+        o.sub_pitch = o.chan_pitch = round_up(o.F, words);
+        if ((int64_t)samples * L.C * o.Wf >= (1ll << 31) || (int64_t)samples * L.D * o.Qf >= (1ll << 31)) return false;
+        samples = 1;
+    }
     if (o.F > kWave * kMaxVpt) return false;
     o.vpt = (o.F + kWave - 1) / kWave;
     o.pack = 1;
@@ -226,8 +241,9 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         SlabGeom g{};
         bool ok = false;
         // sub_batch means samples per workgroup for the chunked one-shot form only
+        // (with packed positions: samples laid end to end in one tile, up to 16)
         const int samples = (t.pipeline == 0 && t.chunk_c > 0) ? t.sub_batch : 0;
-        if (samples < 0 || samples > 4) return SC_ERR_UNSUPPORTED;
+        if (samples < 0 || samples > (t.pack ? 16 : 4)) return SC_ERR_UNSUPPORTED;
         if (t.tile_q == 0) {
             // heuristic: widest tile that fits; pointwise layers tile the flattened plane in
             // multiples of a wave, other layers take full rows and as many of them as fit
@@ -250,7 +266,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.variant = SC_VARIANT_SLAB;
             t.tile_p = g.TP;
             t.tile_q = g.TQ;
-            t.sub_batch = g.ns > 1 ? g.ns : 0;
+            t.sub_batch = g.ns > 1 ? g.ns : (g.fs > 1 ? g.fs : 0);
             t.split_n = 0;
             if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
@@ -952,6 +968,32 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_q = pw ? 32 * tile : p.Q;     // pointwise: 64 .. 512 (and 224, 896 -> clipped by the fit)
                     t.chunk_c = cc;
                     t.tile_d = td;
+                    t.pack = pk;
+                    push(t);
+                }
+            }
+        }
+    }
+    // pointwise layers with small planes: the planes of several samples end to end in one tile of
+    // packed positions (up to 512 positions)
+    if (pw && (packable || wide) && p.n > 0 && 2 * p.P * p.Q <= 512) {
+        for (int wpc : {1, 2}) for (int cc : {64, 128, 256}) {
+            if (cc > p.L.C) continue;
+            for (int td : {0, 32, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                for (int fs : {2, 4}) for (int pk : {1, 2}) {
+                    if ((pk == 1 && !packable) || (pk == 2 && !wide)) continue;
+                    if (fs * p.P * p.Q > 512) continue;
+                    sc_tuning_t t{};
+                    t.variant = SC_VARIANT_SLAB;
+                    t.wsrc = 1;
+                    t.wg_per_cu = wpc;
+                    t.wg_threads = 1024;
+                    t.tile_p = 1;
+                    t.tile_q = p.P * p.Q;
+                    t.chunk_c = cc;
+                    t.tile_d = td;
+                    t.sub_batch = fs;
                     t.pack = pk;
                     push(t);
                 }

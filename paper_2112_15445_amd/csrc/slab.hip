@@ -57,6 +57,8 @@ struct SlabArgs {
     int CC, nchunks, DTW, ndt;           // channel-chunked one-shot form
     int copies, copy_bytes;              // packed positions: shifted images of a chunk
     int SR;                              // rows of one channel image
+    int FS;                              // samples laid end to end in one tile (1: off)
+    int fs_vec;                          // ... and every sample's chunk is a 16-byte aligned block of whole 16-byte words
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -1282,7 +1284,8 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int t = bt - bg * tiles;
     // MS: the workgroup takes VPT samples of a tile of at most 64 positions (slot k of a lane is
     // sample b + k); otherwise one sample, and slot k is position k * 64 + lane
-    const int b = MS ? bg * VPT : bg;
+    // (a.FS > 1: the tile is the planes of samples b .. b + FS - 1 of a pointwise layer, end to end)
+    const int b = MS ? bg * VPT : bg * a.FS;
     const int tpi = fdiv(t, a.inv_tiles_q);
     const int tqi = t - tpi * a.tiles_q;
     const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
@@ -1299,6 +1302,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const int f = MS ? lane : (k * 64 + lane) * E + e;
+            if (!MS && a.FS > 1) {
+                const int sm = fdiv(f, 1.0f / (float)a.Qf);
+                out_off[k][e] = (f < a.F && b + sm < a.N) ? sm * a.D * a.Qf + (f - sm * a.Qf) : -1;
+                continue;
+            }
             const int tp = fdiv(f, a.inv_Qs);
             const int tq = f - tp * a.Qs;
             const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
@@ -1333,6 +1341,12 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int per_c = rcnt * vpr;                                    // loads per channel
     const float inv_per_c = 1.0f / (float)per_c, inv_vpr = 1.0f / (float)vpr;
     for (int rem = tid; rem < ((FLAT || ROWB > 0) ? 0 : a.chan_pitch); rem += nthreads) {
+        if (!MS && a.FS > 1) {
+            // element rem of a channel image is position rem % plane of sample b + rem / plane
+            const int sm = fdiv(rem, 1.0f / (float)plane);
+            tab[rem] = (rem < a.F && b + sm < a.N) ? sm * (int)a.x_sample_stride + (rem - sm * plane) : -1;
+            continue;
+        }
         const int sub = fdiv(rem, a.inv_sub_pitch);
         const int rem2 = rem - sub * a.sub_pitch;
         const int i = fdiv(rem2, a.inv_Qs);
@@ -1364,6 +1378,43 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
         if (ch > 0) __syncthreads();      // the previous chunk has been consumed
         // four elements per thread and pass, loads first, so that four loads are in flight
+        if (!MS && a.fs_vec) {
+            // samples end to end: the chunk of each sample is one contiguous block of the input, read
+            // 16 bytes per load; the elements of a load go to their channel rows one by one
+            constexpr int EPV = 16 / (int)sizeof(X);
+            struct alignas(16) Vec { X e[EPV]; };
+            const float inv_plane = 1.0f / (float)plane;
+            const int nvec = min(a.CC, a.C - c0) * plane / EPV;
+            const float inv_nvec = 1.0f / (float)nvec;
+            const int total = min(a.FS, a.N - b) * nvec;
+            for (int i0 = tid; i0 < total; i0 += kStageLoads * nthreads) {
+                Vec v[kStageLoads];
+                int smi[kStageLoads];
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < total) {
+                        smi[u] = fdiv(i, inv_nvec);
+                        const int iv = i - smi[u] * nvec;
+                        v[u] = *reinterpret_cast<const Vec*>(xb + (int64_t)smi[u] * a.x_sample_stride + (int64_t)c0 * plane + iv * EPV);
+                        smi[u] *= plane;                       // first position of the sample in a channel row
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kStageLoads; ++u) {
+                    const int i = i0 + u * nthreads;
+                    if (i < total) {
+                        const int sm = fdiv(i, inv_nvec);
+                        const int e0 = (i - sm * nvec) * EPV;
+#pragma unroll
+                        for (int j = 0; j < EPV; ++j) {
+                            const int c = fdiv(e0 + j, inv_plane);
+                            slab[c * a.chan_pitch + smi[u] + (e0 + j - c * plane)] = v[u].e[j];
+                        }
+                    }
+                }
+            }
+        } else
         for (int sm = 0; sm < (MS ? VPT : 1); ++sm) {
         if (MS && b + sm >= a.N) break;
         const X* xc = xb + (int64_t)sm * a.x_sample_stride + (int64_t)c0 * plane;
@@ -1566,7 +1617,7 @@ static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, 
 static int row_run_bytes(const Plan& p, const void* x)
 {
     const SlabGeom& g = p.geom;
-    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1) return 0;
+    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1 || g.fs != 1) return 0;
     if (g.Hf == 1) return 0;                                      // flattened pointwise layers
     if (p.L.stride_h == 1 && p.L.stride_w == 1) {
         if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
@@ -1595,7 +1646,7 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
         // of the input (and, with packed positions, no shifted images): staged as a plain copy
         const SlabGeom& g = p.geom;
         const int64_t chunk_bytes = (int64_t)g.CC * g.chan_pitch * p.ex;
-        if (g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
+        if (g.fs == 1 && g.Hf == 1 && g.Pf == 1 && g.tiles_q == 1 && g.TQ == g.Wf && g.chan_pitch == g.Wf && chunk_bytes % 16 == 0 &&
             g.copies == 1 && ((int64_t)p.L.C * g.Wf * p.ex) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
             return launch_cc_w<DT, VPT, MS, E, false, true>(p, a, x, y, grid, stream);
     }
@@ -1994,9 +2045,15 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
     a.y_plane = (int64_t)g.Pf * g.Qf;
     if (p.tuning.chunk_c > 0) {
         a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt;
-        a.copies = g.copies; a.copy_bytes = g.copy_bytes; a.SR = g.SR;
+        a.copies = g.copies; a.copy_bytes = g.copy_bytes; a.SR = g.SR; a.FS = g.fs;
+        {
+            const int64_t plane_bytes = (int64_t)g.Hf * g.Wf * p.ex;
+            a.fs_vec = (g.fs > 1 && reinterpret_cast<uintptr_t>(x) % 16 == 0 && (p.L.C * plane_bytes) % 16 == 0 &&
+                        (g.CC * plane_bytes) % 16 == 0) ? 1 : 0;
+        }
         a.inv_ndt = 1.0f / (float)g.ndt;
-        const int64_t gridc = (int64_t)((N + g.ns - 1) / g.ns) * g.tiles_p * g.tiles_q * g.ndt;
+        const int per_wg = g.ns > 1 ? g.ns : g.fs;
+        const int64_t gridc = (int64_t)((N + per_wg - 1) / per_wg) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {
             case SC_F32: return launch_cc<SC_F32>(p, a, x, y, (int)gridc, stream);

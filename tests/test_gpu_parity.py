@@ -749,3 +749,31 @@ def test_autotune_takes_the_ragged_table_when_rows_are_uneven():
     print("case ragtune", t, flush=True)
     assert t["ragged"] == 1
     G.check(l, G.run_gpu(plan, data["x"]), ref, str(t))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_samples_laid_end_to_end_in_one_packed_tile(dtype):
+    """Pointwise layers with small planes: sub_batch samples end to end along the position axis of
+    one packed tile.  7x7, 5x3 and 14x14 planes (channel pitches that need rounding up to a word),
+    batches that leave a short last group, a last chunk with fewer channels, output-channel blocks,
+    one and two slots per lane, 32- and 128-bit words."""
+    packs = {"f32": [2], "f16": [1, 2], "i8": [1]}[dtype]
+    for l, shapes in (
+            (wl.Layer("e2e7", 72, 24, 7, 7, 1, 1, 1, 1, 0, 0, N=11, sparsity=0.8, dtype=dtype, seed=61),
+             [{"sub_batch": 2, "chunk_c": 16}, {"sub_batch": 4, "chunk_c": 32, "tile_d": 8},
+              {"sub_batch": 5, "chunk_c": 72}, {"sub_batch": 10, "chunk_c": 16, "tile_d": 16}]),
+            (wl.Layer("e2e53", 33, 10, 5, 3, 1, 1, 1, 1, 0, 0, N=9, sparsity=0.6, dtype=dtype, seed=62),
+             [{"sub_batch": 3, "chunk_c": 8}, {"sub_batch": 16, "chunk_c": 16}]),
+            (wl.Layer("e2e14", 40, 20, 14, 14, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.7, dtype=dtype, seed=63),
+             [{"sub_batch": 2, "chunk_c": 8, "tile_d": 8}])):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in shapes:
+            for pack in packs:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=256, wg_per_cu=1,
+                                tile_q=l.H * l.W, pack=pack, **extra)
+                t = plan.get_tuning().as_dict()
+                assert t["sub_batch"] == extra["sub_batch"] and t["pack"] == pack and t["chunk_c"] == extra["chunk_c"]
+                print("case", l.name, dtype, t, flush=True)
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
