@@ -203,6 +203,8 @@ def main():
                     help='pin the launch shape instead of autotuning, e.g. '
                          '\'{"variant":2,"wg_threads":1024,"tile_q":64,"wg_per_cu":2,"wsrc":1}\'')
     ap.add_argument("--report", default=None, help="also time every layer of all configs -> JSON file")
+    ap.add_argument("--report-configs", default="1,2,3,4,5,6,7",
+                    help="with --report: the workload configurations to cover (comma-separated)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark, run 20 plain 256 MiB device copies (the known-size "
                          "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled against)")
@@ -292,7 +294,7 @@ def main():
 
     if args.report:
         rows = []
-        for cfg in (1, 2, 3, 4, 5, 6, 7):
+        for cfg in sorted(int(c) for c in args.report_configs.split(",")):
             for lay in wl.CONFIGS[cfg]():
                 r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl)
                 p.destroy()

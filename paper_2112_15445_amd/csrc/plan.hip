@@ -882,9 +882,11 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     // channel-chunked one-shot form on pointwise layers: for planes too small or too oddly sized
     // for the persistent forms
     if (pw && !is_codebook(p.dtype) && p.n > 0) {
-        for (int wpc : {1, 2, 3}) for (int cc : {32, 64, 128, 256}) {
-            if (cc >= p.L.C) continue;
-            for (int td : {0, 64, 128}) {
+    // (deep layers with small planes: the more channels per chunk the better -- fewer, longer
+    // (row, chunk) segments -- up to the whole LDS for one workgroup)
+        for (int wpc : {1, 2, 3}) for (int cc : {32, 64, 128, 256, 384, 512, 768, 1024}) {
+            if (cc >= p.L.C || (cc > 256 && wpc > 1)) continue;
+            for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 for (int tq : {64, 128, 256}) {
                     sc_tuning_t t{};
@@ -905,8 +907,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     }
     // the same with several samples per workgroup, for planes of at most one wave of positions
     if (!is_codebook(p.dtype) && p.n > 0 && p.P * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 64) {
-        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
-            if (cc >= p.L.C) continue;
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 192, 256, 384, 512, 768}) {
+            if (cc >= p.L.C || (cc > 256 && wpc > 1)) continue;
             for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 for (int ns : {2, 4}) {
@@ -953,8 +955,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     // 16- and 8-bit activations: the chunked one-shot form with packed positions (one LDS read per
     // 2 or 4 positions), tiles of up to 8 positions per lane
     if ((packable || wide) && p.n > 0) {
-        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256}) {
-            if (cc > p.L.C && cc != 16) continue;
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256, 512}) {
+            if ((cc > p.L.C && cc != 16) || (cc > 256 && wpc > 1)) continue;
             for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 for (int tile : {2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2}) {
@@ -977,8 +979,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     // pointwise layers with small planes: the planes of several samples end to end in one tile of
     // packed positions (up to 512 positions)
     if (pw && (packable || wide) && p.n > 0 && 2 * p.P * p.Q <= 512) {
-        for (int wpc : {1, 2}) for (int cc : {64, 128, 256}) {
-            if (cc > p.L.C) continue;
+        for (int wpc : {1, 2}) for (int cc : {64, 128, 256, 512}) {
+            if (cc > p.L.C || (cc > 256 && wpc > 1)) continue;
             for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
                 for (int fs : {2, 4}) for (int pk : {1, 2}) {

@@ -418,6 +418,8 @@ def test_headline_layer_full_size_as_benchmarked():
     ("s7_conv3x3_sp90", {"tile_p": 7, "chunk_c": 64, "tile_d": 128, "sub_batch": 2}),
     ("s7_expand1x1_sp90", {"tile_p": 1, "tile_q": 49, "chunk_c": 128, "tile_d": 128, "sub_batch": 4, "wg_per_cu": 1}),
     ("s14_reduce1x1_sp90", {"tile_p": 1, "tile_q": 128, "chunk_c": 128, "tile_d": 128, "pipeline": 2}),
+    ("s7_reduce1x1_sp90", {"tile_p": 1, "tile_q": 49, "chunk_c": 768, "tile_d": 64, "wg_per_cu": 1}),
+    ("s7_conv3x3_sp80", {"tile_p": 7, "chunk_c": 192, "tile_d": 32, "sub_batch": 2, "wg_per_cu": 1}),
 ])
 def test_full_size_layers_through_the_chunked_kernels(name, extra):
     """Full-size ResNet-50-shaped layers (batch 32) through the channel-chunked kernels with
@@ -612,12 +614,15 @@ def test_full_width_tiles_staged_by_row_runs(dtype):
     ("s14_reduce1x1_sp90", {"pipeline": 2, "tile_q": 128, "chunk_c": 256, "tile_d": 64, "pack": 1}),
     ("s7_reduce1x1_sp90", {"tile_q": 49, "chunk_c": 256, "tile_d": 32, "sub_batch": 2, "wg_per_cu": 1}),
     ("s7_expand1x1_sp90", {"tile_q": 49, "chunk_c": 256, "tile_d": 64, "sub_batch": 4, "wg_per_cu": 1, "wsrc": 3}),
+    ("s7_reduce1x1_sp80", {"tile_q": 49, "chunk_c": 768, "tile_d": 32, "sub_batch": 2, "wg_per_cu": 1}),
+    ("s7_expand1x1_sp80", {"tile_q": 49, "chunk_c": 256, "tile_d": 64, "sub_batch": 4, "wg_per_cu": 1, "pack": 1}),
 ])
 def test_full_size_half_precision_layers_packed_and_small_plane_forms(name, extra):
     """Full-size ResNet-50-shaped fp16 layers (batch 32) in the launch shapes the per-layer report
     picks: packed positions (shifted images on the 3x3 layers, row-run staging where the tile spans
-    the plane), whole-plane copies and lane-distributed weights on the 7x7 layers.  First and last
-    sample checked completely against the oracle."""
+    the plane), whole-plane copies, lane-distributed weights, chunks of 768 channels and the planes
+    of four samples end to end in one packed tile on the 7x7 layers.  First and last sample checked
+    completely against the oracle."""
     l = {x.name: x for x in wl.config4()}[name]
     data = wl.prepare(l)
     plan = G.make_plan(l, data)
