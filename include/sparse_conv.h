@@ -212,9 +212,13 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
 
 /* Per-layer launch-shape search (the gfx950 counterpart of the paper's empirical tuning of sb_S):
  * times every candidate tuning that fits the layer on the caller's buffers (y_dev is overwritten)
- * with HIP events on `stream`, keeps the fastest, and leaves it installed.  Synchronises.
- * Candidates that these pointers rule out (see sparse_conv_forward) are skipped, so the installed
- * shape is valid for buffers aligned like x_dev and y_dev.
+ * with HIP events on `stream`, times the six fastest again over a ring of scratch copies of x and
+ * scratch outputs larger than twice the 256 MB last-level cache (so that the choice holds for a
+ * caller that streams activations from HBM), keeps the fastest of those, and leaves it installed.
+ * Synchronises.  Allocates that ring (about 0.5-1 GB of device memory, aligned like x_dev / y_dev)
+ * for the duration of the call and frees it; if it cannot be had, the second round runs on the
+ * caller's buffers.  Candidates that these pointers rule out (see sparse_conv_forward) are
+ * skipped, so the installed shape is valid for buffers aligned like x_dev and y_dev.
  * workspace must hold sparse_conv_workspace_size_max(plan, N). */
 sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
                                       int32_t N, void* workspace_dev, size_t workspace_bytes,

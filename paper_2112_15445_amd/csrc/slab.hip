@@ -1250,7 +1250,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB, bool FSM>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1284,8 +1284,9 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int t = bt - bg * tiles;
     // MS: the workgroup takes VPT samples of a tile of at most 64 positions (slot k of a lane is
     // sample b + k); otherwise one sample, and slot k is position k * 64 + lane
-    // (a.FS > 1: the tile is the planes of samples b .. b + FS - 1 of a pointwise layer, end to end)
-    const int b = MS ? bg * VPT : bg * a.FS;
+    // (FSM: the tile is the planes of samples b .. b + a.FS - 1 of a pointwise layer, end to end)
+    static_assert(!FSM || (E > 1 && !MS && !LANES && !FLAT && ROWB == 0), "samples end to end: packed positions, staged by table or by blocks");
+    const int b = MS ? bg * VPT : (FSM ? bg * a.FS : bg);
     const int tpi = fdiv(t, a.inv_tiles_q);
     const int tqi = t - tpi * a.tiles_q;
     const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
@@ -1302,7 +1303,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const int f = MS ? lane : (k * 64 + lane) * E + e;
-            if (!MS && a.FS > 1) {
+            if constexpr (FSM) {
                 const int sm = fdiv(f, 1.0f / (float)a.Qf);
                 out_off[k][e] = (f < a.F && b + sm < a.N) ? sm * a.D * a.Qf + (f - sm * a.Qf) : -1;
                 continue;
@@ -1341,7 +1342,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int per_c = rcnt * vpr;                                    // loads per channel
     const float inv_per_c = 1.0f / (float)per_c, inv_vpr = 1.0f / (float)vpr;
     for (int rem = tid; rem < ((FLAT || ROWB > 0) ? 0 : a.chan_pitch); rem += nthreads) {
-        if (!MS && a.FS > 1) {
+        if constexpr (FSM) {
             // element rem of a channel image is position rem % plane of sample b + rem / plane
             const int sm = fdiv(rem, 1.0f / (float)plane);
             tab[rem] = (rem < a.F && b + sm < a.N) ? sm * (int)a.x_sample_stride + (rem - sm * plane) : -1;
@@ -1378,7 +1379,9 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
         if (ch > 0) __syncthreads();      // the previous chunk has been consumed
         // four elements per thread and pass, loads first, so that four loads are in flight
-        if (!MS && a.fs_vec) {
+        bool staged = false;
+        if constexpr (FSM) if (a.fs_vec) {
+            staged = true;
             // samples end to end: the chunk of each sample is one contiguous block of the input, read
             // 16 bytes per load; the elements of a load go to their channel rows one by one
             constexpr int EPV = 16 / (int)sizeof(X);
@@ -1406,15 +1409,21 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                     if (i < total) {
                         const int sm = fdiv(i, inv_nvec);
                         const int e0 = (i - sm * nvec) * EPV;
+                        int c = fdiv(e0, inv_plane);
+                        int pos = e0 - c * plane;
+                        int dst = c * a.chan_pitch + smi[u] + pos;
 #pragma unroll
                         for (int j = 0; j < EPV; ++j) {
-                            const int c = fdiv(e0 + j, inv_plane);
-                            slab[c * a.chan_pitch + smi[u] + (e0 + j - c * plane)] = v[u].e[j];
+                            slab[dst] = v[u].e[j];
+                            // next element: the next position, or the first of the next channel row
+                            ++pos; ++dst;
+                            if (pos == plane) { pos = 0; dst += a.chan_pitch - plane; }
                         }
                     }
                 }
             }
-        } else
+        }
+        if (!staged)
         for (int sm = 0; sm < (MS ? VPT : 1); ++sm) {
         if (MS && b + sm >= a.N) break;
         const X* xc = xb + (int64_t)sm * a.x_sample_stride + (int64_t)c0 * plane;
@@ -1593,13 +1602,13 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0, bool FSM = false>
 static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB, FSM>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1640,6 +1649,11 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
 {
     if constexpr (E == 1) {
         if (p.tuning.wsrc == 3) return launch_cc_w<DT, VPT, MS, E, true, false>(p, a, x, y, grid, stream);
+    }
+    if (p.geom.fs > 1) {
+        // samples end to end in one packed tile: its own instantiation
+        if constexpr (E > 1 && !MS) return launch_cc_w<DT, VPT, MS, E, false, false, 0, true>(p, a, x, y, grid, stream);
+        return SC_ERR_UNSUPPORTED;
     }
     {
         // pointwise layer, one tile per plane, chunk images that are whole 16-byte aligned blocks
