@@ -135,7 +135,12 @@ typedef struct {
                            pointwise) LDS holds as many shifted images of each chunk as a word has
                            positions.  0 = one position per LDS read.  With pipeline = 1 or 2 a lane's results
                            leave as one store and y must be aligned to it (4 bytes for pack = 1 with f16,
-                           16 bytes otherwise); pack = 2 there needs 16-byte aligned rows */
+                           16 bytes otherwise); pack = 2 there needs 16-byte aligned rows.
+                           3 (SC_F32 / SC_F16 / SC_I8, pipeline = 0, chunk_c > 0, sub_batch = 0) = samples
+                           interleaved: a workgroup takes 4 (f32, i8) or 8 (f16) consecutive samples and an
+                           LDS word (128 bits; 32 bits for i8) holds the same element of each, so every
+                           offset is a whole word on any layer shape -- one LDS read per stored weight
+                           feeds that many samples; at most 8 / word-size positions per lane */
 } sc_tuning_t;
 
 typedef struct {

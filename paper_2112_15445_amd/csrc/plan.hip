@@ -111,7 +111,17 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     if (o.F > kWave * kMaxVpt) return false;
     o.vpt = (o.F + kWave - 1) / kWave;
     o.pack = 1;
-    if (pack) {
+    o.si = 0;
+    if (pack == 3) {
+        // samples interleaved: an LDS word holds the same position of 4 (32-bit floats, 8-bit
+        // integers) or 8 (16-bit floats) consecutive samples, so every offset is a whole word on
+        // any layer shape; chunked one-shot form, weights by scalar loads
+        if (samples > 1 || pipeline != 0 || chunk_c <= 0 || wsrc != 1) return false;
+        if (p.dtype != SC_F32 && p.dtype != SC_F16 && p.dtype != SC_I8) return false;
+        o.si = 1;
+        o.pack = p.dtype == SC_I8 ? 4 : 16 / p.ex;
+        if (o.vpt * o.pack > 8) return false;
+    } else if (pack) {
         // packed positions: chunked forms, one sample per workgroup; a lane owns the adjacent
         // positions of one 32-bit word (pack = 1: 16- or 8-bit activations) or of one 128-bit word
         // (pack = 2: 32- or 16-bit activations), at most 8 positions
@@ -150,13 +160,13 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
         o.ns = samples;
     }
-    int64_t slab = (int64_t)o.ns * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
+    int64_t slab = (int64_t)o.ns * (o.si ? o.pack : 1) * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
     // packed positions read aligned 32-bit words only (unaligned LDS reads are several times
     // slower): unless every lambda is a whole number of words (pointwise layer, even channel
     // pitch), LDS holds `pack` images of the chunk, image s shifted by s elements, and an entry
     // with lambda = s (mod pack) reads image s at lambda - s
     o.copies = 1;
-    if (o.pack > 1 && pipeline == 0 && !(pw && o.chan_pitch % o.pack == 0)) o.copies = o.pack;
+    if (o.pack > 1 && !o.si && pipeline == 0 && !(pw && o.chan_pitch % o.pack == 0)) o.copies = o.pack;
     slab = (int64_t)o.copies * round_up((int)std::min<int64_t>(slab, kMaxLdsBytes), 16);
     if (slab > lds_budget) return false;
     o.slab_bytes = round_up((int)slab, 16);
@@ -230,7 +240,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.chunk_c == 0) t.tile_d = 0;
     if (t.ragged < 0 || t.ragged > 1) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.ragged = 0;
-    if (t.pack < 0 || t.pack > 2) return SC_ERR_UNSUPPORTED;
+    if (t.pack < 0 || t.pack > 3) return SC_ERR_UNSUPPORTED;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER;
     if (want_slab) {
@@ -398,7 +408,7 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
 {
     if (t.variant == SC_VARIANT_SLAB) {
         sc_status_t st = launch_stretch(*p, p->d_lam_slab, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
-                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex, t.chunk_c, stream);
+                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex * (g.si ? g.pack : 1), t.chunk_c, stream);
         if (st != SC_OK) return st;
         if (t.wsrc != 0 && t.chunk_c == 0) {
             st = expand_weights(*p, stream);
@@ -959,8 +969,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             if ((cc > p.L.C && cc != 16) || (cc > 256 && wpc > 1)) continue;
             for (int td : {0, 32, 64, 128}) {
                 if (td >= p.L.D && td != 0) continue;
-                for (int tile : {2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2}) {
-                    if ((pk == 1 && !packable) || (pk == 2 && !wide)) continue;
+                for (int tile : {1, 2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2, 3}) {
+                    if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3)) continue;
                     sc_tuning_t t{};
                     t.variant = SC_VARIANT_SLAB;
                     t.wsrc = 1;

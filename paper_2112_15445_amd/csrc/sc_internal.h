@@ -43,6 +43,7 @@ struct SlabGeom {
     int vec;                   // 1: slab rows can be staged with 16-byte loads
     int dmab;                  // bytes per lane of the direct-to-LDS copy the rows allow: 16, 4 or 0
     int ns;                    // samples per workgroup (chunked one-shot form, tiles of <= 64 positions)
+    int si;                    // 1: an LDS word holds the same position of `pack` consecutive samples (tuning.pack = 3)
     int fs;                    // samples laid end to end along the tile's position axis (packed one-shot chunked form on pointwise layers); 1: off
     int nwaves;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs;

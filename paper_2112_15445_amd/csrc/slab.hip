@@ -1250,7 +1250,7 @@ static sc_status_t launch_symc_one(const Plan& p, const ChunkArgs& a, const void
 // chunked table, read by scalar loads 8 entries at a time.  Loads and arithmetic of one workgroup
 // alternate; two or more workgroups per CU overlap them.
 // ------------------------------------------------------------------------------------------------
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB, bool FSM>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB, int SMODE>
 __global__ void
 slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                const int2* __restrict__ wlc, const int32_t* __restrict__ seg_off, const SlabArgs a)
@@ -1284,9 +1284,12 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     const int t = bt - bg * tiles;
     // MS: the workgroup takes VPT samples of a tile of at most 64 positions (slot k of a lane is
     // sample b + k); otherwise one sample, and slot k is position k * 64 + lane
-    // (FSM: the tile is the planes of samples b .. b + a.FS - 1 of a pointwise layer, end to end)
-    static_assert(!FSM || (E > 1 && !MS && !LANES && !FLAT && ROWB == 0), "samples end to end: packed positions, staged by table or by blocks");
-    const int b = MS ? bg * VPT : (FSM ? bg * a.FS : bg);
+    // (SMODE 1, FSM: the tile is the planes of samples b .. b + a.FS - 1 of a pointwise layer, end
+    // to end.  SMODE 2, SI: the workgroup takes E samples, an LDS word holds the same element of all
+    // of them and slot k of a lane is position k * 64 + lane of each)
+    constexpr bool FSM = SMODE == 1, SI = SMODE == 2;
+    static_assert(SMODE == 0 || (E > 1 && !MS && !LANES && !FLAT && ROWB == 0), "several samples per packed tile: staged by table or by blocks");
+    const int b = MS ? bg * VPT : (FSM ? bg * a.FS : (SI ? bg * E : bg));
     const int tpi = fdiv(t, a.inv_tiles_q);
     const int tqi = t - tpi * a.tiles_q;
     const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
@@ -1302,7 +1305,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     for (int k = 0; k < VPT; ++k) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            const int f = MS ? lane : (k * 64 + lane) * E + e;
+            const int f = (MS || SI) ? (SI ? k * 64 + lane : lane) : (k * 64 + lane) * E + e;
             if constexpr (FSM) {
                 const int sm = fdiv(f, 1.0f / (float)a.Qf);
                 out_off[k][e] = (f < a.F && b + sm < a.N) ? sm * a.D * a.Qf + (f - sm * a.Qf) : -1;
@@ -1310,7 +1313,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             }
             const int tp = fdiv(f, a.inv_Qs);
             const int tq = f - tp * a.Qs;
-            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N);
+            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N) && (!SI || b + e < a.N);
             out_off[k][e] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
         }
     }
@@ -1420,6 +1423,38 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                             if (pos == plane) { pos = 0; dst += a.chan_pitch - plane; }
                         }
                     }
+                }
+            }
+        }
+        if constexpr (SI) {
+            // one word per element of the chunk image: that element of each of the E samples
+            // (zero where the image shows padding or the batch has ended)
+            staged = true;
+            struct alignas(E * sizeof(X)) Word { X e[E]; };
+            Word* wslab = reinterpret_cast<Word*>(lds);
+            const X* xc = xb + (int64_t)c0 * plane;
+            constexpr int kWords = 2;
+            for (int e0 = tid; e0 < elems; e0 += kWords * nthreads) {
+                Word v[kWords];
+#pragma unroll
+                for (int u = 0; u < kWords; ++u) {
+                    const int e = e0 + u * nthreads;
+#pragma unroll
+                    for (int sm = 0; sm < E; ++sm) v[u].e[sm] = X(0);
+                    if (e < elems) {
+                        const int c = fdiv(e, a.inv_chan_pitch);
+                        const int o = tab[e - c * a.chan_pitch];
+                        if (o >= 0) {
+#pragma unroll
+                            for (int sm = 0; sm < E; ++sm)
+                                if (b + sm < a.N) v[u].e[sm] = xc[(int64_t)sm * a.x_sample_stride + (int64_t)c * plane + o];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kWords; ++u) {
+                    const int e = e0 + u * nthreads;
+                    if (e < elems) wslab[e] = v[u];
                 }
             }
         }
@@ -1596,19 +1631,19 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
                 for (int e = 0; e < E; ++e)
                     if (out_off[k][e] >= 0)
-                        store_out(yd + (int64_t)(MS ? k : 0) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
+                        store_out(yd + (int64_t)(MS ? k : (SI ? e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
                                   narrow<DT>(acc[r][k][e]));
         }
     }
 }
 
-template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0, bool FSM = false>
+template <sc_dtype_t DT, int VPT, bool MS, int E, bool LANES, bool FLAT, int ROWB = 0, int SMODE = 0>
 static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
                                hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB, FSM>;
+    auto kernel = slab_cc_kernel<DT, VPT, MS, E, LANES, FLAT, ROWB, SMODE>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -1626,7 +1661,7 @@ static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, 
 static int row_run_bytes(const Plan& p, const void* x)
 {
     const SlabGeom& g = p.geom;
-    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1 || g.fs != 1) return 0;
+    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1 || g.fs != 1 || g.si) return 0;
     if (g.Hf == 1) return 0;                                      // flattened pointwise layers
     if (p.L.stride_h == 1 && p.L.stride_w == 1) {
         if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
@@ -1652,7 +1687,12 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
     }
     if (p.geom.fs > 1) {
         // samples end to end in one packed tile: its own instantiation
-        if constexpr (E > 1 && !MS) return launch_cc_w<DT, VPT, MS, E, false, false, 0, true>(p, a, x, y, grid, stream);
+        if constexpr (E > 1 && !MS) return launch_cc_w<DT, VPT, MS, E, false, false, 0, 1>(p, a, x, y, grid, stream);
+        return SC_ERR_UNSUPPORTED;
+    }
+    if (p.geom.si) {
+        // the same position of E samples in one word: its own instantiation, staged by table
+        if constexpr (E > 1 && !MS) return launch_cc_w<DT, VPT, MS, E, false, false, 0, 2>(p, a, x, y, grid, stream);
         return SC_ERR_UNSUPPORTED;
     }
     {
@@ -2066,7 +2106,7 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
                         (g.CC * plane_bytes) % 16 == 0) ? 1 : 0;
         }
         a.inv_ndt = 1.0f / (float)g.ndt;
-        const int per_wg = g.ns > 1 ? g.ns : g.fs;
+        const int per_wg = g.si ? g.pack : (g.ns > 1 ? g.ns : g.fs);
         const int64_t gridc = (int64_t)((N + per_wg - 1) / per_wg) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {

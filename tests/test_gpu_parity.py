@@ -782,3 +782,32 @@ def test_samples_laid_end_to_end_in_one_packed_tile(dtype):
                 assert t["sub_batch"] == extra["sub_batch"] and t["pack"] == pack and t["chunk_c"] == extra["chunk_c"]
                 print("case", l.name, dtype, t, flush=True)
                 G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_samples_interleaved_in_the_lds_word(dtype):
+    """tuning.pack = 3: an LDS word holds the same position of 4 (f32, i8) or 8 (f16) consecutive
+    samples, so the wide reads work on any layer shape.  3x3 with padding, stride 2, a 1x3 filter, a
+    pointwise layer; batches that leave a short last group (and one smaller than a word); a last
+    chunk with fewer channels; one and two slots per lane; output-channel blocks."""
+    for l, shapes in (
+            (wl.Layer("si3x3", 40, 24, 7, 7, 3, 3, 1, 1, 1, 1, N=11, sparsity=0.8, dtype=dtype, seed=71),
+             [{"tile_p": 7, "chunk_c": 16}, {"tile_p": 7, "chunk_c": 8, "tile_d": 8}, {"tile_p": 3, "chunk_c": 40}]),
+            (wl.Layer("si14", 24, 12, 14, 14, 3, 3, 1, 1, 1, 1, N=5, sparsity=0.7, dtype=dtype, seed=72),
+             [{"tile_p": 4, "chunk_c": 8}] + ([{"tile_p": 8, "chunk_c": 8, "tile_d": 4}] if dtype != "f16" else [])),
+            (wl.Layer("sis2", 20, 16, 15, 13, 3, 3, 2, 2, 1, 1, N=3, sparsity=0.6, dtype=dtype, seed=73),
+             [{"tile_p": 4, "chunk_c": 8}, {"tile_p": 8, "chunk_c": 4}]),
+            (wl.Layer("si1x3", 30, 10, 1, 40, 1, 3, 1, 1, 0, 1, N=9, sparsity=0.5, dtype=dtype, seed=74),
+             [{"tile_p": 1, "chunk_c": 16}]),
+            (wl.Layer("sipw", 32, 16, 6, 5, 1, 1, 1, 1, 0, 0, N=6, sparsity=0.5, dtype=dtype, seed=75),
+             [{"tile_p": 1, "tile_q": 30, "chunk_c": 8}])):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in shapes:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=256, wg_per_cu=1,
+                            pack=3, **{"tile_q": l.Q if l.R * l.S > 1 else l.H * l.W, **extra})
+            t = plan.get_tuning().as_dict()
+            assert t["pack"] == 3 and t["chunk_c"] == extra["chunk_c"]
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
