@@ -1099,7 +1099,27 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
     int best_i = -1;
     if (st == SC_OK && !timed.empty()) {
         std::sort(timed.begin(), timed.end());
-        const size_t finalists = std::min<size_t>(timed.size(), 6);
+        // finalists: the six fastest, and the fastest of every kernel family (variant, pipeline,
+        // packing, samples per workgroup) not among them -- near-identical shapes of one family
+        // must not crowd out the family that wins once the buffers rotate
+        {
+            auto family = [&](int i) {
+                const sc_tuning_t& c = cands[i];
+                return (c.variant << 12) | (c.pipeline << 8) | (c.pack << 4) | (c.sub_batch > 1 ? 2 : 0) | (c.chunk_c > 0 ? 1 : 0);
+            };
+            std::vector<int> seen;
+            size_t keep = std::min<size_t>(timed.size(), 6);
+            for (size_t k = 0; k < keep; ++k) seen.push_back(family(timed[k].second));
+            for (size_t k = keep; k < timed.size() && keep < 16; ++k) {
+                const int f = family(timed[k].second);
+                if (std::find(seen.begin(), seen.end(), f) != seen.end()) continue;
+                seen.push_back(f);
+                std::swap(timed[keep], timed[k]);
+                ++keep;
+            }
+            timed.resize(keep);
+        }
+        const size_t finalists = timed.size();
         const size_t x_bytes = (size_t)N * p->L.C * p->L.H * p->L.W * p->ex;
         const size_t y_bytes = (size_t)N * p->L.D * p->P * p->Q * p->ey;
         const size_t x_mis = reinterpret_cast<uintptr_t>(x_dev) & 255, y_mis = reinterpret_cast<uintptr_t>(y_dev) & 255;
