@@ -217,7 +217,7 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
 
 /* Per-layer launch-shape search (the gfx950 counterpart of the paper's empirical tuning of sb_S):
  * times every candidate tuning that fits the layer on the caller's buffers (y_dev is overwritten)
- * with HIP events on `stream`, times the six fastest again over a ring of scratch copies of x and
+ * with HIP events on `stream`, times the fastest few (of every kernel family) again over a ring of scratch copies of x and
  * scratch outputs larger than twice the 256 MB last-level cache (so that the choice holds for a
  * caller that streams activations from HBM), keeps the fastest of those, and leaves it installed.
  * Synchronises.  Allocates that ring (about 0.5-1 GB of device memory, aligned like x_dev / y_dev)
