@@ -967,10 +967,10 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     if ((packable || wide) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256, 384, 512}) {
             if ((cc > p.L.C && cc != 16) || (cc > 256 && wpc > 1)) continue;
-            for (int td : {0, 32, 64, 128}) {
+            for (int td : {0, 16, 32, 64, 128}) {   // (16: with interleaved samples only -- enough workgroups on small layers)
                 if (td >= p.L.D && td != 0) continue;
                 for (int tile : {1, 2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2, 3}) {
-                    if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3)) continue;
+                    if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3) || (td == 16 && pk != 3)) continue;
                     sc_tuning_t t{};
                     t.variant = SC_VARIANT_SLAB;
                     t.wsrc = 1;
