@@ -420,10 +420,14 @@ def test_headline_layer_full_size_as_benchmarked():
     ("s14_reduce1x1_sp90", {"tile_p": 1, "tile_q": 128, "chunk_c": 128, "tile_d": 128, "pipeline": 2}),
     ("s7_reduce1x1_sp90", {"tile_p": 1, "tile_q": 49, "chunk_c": 768, "tile_d": 64, "wg_per_cu": 1}),
     ("s7_conv3x3_sp80", {"tile_p": 7, "chunk_c": 192, "tile_d": 32, "sub_batch": 2, "wg_per_cu": 1}),
+    ("s7_conv3x3_sp80", {"tile_p": 7, "chunk_c": 64, "tile_d": 16, "wg_per_cu": 1, "pack": 3}),
+    ("s56_conv3x3_sp80", {"tile_p": 2, "chunk_c": 32, "tile_d": 64, "wg_per_cu": 1, "pack": 3}),
+    ("s14_conv3x3_s2_sp90", {"tile_p": 4, "chunk_c": 32, "tile_d": 32, "wg_per_cu": 1, "pack": 3}),
 ])
 def test_full_size_layers_through_the_chunked_kernels(name, extra):
     """Full-size ResNet-50-shaped layers (batch 32) through the channel-chunked kernels with
-    output-channel blocks and several samples per workgroup; first and last sample checked."""
+    output-channel blocks, several samples per workgroup and samples interleaved in the LDS word;
+    first and last sample checked."""
     l = {x.name: x for x in wl.config3()}[name]
     data = wl.prepare(l)
     plan = G.make_plan(l, data)
