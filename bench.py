@@ -15,7 +15,9 @@ every launch really streams from HBM.
 Prints ONE JSON line: metric / value / unit (useful GFLOP/s of the layer), ms_per_step, config
 (workload and launch shape), timing_spread (median / min / max of ten short cold runs and a
 cache-warm run, for context), roofline (algorithmic bytes per launch over the measured kernel time,
-against the 8 TB/s HBM peak), the dense MIOpen time of the same layer for context, and
+against the 8 TB/s HBM peak), a measured plain-copy bandwidth beside it), parity (the launch shape that was timed, checked
+against the CPU oracle outside the timed region; a mismatch makes the exit status 1), the dense
+MIOpen time of the same layer for context (cache-warm and over the same cold ring), and
 cpu_baseline (the CPU oracle timed on the host cores).
 """
 from __future__ import annotations
@@ -36,12 +38,12 @@ INFINITY_CACHE_BYTES = 256 << 20
 
 # HBM traffic per launch of the dominant kernel, measured offline with rocprofv3 --pmc
 # (FETCH_SIZE / WRITE_SIZE, scaled by the same counters on a plain copy kernel); the summaries and
-# the commands that produced them are under profiles/.  Keyed by workload name; None = not measured.
+# the commands that produced them are under profiles/.  Keyed by (workload, launch shape): a run in
+# which the autotuner installs another shape reports no traffic figure rather than a stale one.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 50394.5 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25123.9 KiB x 1.000, measured
-    # for the persistent chunked slab kernel the autotuner picks (the other slab kernels move the same
-    # bytes to within 0.2 %)
-    "s56_reduce1x1_sp90": int((50394.5 * 2.000 + 25123.9 * 1.000) * 1024),
+    # FETCH_SIZE 50394.5 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25123.9 KiB x 1.000
+    ("s56_reduce1x1_sp90", "variant=2 wg_threads=1024 tile_p=1 tile_q=512 wg_per_cu=1 wsrc=1 pipeline=1 "
+     "producers=2 chunk_c=32 tile_d=64 pack=2"): int((50394.5 * 2.000 + 25123.9 * 1.000) * 1024),
 }
 
 
@@ -51,7 +53,7 @@ def _ring(plan, data, l, torch, G, B):
     x0 = G.to_device(data["x"])
     ybytes = l.N * l.D * inf.P * inf.Q * (2 if l.dtype in ("f16", "cb4h") else 4)
     per = x0.numel() * x0.element_size() + ybytes
-    R = max(2, min(16, int(2 * INFINITY_CACHE_BYTES // per) + 1))
+    R = max(2, min(1024, int(2 * INFINITY_CACHE_BYTES // per) + 2))      # sized by bytes, not by count
     xs = [x0] + [x0.clone() for _ in range(R - 1)]
     ys = [torch.empty((l.N, l.D, inf.P, inf.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
           for _ in range(R)]
@@ -87,25 +89,62 @@ def _spread(plan, xs, ys, ws, N, torch, repeats=10, launches=100):
             "min_ms": min(vals), "max_ms": max(vals), "cache_warm_ms": warm}
 
 
-def _dense_reference_ms(l, torch, reps=30):
-    """Dense MIOpen convolution of the same layer (torch conv2d), cache-warm, for context."""
+def _dense_reference_ms(l, torch, xs=None, reps=30):
+    """Dense MIOpen convolution of the same layer (torch conv2d), for context: (cache-warm ms on one
+    buffer pair, cold ms rotating over the same ring of inputs the sparse kernel is timed on, with as
+    many outputs kept alive).  Whatever layout changes the library makes around its kernel are
+    inside both figures."""
     dt = {"f32": torch.float32, "f16": torch.float16, "cb4h": torch.float16}.get(l.dtype)
     if dt is None:
-        return None
+        return None, None
     x = torch.empty((l.N, l.C, l.H, l.W), dtype=dt, device="cuda").uniform_(-1, 1)
     w = torch.empty((l.D, l.C, l.R, l.S), dtype=dt, device="cuda").normal_(0, 0.05)
-    conv = lambda: torch.nn.functional.conv2d(x, w, stride=(l.stride_h, l.stride_w),
-                                              padding=(l.pad_h, l.pad_w))
+    conv = lambda inp: torch.nn.functional.conv2d(inp, w, stride=(l.stride_h, l.stride_w),
+                                                  padding=(l.pad_h, l.pad_w))
     for _ in range(3):
-        conv()
+        conv(x)
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        conv()
+        conv(x)
     e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
+    warm = e0.elapsed_time(e1) / reps
+    cold = None
+    if xs is not None and xs[0].dtype == dt:
+        R = len(xs)
+        keep = [None] * R
+        n = max(reps, min(R, 300))
+        for i in range(min(R, n)):        # the allocator hands out R distinct output blocks from here on
+            keep[i % R] = conv(xs[i % R])
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            keep[i % R] = conv(xs[i % R])
+        e1.record()
+        torch.cuda.synchronize()
+        cold = e0.elapsed_time(e1) / n
+        del keep
+    return warm, cold
+
+
+def _copy_bandwidth_gbs(torch, mib=256, reps=20):
+    """A plain device-to-device streaming copy on this GPU (read + written bytes per second): what
+    the 8 TB/s peak comes down to for the simplest kernel there is."""
+    a = torch.empty(mib << 18, dtype=torch.float32, device="cuda").fill_(1)
+    bufs = [torch.empty_like(a) for _ in range(3)]
+    for b in bufs:
+        b.copy_(a)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        bufs[i % 3].copy_(a if i % 2 == 0 else bufs[(i + 1) % 3])
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * (mib << 20) * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def _cpu_baseline(l, data, oracle, max_samples):
@@ -156,7 +195,13 @@ def _graph_time_ms(plan, xs, ys, ws, N, torch, launches=100, replays=5):
     return sum(times[1:]) / replays
 
 
-def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuning=None, spread=False):
+def _tuning_key(t):
+    """Launch shape as a short canonical string (the non-zero fields of sc_tuning_t)."""
+    return " ".join(f"{k}={v}" for k, v in t.items() if v)
+
+
+def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuning=None, spread=False,
+              parity=True):
     data = wl.prepare(l)
     plan = G.make_plan(l, data)
     if tuning:
@@ -164,14 +209,20 @@ def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuni
         autotune = False
     xs, ys = _ring(plan, data, l, torch, G, B)
     ws_bytes = plan.workspace_size_max(l.N)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
     if autotune:
+        # a workspace that also holds the autotuner's ring of scratch buffers: the search then
+        # allocates nothing itself
+        ws = torch.empty(max(plan.autotune_workspace_size(l.N), 16), dtype=torch.uint8, device="cuda")
         plan.autotune(xs[0].data_ptr(), ys[0].data_ptr(), l.N, ws.data_ptr(), ws.numel(),
                       torch.cuda.current_stream().cuda_stream)
+        del ws
+        torch.cuda.empty_cache()
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
     wall_ms, ev_ms = _time_steps(plan, xs, ys, ws, l.N, steps, warmup, torch)
     inf = plan.info()
     useful = 2.0 * l.N * inf.useful_macs_per_sample
     alg_bytes = l.N * inf.act_bytes_per_sample + inf.weight_bytes
+    ring_bytes = sum(t.numel() * t.element_size() for t in xs + ys)
     out = {
         "layer": l.name, "dtype": l.dtype, "n": inf.n, "ms_wall": wall_ms, "ms_events": ev_ms,
         "useful_gflops": useful / (wall_ms * 1e-3) / 1e9,
@@ -179,14 +230,19 @@ def run_layer(l, steps, warmup, autotune, torch, G, B, wl, with_dense=True, tuni
         "achieved_gbs": alg_bytes / (ev_ms * 1e-3) / 1e9,
         "hbm_frac": alg_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "tuning": inf.tuning.as_dict(), "lds_bytes": inf.lds_bytes, "ring": len(xs),
+        "ring_bytes": ring_bytes,
     }
     if ev_ms < 0.010:
         # launch-limited: back-to-back launches from the host cannot keep up with kernels this short
-        out["graph_ms"] = _graph_time_ms(plan, xs, ys, ws, l.N, torch)
+        out["graph_ms"] = _graph_time_ms(plan, xs[:64], ys[:64], ws, l.N, torch)
     if with_dense:
-        out["dense_miopen_ms"] = _dense_reference_ms(l, torch)
+        out["dense_miopen_ms"], out["dense_miopen_cold_ms"] = _dense_reference_ms(l, torch, xs)
     if spread:
         out["spread"] = _spread(plan, xs, ys, ws, l.N, torch)
+    if parity:
+        # the launch shape that was just timed, on the full batch, against the CPU oracle (outside the
+        # timed region): samples 0..15 and the last one, element by element
+        out["parity"] = G.full_batch_parity(l, data, plan, xs[0], ws)
     return out, data, plan
 
 
@@ -202,6 +258,10 @@ def main():
     ap.add_argument("--tuning", default=None,
                     help='pin the launch shape instead of autotuning, e.g. '
                          '\'{"variant":2,"wg_threads":1024,"tile_q":64,"wg_per_cu":2,"wsrc":1}\'')
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense library reference")
+    ap.add_argument("--tunings", default=None,
+                    help="JSON list of {layer, dtype, tuning} rows (a saved --report file): install these "
+                         "launch shapes instead of autotuning")
     ap.add_argument("--report", default=None, help="also time every layer of all configs -> JSON file")
     ap.add_argument("--report-configs", default="1,2,3,4,5,6,7",
                     help="with --report: the workload configurations to cover (comma-separated)")
@@ -259,13 +319,20 @@ def main():
             plan.destroy()
         return
 
+    tunings = {}
+    if args.tunings:
+        tunings = {(r["layer"], r["dtype"]): r["tuning"] for r in json.load(open(args.tunings))}
+
     l = wl.headline_layer()
     if args.layer:
-        l = {x.name: x for c in (3, 4, 2, 5, 1, 6, 7) for x in wl.CONFIGS[c]()}[args.layer]
+        cands = [x for c in (3, 4, 2, 5, 1, 6, 7) for x in wl.CONFIGS[c]() if x.name == args.layer]
+        l = ([x for x in cands if x.dtype == args.dtype] or cands)[0]
         if args.dtype:
             l = l.replace(dtype=args.dtype)
+    pinned = json.loads(args.tuning) if args.tuning else tunings.get((l.name, l.dtype))
     res, data, plan = run_layer(l, args.steps, args.warmup, not args.no_autotune, torch, G, B, wl,
-                                tuning=json.loads(args.tuning) if args.tuning else None, spread=True)
+                                with_dense=not args.no_dense, tuning=pinned, spread=True)
+    copy_gbs = _copy_bandwidth_gbs(torch)
 
     line = {
         "metric": "useful GFLOP/s (nnz MACs) per sparse conv layer",
@@ -276,16 +343,20 @@ def main():
                    "C": l.C, "D": l.D, "H": l.H, "W": l.W, "R": l.R, "S": l.S,
                    "stride": l.stride_h, "pad": l.pad_h, "batch": l.N, "sparsity": l.sparsity,
                    "n_per_channel": res["n"], "tuning": res["tuning"], "lds_bytes": res["lds_bytes"],
-                   "buffer_ring": res["ring"], "cache": "cold (ring > 2x Infinity Cache)"},
+                   "buffer_ring": res["ring"], "buffer_ring_bytes": res["ring_bytes"],
+                   "cache": "cold (ring > 2x Infinity Cache)"},
         "roofline": {"bound": "hbm", "achieved": res["achieved_gbs"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": res["hbm_frac"],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(l.name),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((l.name, _tuning_key(res["tuning"]))),
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
-                     "kernel_ms": res["ms_events"]},
+                     "kernel_ms": res["ms_events"],
+                     "measured_copy_gbs": copy_gbs, "frac_of_measured_copy": res["achieved_gbs"] / copy_gbs},
+        "parity": res.get("parity"),
         "timing_spread": res.get("spread"),
         "dense_miopen_ms": res.get("dense_miopen_ms"),
-        "sparse_vs_dense_speedup": (res["dense_miopen_ms"] / res["ms_events"]
-                                    if res.get("dense_miopen_ms") else None),
+        "dense_miopen_cold_ms": res.get("dense_miopen_cold_ms"),
+        "sparse_vs_dense_speedup": (res["dense_miopen_cold_ms"] / res["ms_events"]
+                                    if res.get("dense_miopen_cold_ms") else None),
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -296,39 +367,104 @@ def main():
         rows = []
         for cfg in sorted(int(c) for c in args.report_configs.split(",")):
             for lay in wl.CONFIGS[cfg]():
-                r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl)
+                r, _, p = run_layer(lay, 200, 10, not args.no_autotune, torch, G, B, wl,
+                                    with_dense=not args.no_dense, tuning=tunings.get((lay.name, lay.dtype)))
                 p.destroy()
                 r["config"] = cfg
                 rows.append(r)
                 print(json.dumps(r), file=sys.stderr, flush=True)
                 torch.cuda.empty_cache()
-        with open(args.report, "w") as f:
-            json.dump(rows, f, indent=1)
-        with open(args.report + ".txt", "w") as f:      # the same rows as a table
-            # per-layer choice between the sparse kernel and the dense library (the paper's main
-            # scheme, steps 3-4: compare layer times, then configure the network)
-            for cfg in sorted({r["config"] for r in rows}):
-                rs = [r for r in rows if r["config"] == cfg and r.get("dense_miopen_ms")]
-                if rs:
-                    sp = sum(r["ms_events"] for r in rs) * 1e3
-                    de = sum(r["dense_miopen_ms"] for r in rs) * 1e3
-                    di = sum(min(r["ms_events"], r["dense_miopen_ms"]) for r in rs) * 1e3
-                    f.write(f"# config {cfg}: sum over {len(rs)} layers: all sparse {sp:.1f} us, all dense {de:.1f} us, "
-                            f"faster of the two per layer {di:.1f} us\n")
-            for r in rows:
-                if r.get("graph_ms"):
-                    f.write(f"# {r['layer']} ({r['dtype']}): {r['ms_events']*1e3:.2f} us between events, "
-                            f"{r['graph_ms']*1e3:.2f} us per launch inside a captured HIP graph\n")
-            f.write("cfg layer                      dtype    n   sparse_us  alg_GB/s  hbm_frac  useful_TF  "
-                    "dense_us  launch shape\n")
-            for r in rows:
-                t = {k: v for k, v in r["tuning"].items() if v}
-                dm = r.get("dense_miopen_ms")
-                f.write(f"{r['config']:3d} {r['layer']:26s} {r['dtype']:4s} {r['n']:5d} {r['ms_events']*1e3:10.2f} "
-                        f"{r['achieved_gbs']:9.0f} {r['hbm_frac']*100:8.1f}% {r['useful_gflops']/1e3:9.2f} "
-                        f"{(dm*1e3 if dm else float('nan')):9.2f}  {json.dumps(t)}\n")
+                with open(args.report, "w") as f:          # rewritten after every layer: a run cut short keeps its rows
+                    json.dump(rows, f, indent=1)
+        with open(args.report + ".txt", "w") as f:
+            f.write(report_table(rows))
 
     print(json.dumps(line), flush=True)
+    if line["parity"] is not None and not line["parity"]["ok"]:
+        sys.exit(1)
+
+
+def short_shape(t):
+    """One-line name of a launch shape."""
+    if t.get("variant") == 1:
+        return f"gather sb{t.get('sub_batch', 0)} split{t.get('split_n', 1)}"
+    sh = "slab"
+    if t.get("pipeline"):
+        sh += f" pl{t['pipeline']}"
+    if t.get("producers"):
+        sh += f" np{t['producers']}"
+    sh += f" tp{t.get('tile_p', 1)} tq{t.get('tile_q', 0)} thr{t.get('wg_threads')} wpc{t.get('wg_per_cu', 1)} ws{t.get('wsrc', 0)}"
+    if t.get("chunk_c"):
+        sh += f" cc{t['chunk_c']} td{t.get('tile_d', 0)}"
+    if t.get("sub_batch"):
+        sh += f" ns{t['sub_batch']}"
+    if t.get("pack"):
+        sh += {1: " pk32", 2: " pk128", 3: " si"}.get(t["pack"], f" pk?{t['pack']}")
+    if t.get("ragged"):
+        sh += " ragged"
+    return sh
+
+
+def report_table(rows):
+    """The per-layer rows as text: break-even tables against the dense library (both timed cold, over
+    the same ring of inputs), per-configuration sums (all sparse / all dense / the faster of the two
+    per layer -- the per-layer choice of the paper's main scheme), then one line per layer."""
+    import collections
+    out = []
+
+    def dense(r):
+        return r.get("dense_miopen_cold_ms") or r.get("dense_miopen_ms")
+
+    def ratio(r):
+        return dense(r) / r["ms_events"] if dense(r) else None
+
+    bad = [r for r in rows if r.get("parity") and not r["parity"]["ok"]]
+    checked = [r for r in rows if r.get("parity")]
+    out.append(f"# parity: {len(checked) - len(bad)} of {len(checked)} layers match the CPU oracle in the launch shape timed "
+               "(samples 0..15 and the last one of the full batch, element by element)")
+    for cfg in sorted({r["config"] for r in rows}):
+        rs = [r for r in rows if r["config"] == cfg and ratio(r)]
+        if rs:
+            w = sum(1 for r in rs if ratio(r) >= 1.0)
+            out.append(f"# config {cfg}: sparse kernel faster than the dense library on {w} of {len(rs)} layers")
+    fam = collections.defaultdict(list)
+    for r in rows:
+        if r["config"] in (3, 4) and ratio(r) and "_sp" in r["layer"]:
+            name, sp = r["layer"].rsplit("_sp", 1)
+            fam[(r["config"], name)].append((int(sp), ratio(r)))
+    for cfg in (4, 3):
+        if any(k[0] == cfg for k in fam):
+            out.append(f"# break-even against the dense library, config {cfg} (speed-up = dense_us / sparse_us, both cold):")
+            for (c, name), v in fam.items():
+                if c != cfg:
+                    continue
+                v.sort()
+                be = [sp for sp, ra in v if ra >= 1.0]
+                out.append(f"#   {name:18s} {'>= %d %%' % min(be) if be else ' > %d %%' % v[-1][0]:9s} "
+                           + "  ".join(f"{sp}%: {ra:4.2f}x" for sp, ra in v))
+    for cfg in sorted({r["config"] for r in rows}):
+        rs = [r for r in rows if r["config"] == cfg and dense(r)]
+        if rs:
+            sp = sum(r["ms_events"] for r in rs) * 1e3
+            de = sum(dense(r) for r in rs) * 1e3
+            di = sum(min(r["ms_events"], dense(r)) for r in rs) * 1e3
+            out.append(f"# config {cfg}: sum over {len(rs)} layers: all sparse {sp:.1f} us, all dense {de:.1f} us, "
+                       f"faster of the two per layer {di:.1f} us")
+    for r in rows:
+        if r.get("graph_ms"):
+            out.append(f"# {r['layer']} ({r['dtype']}): {r['ms_events']*1e3:.2f} us between events, "
+                       f"{r['graph_ms']*1e3:.2f} us per launch inside a captured HIP graph (launch-limited)")
+    out.append("cfg layer                      dtype    n   sparse_us  alg_GB/s  hbm_frac  useful_TF  dense_cold_us "
+               "dense_warm_us  parity    launch shape")
+    for r in rows:
+        dc, dw = r.get("dense_miopen_cold_ms"), r.get("dense_miopen_ms")
+        par = r.get("parity")
+        ptxt = "-" if par is None else ("ok" if par["ok"] else "FAIL")
+        out.append(f"{r['config']:3d} {r['layer']:26s} {r['dtype']:4s} {r['n']:5d} {r['ms_events']*1e3:10.2f} "
+                   f"{r['achieved_gbs']:9.0f} {r['hbm_frac']*100:8.1f}% {r['useful_gflops']/1e3:9.2f} "
+                   f"{(dc*1e3 if dc else float('nan')):13.2f} {(dw*1e3 if dw else float('nan')):13.2f}  {ptxt:8s}  "
+                   f"{short_shape(r['tuning'])}")
+    return "\n".join(out) + "\n"
 
 
 if __name__ == "__main__":

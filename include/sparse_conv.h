@@ -182,15 +182,21 @@ sc_status_t sparse_conv_plan_create_ell(const sc_layer_t* layer, sc_dtype_t dtyp
 
 void sparse_conv_plan_destroy(sparse_conv_plan_t* plan); /* NULL is allowed */
 
-/* Geometry, traffic model and current tuning of a plan. */
+/* Geometry, traffic model and current tuning of a plan: the unified stored count N_nz of the section
+ * "Convolution operation using a sparse operation on GPGPU", the output extents that follow from
+ * the padded input of eq. load_in_to_registers (t_in_p), and the multiply-accumulate count that the
+ * GPU results section states is the dense count reduced by the sparsity ratio. */
 sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t* info);
 
-/* Test hook for the stretch pass: copies the device-built canonical offsets
+/* Test hook for the stretch pass (same section: the column-index array Lambda "is modified to store
+ * these pre-computed indexes"; the formula itself is the one that makes Algorithm 3's address
+ * t_in_p + lambda hit input element (c, p*s_h + r, q*s_w + s)): copies the device-built canonical offsets
  * lambda[d][j] = c*Hp*Wp + r*Wp + s (elements, relative to one padded sample) to host_out [D*n].
  * Synchronises the device. */
 sc_status_t sparse_conv_plan_debug_offsets(const sparse_conv_plan_t* plan, int32_t* host_out);
 
-/* Replace the launch shape.  Fields left 0 are filled by heuristic.  SC_ERR_UNSUPPORTED if the
+/* Replace the launch shape -- the per-layer choice the paper makes through sb_S (eq. N_B and the
+ * table "Impact of the number of thread blocks").  Fields left 0 are filled by heuristic.  SC_ERR_UNSUPPORTED if the
  * shape does not fit the layer (e.g. the slab does not fit in LDS); the previous tuning stays.
  * Rebuilds the variant-specific offset table on `stream` and waits for it. */
 sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tuning_t* tuning,
@@ -198,13 +204,18 @@ sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tunin
 sc_status_t sparse_conv_plan_get_tuning(const sparse_conv_plan_t* plan, sc_tuning_t* tuning);
 
 /* Bytes of device workspace sparse_conv_forward needs for batch N with the current tuning
- * (0 unless the GATHER variant has to materialise a padded input). */
+ * (0 unless the GATHER variant has to materialise a padded input, as the paper's own kernel is fed:
+ * the GPU results section lists its inputs with the padding already in place, 226 x 226 for
+ * 224 x 224). */
 sc_status_t sparse_conv_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
 
 /* Upper bound of sparse_conv_workspace_size over every tuning autotune may try. */
 sc_status_t sparse_conv_workspace_size_max(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
 
-/* Y = conv(X): x_dev [N,C,H,W] unpadded, y_dev [N,D,P,Q], both contiguous device memory in the
+/* The forward pass of Algorithm 3 ("Convolution operation using a sparse operation on GPGPU"):
+ * every output value is the sum over the N_nz stored entries of its output channel of
+ * theta * input[t_in_p + lambda] (eq. load_in_to_registers), one accumulator per output, one store.
+ * Y = conv(X): x_dev [N,C,H,W] unpadded, y_dev [N,D,P,Q], both contiguous device memory in the
  * plan's storage types, aligned to their element size.  Asynchronous on `stream`; allocates nothing.
  * The pipelined launch shapes (tuning.pipeline = 1 or 2) copy rows with 16-byte (4-byte where the
  * rows allow no more) direct-to-LDS loads and need x_dev aligned to that; with tuning.pack they
@@ -215,19 +226,32 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
                                 int32_t N, void* workspace_dev, size_t workspace_bytes,
                                 void* stream);
 
-/* Per-layer launch-shape search (the gfx950 counterpart of the paper's empirical tuning of sb_S):
- * times every candidate tuning that fits the layer on the caller's buffers (y_dev is overwritten)
- * with HIP events on `stream`, times the fastest few (of every kernel family) again over a ring of scratch copies of x and
- * scratch outputs larger than twice the 256 MB last-level cache (so that the choice holds for a
+/* Per-layer launch-shape search: the gfx950 counterpart of the paper's empirical per-layer tuning
+ * of the sub-batch size sb_S and with it of the number of thread blocks (eq. N_B = b_S * D / sb_S and
+ * the table "Impact of the number of thread blocks" in the GPU results).  Times every candidate
+ * tuning that fits the layer on the caller's buffers (y_dev is overwritten) with HIP events on
+ * `stream`, times the fastest few (of every kernel family) again over a ring of scratch copies of x
+ * and scratch outputs larger than twice the 256 MB last-level cache (so that the choice holds for a
  * caller that streams activations from HBM), keeps the fastest of those, and leaves it installed.
- * Synchronises.  Allocates that ring (about 0.5-1 GB of device memory, aligned like x_dev / y_dev)
- * for the duration of the call and frees it; if it cannot be had, the second round runs on the
- * caller's buffers.  Candidates that these pointers rule out (see sparse_conv_forward) are
- * skipped, so the installed shape is valid for buffers aligned like x_dev and y_dev.
- * workspace must hold sparse_conv_workspace_size_max(plan, N). */
+ * Synchronises.
+ *   workspace_dev   must hold sparse_conv_workspace_size_max(plan, N) bytes.  When it holds
+ *                   sparse_conv_autotune_workspace_size(plan, N) bytes the ring lies in it and the
+ *                   call allocates no device memory besides the tables of the tunings it installs;
+ *                   otherwise the ring (0.5-1 GB, aligned like x_dev / y_dev) is allocated for the
+ *                   duration of the call and freed, and if that fails the second round runs on
+ *                   the caller's buffers.
+ * Candidates that these pointers rule out (see sparse_conv_forward) are skipped, so the installed
+ * shape is valid for buffers aligned like x_dev and y_dev.
+ * On any error the tuning the plan had on entry is installed again before the call returns.
+ * Errors: SC_ERR_NULL, SC_ERR_SHAPE, SC_ERR_WORKSPACE, SC_ERR_UNSUPPORTED (no candidate runs),
+ * SC_ERR_OOM, SC_ERR_HIP. */
 sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
                                       int32_t N, void* workspace_dev, size_t workspace_bytes,
                                       void* stream);
+
+/* Bytes of workspace with which sparse_conv_plan_autotune takes its ring of scratch buffers from the
+ * caller instead of allocating it (an upper bound over the alignments x_dev / y_dev may have). */
+sc_status_t sparse_conv_autotune_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
 
 /* Number of candidates sparse_conv_plan_autotune would time for this plan, and the i-th of them
  * (for tests that check that every candidate computes the same result). */

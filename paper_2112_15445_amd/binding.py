@@ -29,7 +29,8 @@ EXPORTS = [
     "sparse_conv_plan_create_csr", "sparse_conv_plan_create_ell", "sparse_conv_plan_destroy",
     "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning",
     "sparse_conv_plan_get_tuning", "sparse_conv_workspace_size", "sparse_conv_workspace_size_max",
-    "sparse_conv_forward", "sparse_conv_plan_autotune", "sparse_conv_plan_num_candidates",
+    "sparse_conv_forward", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size",
+    "sparse_conv_plan_num_candidates",
     "sparse_conv_plan_candidate", "sparse_conv_quantize_pow2", "sparse_conv_status_string",
 ]
 
@@ -96,6 +97,7 @@ def lib() -> ctypes.CDLL:
     L.sparse_conv_workspace_size_max.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_forward.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.sparse_conv_plan_autotune.argtypes = [vp, vp, vp, i32, vp, sz, vp]
+    L.sparse_conv_autotune_workspace_size.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_plan_num_candidates.argtypes = [vp, P(i32)]
     L.sparse_conv_plan_candidate.argtypes = [vp, i32, P(sc_tuning_t)]
     L.sparse_conv_quantize_pow2.argtypes = [vp, sz, i32, ctypes.c_float, vp, P(i32)]
@@ -222,6 +224,12 @@ class Plan:
         b = ctypes.c_size_t()
         _check(lib().sparse_conv_workspace_size_max(self._h, N, ctypes.byref(b)),
                "sparse_conv_workspace_size_max")
+        return int(b.value)
+
+    def autotune_workspace_size(self, N: int) -> int:
+        b = ctypes.c_size_t()
+        _check(lib().sparse_conv_autotune_workspace_size(self._h, N, ctypes.byref(b)),
+               "sparse_conv_autotune_workspace_size")
         return int(b.value)
 
     def num_candidates(self) -> int:

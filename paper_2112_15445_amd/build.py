@@ -15,8 +15,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose: bool = False, jobs: int = 4) -> str:
-    """Compile every HIP source and link the shared library.  Always recompiles."""
+def build(verbose: bool = False, jobs: int = 4, incremental: bool = False) -> str:
+    """Compile every HIP source and link the shared library.  Always recompiles, unless
+    `incremental` (development: only sources newer than their object, or older than a header)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
@@ -25,6 +26,11 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
+        if incremental and os.path.exists(obj):
+            deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
+            deps.append(os.path.join(ROOT, "include", "sparse_conv.h"))
+            if all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in deps):
+                continue
         cmd = [hipcc, "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -52,4 +58,4 @@ def _drain(procs):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

@@ -199,11 +199,15 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (!pw || wsrc == 0 || o.nwaves < 8) return false;
         o.lds_bytes = 2 * o.slab_bytes;
     }
+    // (a caller whose x is not aligned for the direct-to-LDS copies is served by the one-shot kernel
+    // with this same allocation: it must also hold that kernel's tile plus its offset table)
+    const int one_shot_bytes = o.slab_bytes + 64 + round_up(o.chan_pitch * 4, 16);
     if (pipeline == 2) {
         // symmetric form: two tile buffers, scalar-load weights, at least one stored entry per row
         if (!pw || wsrc != 1 || p.n == 0) return false;
         o.lds_bytes = 2 * o.slab_bytes;
     }
+    if (pipeline >= 1 && chunk_c <= 0) o.lds_bytes = std::max(o.lds_bytes, one_shot_bytes);
     if (o.lds_bytes > lds_budget || o.lds_bytes > kMaxLdsBytes) return false;
     // 16-byte staging needs every tile row start and the plane pitch to be 16-byte aligned
     const int epv = 16 / p.ex;
@@ -383,8 +387,11 @@ static void free_device(Plan* p)
     if (p->d_theta) (void)hipFree(p->d_theta);
     if (p->d_lam) (void)hipFree(p->d_lam);
     if (p->d_lam_slab) (void)hipFree(p->d_lam_slab);
+    if (p->d_lam_slab_spare) (void)hipFree(p->d_lam_slab_spare);
     if (p->d_wl32) (void)hipFree(p->d_wl32);
-    p->d_wl32 = nullptr;
+    if (p->d_wl32_spare) (void)hipFree(p->d_wl32_spare);
+    p->d_wl32 = p->d_wl32_spare = nullptr;
+    p->d_lam_slab_spare = nullptr;
     if (p->d_wlc) (void)hipFree(p->d_wlc);
     if (p->d_seg_off) (void)hipFree(p->d_seg_off);
     if (p->d_first_j) (void)hipFree(p->d_first_j);
@@ -404,55 +411,89 @@ static sc_status_t hip_status(hipError_t e)
     return e == hipErrorOutOfMemory ? SC_ERR_OOM : SC_ERR_HIP;
 }
 
+// Build the tables of tuning `t` beside the ones in use and swap them in only when every step has
+// succeeded: on any error the plan keeps its previous tuning, geometry and tables untouched.
 static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom& g, hipStream_t stream)
 {
-    if (t.variant == SC_VARIANT_SLAB) {
-        sc_status_t st = launch_stretch(*p, p->d_lam_slab, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
-                                        g.chan_pitch, g.sub_pitch, g.Qs, p->ex * (g.si ? g.pack : 1), t.chunk_c, stream);
-        if (st != SC_OK) return st;
-        if (t.wsrc != 0 && t.chunk_c == 0) {
-            st = expand_weights(*p, stream);
-            if (st != SC_OK) return st;
-        }
-        if (t.chunk_c > 0) {
-            // segment table of the chunked form: for every (row, chunk) the entries whose input
-            // channel lies in the chunk, contiguous because rows are sorted by column; segments
-            // are padded with zero weights to an even length (to whole 8-entry groups for the
-            // symmetric kernel).  Counted on the host, filled by a device pass.
-            const int D = p->L.D, nch = g.nchunks, RS = p->L.R * p->L.S;
-            const int pad = t.pipeline == 2 ? 8 : 2;     // the symmetric kernel reads whole 8-entry groups
-            std::vector<int32_t> seg_off((size_t)D * nch + 1, 0), first_j((size_t)D * nch, 0);
-            int64_t total = 0;
-            for (int d = 0; d < D; ++d) {
-                int j = 0;
-                for (int ch = 0; ch < nch; ++ch) {
-                    seg_off[(size_t)d * nch + ch] = (int32_t)total;
-                    first_j[(size_t)d * nch + ch] = j;
-                    int cnt = 0;
-                    // (ragged: the fillers, which sit behind the row's own entries, are left out)
-                    const int jend = t.ragged ? p->h_len[d] : p->n;
-                    while (j < jend && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt; }
-                    total += (cnt + pad - 1) / pad * pad;
-                }
+    if (t.variant != SC_VARIANT_SLAB) {
+        p->tuning = t;
+        p->geom = g;
+        return SC_OK;
+    }
+    const size_t cnt = (size_t)p->L.D * p->n;
+    hipError_t e;
+    // spare copies of the two tables that are rewritten in place: allocated on first use, then the
+    // roles of (table, spare) swap with every successful install
+    if (cnt && !p->d_lam_slab_spare &&
+        (e = hipMalloc((void**)&p->d_lam_slab_spare, cnt * 4)) != hipSuccess) return hip_status(e);
+    const bool want_wl32 = t.wsrc != 0 && t.chunk_c == 0 && p->d_wl32;
+    const size_t wl_bytes = ((size_t)p->L.D * p->np + 8) * 8;
+    if (want_wl32 && !p->d_wl32_spare) {
+        if ((e = hipMalloc((void**)&p->d_wl32_spare, wl_bytes)) != hipSuccess) return hip_status(e);
+    }
+    int2* wlc = nullptr;
+    int32_t *seg = nullptr, *fj = nullptr;
+    auto fail = [&](sc_status_t st) {
+        (void)hipStreamSynchronize(stream);
+        if (wlc) (void)hipFree(wlc);
+        if (seg) (void)hipFree(seg);
+        if (fj) (void)hipFree(fj);
+        return st;
+    };
+    sc_status_t st = launch_stretch(*p, p->d_lam_slab_spare, g.nsh, g.nsw, p->L.stride_h, p->L.stride_w,
+                                    g.chan_pitch, g.sub_pitch, g.Qs, p->ex * (g.si ? g.pack : 1), t.chunk_c, stream);
+    if (st != SC_OK) return fail(st);
+    if (want_wl32) {
+        // (the 8 slack entries behind the table stay zero: the pass writes the rows only)
+        if ((e = hipMemsetAsync(p->d_wl32_spare, 0, wl_bytes, stream)) != hipSuccess) return fail(hip_status(e));
+        st = expand_weights(*p, p->d_lam_slab_spare, p->d_wl32_spare, stream);
+        if (st != SC_OK) return fail(st);
+    }
+    std::vector<int32_t> seg_off, first_j;      // must outlive the async copies
+    if (t.chunk_c > 0) {
+        // segment table of the chunked form: for every (row, chunk) the entries whose input
+        // channel lies in the chunk, contiguous because rows are sorted by column; segments
+        // are padded with zero weights to an even length (to whole 8-entry groups for the
+        // symmetric kernel).  Counted on the host, filled by a device pass.
+        const int D = p->L.D, nch = g.nchunks, RS = p->L.R * p->L.S;
+        const int pad = t.pipeline == 2 ? 8 : 2;     // the symmetric kernel reads whole 8-entry groups
+        seg_off.assign((size_t)D * nch + 1, 0);
+        first_j.assign((size_t)D * nch, 0);
+        int64_t total = 0;
+        for (int d = 0; d < D; ++d) {
+            int j = 0;
+            for (int ch = 0; ch < nch; ++ch) {
+                seg_off[(size_t)d * nch + ch] = (int32_t)total;
+                first_j[(size_t)d * nch + ch] = j;
+                int cnt_ = 0;
+                // (ragged: the fillers, which sit behind the row's own entries, are left out)
+                const int jend = t.ragged ? p->h_len[d] : p->n;
+                while (j < jend && ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) / RS) / g.CC == ch) { ++j; ++cnt_; }
+                total += (cnt_ + pad - 1) / pad * pad;
             }
-            seg_off[(size_t)D * nch] = (int32_t)total;
-            if (total + 16 >= (1ll << 28)) return SC_ERR_RANGE;
-            if (p->d_wlc) { (void)hipFree(p->d_wlc); p->d_wlc = nullptr; }
-            if (p->d_seg_off) { (void)hipFree(p->d_seg_off); p->d_seg_off = nullptr; }
-            if (p->d_first_j) { (void)hipFree(p->d_first_j); p->d_first_j = nullptr; }
-            hipError_t e;
-            if ((e = hipMalloc((void**)&p->d_wlc, (size_t)(total + 16) * 8)) != hipSuccess) return hip_status(e);
-            if ((e = hipMalloc((void**)&p->d_seg_off, seg_off.size() * 4)) != hipSuccess) return hip_status(e);
-            if ((e = hipMalloc((void**)&p->d_first_j, std::max<size_t>(first_j.size(), 1) * 4)) != hipSuccess) return hip_status(e);
-            if ((e = hipMemcpyAsync(p->d_seg_off, seg_off.data(), seg_off.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_status(e);
-            if (!first_j.empty() && (e = hipMemcpyAsync(p->d_first_j, first_j.data(), first_j.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_status(e);
-            if ((e = hipMemsetAsync(p->d_wlc, 0, (size_t)(total + 16) * 8, stream)) != hipSuccess) return hip_status(e);
-            st = expand_weights_chunked(*p, g, total, stream);
-            if (st != SC_OK) return st;
-            // seg_off / first_j are read by the async copies until the synchronize below
-            if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
         }
-        if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
+        seg_off[(size_t)D * nch] = (int32_t)total;
+        if (total + 16 >= (1ll << 28)) return fail(SC_ERR_RANGE);
+        if ((e = hipMalloc((void**)&wlc, (size_t)(total + 16) * 8)) != hipSuccess) return fail(hip_status(e));
+        if ((e = hipMalloc((void**)&seg, seg_off.size() * 4)) != hipSuccess) return fail(hip_status(e));
+        if ((e = hipMalloc((void**)&fj, std::max<size_t>(first_j.size(), 1) * 4)) != hipSuccess) return fail(hip_status(e));
+        if ((e = hipMemcpyAsync(seg, seg_off.data(), seg_off.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return fail(hip_status(e));
+        if (!first_j.empty() && (e = hipMemcpyAsync(fj, first_j.data(), first_j.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return fail(hip_status(e));
+        if ((e = hipMemsetAsync(wlc, 0, (size_t)(total + 16) * 8, stream)) != hipSuccess) return fail(hip_status(e));
+        st = expand_weights_chunked(*p, g, p->d_lam_slab_spare, seg, fj, wlc, stream);
+        if (st != SC_OK) return fail(st);
+    }
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(SC_ERR_HIP);
+    // ---- commit: nothing below can fail
+    std::swap(p->d_lam_slab, p->d_lam_slab_spare);
+    if (want_wl32) std::swap(p->d_wl32, p->d_wl32_spare);
+    if (t.chunk_c > 0) {
+        if (p->d_wlc) (void)hipFree(p->d_wlc);
+        if (p->d_seg_off) (void)hipFree(p->d_seg_off);
+        if (p->d_first_j) (void)hipFree(p->d_first_j);
+        p->d_wlc = wlc;
+        p->d_seg_off = seg;
+        p->d_first_j = fj;
     }
     p->tuning = t;
     p->geom = g;
@@ -1044,6 +1085,27 @@ sc_status_t sparse_conv_plan_candidate(const sparse_conv_plan_t* plan, int32_t i
     return SC_OK;
 }
 
+// Ring of scratch buffer pairs for the second round of the search: large enough that a pass over it
+// streams from HBM (more than twice the 256 MB last-level cache), whatever the size of one pair.
+static size_t autotune_ring_slots(size_t x_bytes, size_t y_bytes)
+{
+    const size_t target = (size_t)512 << 20;
+    return std::min<size_t>(1024, target / std::max<size_t>(x_bytes + y_bytes, 1) + 2);
+}
+
+sc_status_t sparse_conv_autotune_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes)
+{
+    if (!plan || !bytes) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    const Plan* p = reinterpret_cast<const Plan*>(plan);
+    const size_t x_bytes = (size_t)N * p->L.C * p->L.H * p->L.W * p->ex;
+    const size_t y_bytes = (size_t)N * p->L.D * p->P * p->Q * p->ey;
+    // every slot may be shifted by up to 255 bytes to copy the caller's alignment
+    const size_t x_slot = (x_bytes + 255 + 255) / 256 * 256, y_slot = (y_bytes + 255 + 255) / 256 * 256;
+    *bytes = (gather_workspace_bytes(*p, N) + 255) / 256 * 256 + 256 + autotune_ring_slots(x_bytes, y_bytes) * (x_slot + y_slot);
+    return SC_OK;
+}
+
 sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
                                       int32_t N, void* workspace_dev, size_t workspace_bytes, void* stream)
 {
@@ -1054,8 +1116,9 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
     std::vector<sc_tuning_t> cands;
     build_candidates(*p, &cands);
     if (cands.empty()) return SC_ERR_UNSUPPORTED;
-    if (workspace_bytes < gather_workspace_bytes(*p, N) || (gather_workspace_bytes(*p, N) && !workspace_dev))
-        return SC_ERR_WORKSPACE;
+    const size_t gather_ws = gather_workspace_bytes(*p, N);
+    if (workspace_bytes < gather_ws || (gather_ws && !workspace_dev)) return SC_ERR_WORKSPACE;
+    const sc_tuning_t entry = p->tuning;          // re-installed if the search fails
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return SC_ERR_HIP;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SC_ERR_HIP; }
@@ -1093,8 +1156,10 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
     // hold, while a caller that streams fresh activations pays DRAM, and the order of the candidates
     // can differ between the two.  The few fastest are therefore timed again, over a longer run
     // that rotates over a ring of scratch copies of x (and as many y buffers) larger than twice
-    // that cache, each at the caller's alignment; if the ring cannot be allocated, on the caller's
-    // pair.  The best of that round is kept.
+    // that cache, each at the caller's alignment.  The ring lies in the caller's workspace behind the
+    // part the launch shapes use when the workspace holds sparse_conv_autotune_workspace_size bytes,
+    // else it is allocated here for the duration of the call; if neither works the round runs on
+    // the caller's pair.  The best of that round is kept.
     float best = INFINITY;
     int best_i = -1;
     if (st == SC_OK && !timed.empty()) {
@@ -1124,9 +1189,24 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
         const size_t y_bytes = (size_t)N * p->L.D * p->P * p->Q * p->ey;
         const size_t x_mis = reinterpret_cast<uintptr_t>(x_dev) & 255, y_mis = reinterpret_cast<uintptr_t>(y_dev) & 255;
         const size_t x_slot = (x_bytes + x_mis + 255) / 256 * 256, y_slot = (y_bytes + y_mis + 255) / 256 * 256;
-        const size_t ring = std::min<size_t>(16, ((size_t)512 << 20) / (x_bytes + y_bytes) + 2);
+        size_t ring = autotune_ring_slots(x_bytes, y_bytes);
         unsigned char* pool = nullptr;
-        if (hipMalloc((void**)&pool, ring * (x_slot + y_slot)) != hipSuccess) { pool = nullptr; (void)hipGetLastError(); }
+        bool pool_owned = false;
+        {
+            // the caller's workspace first: behind the part the launch shapes use, from the next
+            // 256-byte boundary
+            const uintptr_t w0 = reinterpret_cast<uintptr_t>(workspace_dev);
+            const uintptr_t ring0 = (w0 + gather_ws + 255) / 256 * 256;
+            if (workspace_dev && ring0 + ring * (x_slot + y_slot) <= w0 + workspace_bytes)
+                pool = reinterpret_cast<unsigned char*>(ring0);
+        }
+        if (!pool) {
+            size_t free_b = 0, total_b = 0;
+            if (hipMemGetInfo(&free_b, &total_b) == hipSuccess)        // leave a quarter of what is free alone
+                ring = std::min(ring, std::max<size_t>(2, free_b / 4 * 3 / (x_slot + y_slot)));
+            if (hipMalloc((void**)&pool, ring * (x_slot + y_slot)) != hipSuccess) { pool = nullptr; (void)hipGetLastError(); }
+            pool_owned = pool != nullptr;
+        }
         for (size_t r = 0; pool && r < ring; ++r)
             if (hipMemcpyAsync(pool + r * x_slot + x_mis, x_dev, x_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) st = SC_ERR_HIP;
         for (size_t k = 0; k < finalists && st == SC_OK; ++k) {
@@ -1135,9 +1215,10 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
             if (st != SC_OK) break;
             st = sparse_conv_forward(plan, x_dev, y_dev, N, workspace_dev, workspace_bytes, stream);
             if (st != SC_OK) break;
-            const int reps = (int)std::min(200.0f, std::max(10.0f, 8.0f / std::max(timed[k].first, 1e-3f)));
+            int reps = (int)std::min(200.0f, std::max(10.0f, 8.0f / std::max(timed[k].first, 1e-3f)));
             float ms;
             if (pool) {
+                reps = (int)std::max<size_t>(reps, std::min<size_t>(ring, 400));   // at least once round the ring
                 if (hipEventRecord(e0, s) != hipSuccess) { st = SC_ERR_HIP; break; }
                 for (int r = 0; r < reps && st == SC_OK; ++r)
                     st = sparse_conv_forward(plan, pool + (r % ring) * x_slot + x_mis,
@@ -1154,7 +1235,7 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
             timed[k].first = ms;
             best = std::min(best, ms);
         }
-        if (pool) {
+        if (pool_owned) {
             (void)hipStreamSynchronize(s);
             (void)hipFree(pool);
         }
@@ -1168,10 +1249,16 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    if (st != SC_OK) return st;
-    if (best_i < 0) return SC_ERR_UNSUPPORTED;
+    if (st == SC_OK && best_i < 0) st = SC_ERR_UNSUPPORTED;
+    if (st == SC_OK) st = sparse_conv_plan_set_tuning(plan, &cands[best_i], stream);
+    if (st != SC_OK) {
+        // leave the plan as it was found
+        (void)hipStreamSynchronize(s);
+        (void)sparse_conv_plan_set_tuning(plan, &entry, stream);
+        return st;
+    }
     p->last_N = N;
-    return sparse_conv_plan_set_tuning(plan, &cands[best_i], stream);
+    return SC_OK;
 }
 
 }  // extern "C"

@@ -68,6 +68,8 @@ struct Plan {
     void* d_theta = nullptr;        // [D*n] f32 | f16 | i8, or ceil(D*n/2) bytes of packed 4-bit indices
     int32_t* d_lam = nullptr;       // [D*n] canonical offsets (elements into one padded sample)
     int32_t* d_lam_slab = nullptr;  // [D*n] byte offsets into the LDS slab of the current tuning
+    int32_t* d_lam_slab_spare = nullptr;  // the buffer the next tuning's offsets are built in
+    int2* d_wl32_spare = nullptr;   // likewise for d_wl32
     int2* d_wlc = nullptr;          // chunked form of that table: segments (row, chunk), even-padded
     int32_t* d_seg_off = nullptr;   // [D*nchunks + 1] start of every segment in d_wlc (entries)
     int32_t* d_first_j = nullptr;   // [D*nchunks] index within its row of a segment's first entry
@@ -82,7 +84,7 @@ struct Plan {
 // plan.hip
 sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom);
 sc_status_t launch_stretch(const Plan& p, int32_t* d_out, int nsh, int nsw, int s_h, int s_w,
-                           int chan_pitch, int sub_pitch, int row_pitch, int scale,
+                           int chan_pitch, int sub_pitch, int row_pitch, int scale, int chan_mod,
                            hipStream_t stream);
 int elem_size_x(sc_dtype_t dt);
 int elem_size_y(sc_dtype_t dt);
@@ -96,8 +98,9 @@ sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws
 // slab.hip
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 int slab_grid_size(const Plan& p, const SlabGeom& g, int N);
-sc_status_t expand_weights(const Plan& p, hipStream_t stream);
-sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream);
+sc_status_t expand_weights(const Plan& p, const int32_t* lam_slab, int2* wl32_out, hipStream_t stream);
+sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32_t* lam_slab, const int32_t* seg_off,
+                                   const int32_t* first_j, int2* wlc_out, hipStream_t stream);
 constexpr int kMaxRowsPerWave = 8;
 
 }  // namespace sc

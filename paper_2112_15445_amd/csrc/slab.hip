@@ -604,13 +604,16 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, unsig
 {
     static_assert(BYTES == 16 || BYTES == 4, "copy width");
     if constexpr (HAND) {
+        // (M0 carries the LDS address of the copy; the compiler reserves that register for its own
+        // use, so its value is put back before the statement ends)
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
+        uint32_t keep;
         if constexpr (BYTES == 16)
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
-                         : : "v"(lane_off), "s"(base), "s"(l) : "memory");
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "v"(lane_off), "s"(base), "s"(l) : "memory");
         else
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 nt"
-                         : : "v"(lane_off), "s"(base), "s"(l) : "memory");
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2 nt\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "v"(lane_off), "s"(base), "s"(l) : "memory");
     } else {
         if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 16, 0, 2);
         else __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)dst, 4, 0, 2);
@@ -621,12 +624,13 @@ __device__ __forceinline__ void dma16_ptr(const void* src, unsigned char* dst)
 {
     if constexpr (HAND) {
         const uint32_t l = (uint32_t)(uintptr_t)(lptr_t)dst;
+        uint32_t keep;
         if constexpr (BYTES == 16)
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
-                         : : "v"(src), "s"(l) : "memory");
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "v"(src), "s"(l) : "memory");
         else
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off nt"
-                         : : "v"(src), "s"(l) : "memory");
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off nt\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "v"(src), "s"(l) : "memory");
     } else {
         if constexpr (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 2);
         else __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 4, 0, 2);
@@ -937,15 +941,15 @@ expand_chunked_kernel(const void* __restrict__ theta, const int32_t* __restrict_
     out[(int64_t)seg_off[si] + k] = make_int2(weight_bits<DT>(load_weight<DT>(theta, i, l, nullptr)), lb);
 }
 
-sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, int64_t total_entries, hipStream_t stream)
+sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32_t* lam_slab, const int32_t* seg_off,
+                                   const int32_t* first_j, int2* wlc_out, hipStream_t stream)
 {
-    (void)total_entries;
     const int64_t cnt = (int64_t)p.L.D * p.n;
     if (cnt == 0) return SC_OK;
     const unsigned blocks = (unsigned)((cnt + 255) / 256);
 #define SC_EXPANDC(DT)                                                                             \
     hipLaunchKernelGGL(expand_chunked_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
-                       p.d_lam_slab, p.d_col, p.d_seg_off, p.d_first_j, p.d_wlc, p.L.D, p.n,       \
+                       lam_slab, p.d_col, seg_off, first_j, wlc_out, p.L.D, p.n,                   \
                        p.L.R * p.L.S, g.CC, g.nchunks, g.copies, p.ex, g.copy_bytes)
     switch (p.dtype) {
         case SC_F32: SC_EXPANDC(SC_F32); break;
@@ -1869,14 +1873,14 @@ int slab_grid_size(const Plan& p, const SlabGeom& g, int N)
     return N * g.tiles_p * g.tiles_q;
 }
 
-sc_status_t expand_weights(const Plan& p, hipStream_t stream)
+sc_status_t expand_weights(const Plan& p, const int32_t* lam_slab, int2* wl32_out, hipStream_t stream)
 {
     const int64_t cnt = (int64_t)p.L.D * p.np;
-    if (cnt == 0 || !p.d_wl32) return SC_OK;
+    if (cnt == 0 || !wl32_out) return SC_OK;
     const unsigned blocks = (unsigned)((cnt + 255) / 256);
 #define SC_EXPAND(DT)                                                                              \
     hipLaunchKernelGGL(expand_weights_kernel<DT>, dim3(blocks), dim3(256), 0, stream, p.d_theta,   \
-                       p.d_lam_slab, p.d_wl32, p.L.D, p.n, p.np)
+                       lam_slab, wl32_out, p.L.D, p.n, p.np)
     switch (p.dtype) {
         case SC_F32: SC_EXPAND(SC_F32); break;
         case SC_F16: SC_EXPAND(SC_F16); break;

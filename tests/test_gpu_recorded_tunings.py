@@ -1,0 +1,39 @@
+"""Every layer of every workload configuration at FULL batch, in the launch shape recorded for it
+(paper_2112_15445_amd/tunings/mi355x.json: what the autotuner installed on an MI355X and the
+per-layer report timed), against the CPU oracle: samples 0..15 and the last one, element by element.
+
+The shapes are installed with sparse_conv_plan_set_tuning (no autotune here), so that the result
+the benchmark figures stand for is the one that is checked."""
+import json
+import os
+
+import pytest
+
+from paper_2112_15445_amd import binding as B
+from paper_2112_15445_amd import workloads as wl
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+_PATH = os.path.join(os.path.dirname(os.path.abspath(B.__file__)), "tunings", "mi355x.json")
+ROWS = json.load(open(_PATH))
+_LAYERS = {(l.name, l.dtype): l for c in wl.CONFIGS for l in wl.CONFIGS[c]()}
+
+
+def test_every_workload_layer_has_a_recorded_tuning():
+    assert {(r["layer"], r["dtype"]) for r in ROWS} == set(_LAYERS)
+
+
+@pytest.mark.parametrize("row", ROWS, ids=[f"cfg{r['config']}-{r['layer']}-{r['dtype']}" for r in ROWS])
+def test_recorded_tuning_at_full_batch(row):
+    l = _LAYERS[(row["layer"], row["dtype"])]
+    print("case recorded tuning", l.name, l.dtype, "N", l.N, row["tuning"], flush=True)
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    plan.set_tuning(B.sc_tuning_t(), **row["tuning"])
+    got = {k: v for k, v in plan.get_tuning().as_dict().items() if v}
+    assert got == row["tuning"], (got, row["tuning"])        # installed exactly as recorded
+    res = G.full_batch_parity(l, data, plan)
+    plan.destroy()
+    assert res["ok"], res
