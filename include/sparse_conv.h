@@ -226,6 +226,22 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
                                 int32_t N, void* workspace_dev, size_t workspace_bytes,
                                 void* stream);
 
+/* For callers that cannot allocate or pass a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same result as sparse_conv_forward, but the scratch
+ * memory of the launch shape (the padded copy of the input that SC_VARIANT_GATHER makes when the
+ * layer has padding) is a static device array of SC_STATIC_WORKSPACE_BYTES inside the library, one
+ * per GPU, held until the process ends.  Calls no hipMalloc / hipFree and no allocating library
+ * routine; asynchronous on `stream`.  x_dev / y_dev as for sparse_conv_forward.
+ * Every call on one GPU shares that GPU's array (each call rewrites all of the part it uses, so a
+ * smaller call after a larger one is fine): calls that overlap in time on one GPU -- different
+ * streams or threads -- race, serialise them.
+ * Errors: SC_ERR_NULL, SC_ERR_SHAPE (N <= 0), SC_ERR_WORKSPACE (this N needs more than
+ * SC_STATIC_WORKSPACE_BYTES: use sparse_conv_forward with a workspace), SC_ERR_UNSUPPORTED,
+ * SC_ERR_HIP. */
+#define SC_STATIC_WORKSPACE_BYTES (32u << 20)
+sc_status_t sparse_conv_forward_static(const sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
+                                       int32_t N, void* stream);
+
 /* Per-layer launch-shape search: the gfx950 counterpart of the paper's empirical per-layer tuning
  * of the sub-batch size sb_S and with it of the number of thread blocks (eq. N_B = b_S * D / sb_S and
  * the table "Impact of the number of thread blocks" in the GPU results).  Times every candidate

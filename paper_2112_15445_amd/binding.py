@@ -23,13 +23,14 @@ STATUS_NAMES = {0: "SC_OK", 1: "SC_ERR_NULL", 2: "SC_ERR_SHAPE", 3: "SC_ERR_CSR"
 SC_F32, SC_F16, SC_I8, SC_CB4_I8, SC_CB4_F16 = 0, 1, 2, 3, 4
 DTYPES = {"f32": SC_F32, "f16": SC_F16, "i8": SC_I8, "cb4": SC_CB4_I8, "cb4h": SC_CB4_F16}
 SC_VARIANT_AUTO, SC_VARIANT_GATHER, SC_VARIANT_SLAB = 0, 1, 2
+SC_STATIC_WORKSPACE_BYTES = 32 << 20
 
 # every symbol include/sparse_conv.h declares
 EXPORTS = [
     "sparse_conv_plan_create_csr", "sparse_conv_plan_create_ell", "sparse_conv_plan_destroy",
     "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning",
     "sparse_conv_plan_get_tuning", "sparse_conv_workspace_size", "sparse_conv_workspace_size_max",
-    "sparse_conv_forward", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size",
+    "sparse_conv_forward", "sparse_conv_forward_static", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size",
     "sparse_conv_plan_num_candidates",
     "sparse_conv_plan_candidate", "sparse_conv_quantize_pow2", "sparse_conv_status_string",
 ]
@@ -96,6 +97,7 @@ def lib() -> ctypes.CDLL:
     L.sparse_conv_workspace_size.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_workspace_size_max.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_forward.argtypes = [vp, vp, vp, i32, vp, sz, vp]
+    L.sparse_conv_forward_static.argtypes = [vp, vp, vp, i32, vp]
     L.sparse_conv_plan_autotune.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.sparse_conv_autotune_workspace_size.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_plan_num_candidates.argtypes = [vp, P(i32)]
@@ -249,6 +251,11 @@ class Plan:
         _check(lib().sparse_conv_forward(self._h, ctypes.c_void_p(x_ptr), ctypes.c_void_p(y_ptr), N,
                                          ctypes.c_void_p(ws_ptr), ws_bytes, ctypes.c_void_p(stream)),
                "sparse_conv_forward")
+
+    def forward_static(self, x_ptr: int, y_ptr: int, N: int, stream: int = 0):
+        _check(lib().sparse_conv_forward_static(self._h, ctypes.c_void_p(x_ptr), ctypes.c_void_p(y_ptr), N,
+                                                ctypes.c_void_p(stream)),
+               "sparse_conv_forward_static")
 
     def autotune(self, x_ptr: int, y_ptr: int, N: int, ws_ptr: int = 0, ws_bytes: int = 0,
                  stream: int = 0):

@@ -9,8 +9,16 @@
 // sample_base + p*s_h*Wp + q*s_w + lambda.  The input it reads is the physically zero-padded
 // tensor: when the layer has padding, a small pre-pass writes it into the caller's workspace first
 // (the paper feeds its kernel pre-padded inputs).
+#include <mutex>
+
 #include "sc_device.h"
 #include "sc_internal.h"
+
+// Scratch memory of sparse_conv_forward_static: the padded copy of the input that this variant
+// materialises when the layer has padding.  One array per GPU (the code object is loaded on each),
+// held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress;
+// the address kernels and copies use is the one that call returns.
+static __device__ __align__(256) unsigned char scratch[SC_STATIC_WORKSPACE_BYTES];
 
 namespace sc {
 
@@ -185,3 +193,47 @@ sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws
 }
 
 }  // namespace sc
+
+// ------------------------------------------------------------------------------------------------
+// Entry point that allocates nothing and takes no workspace: the padded input copy lives in the
+// file-scope scratch array above.
+// ------------------------------------------------------------------------------------------------
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on every GPU seen so far
+
+// Address of this GPU's copy of the scratch array, resolved once per device with that device current.
+sc_status_t scratch_address(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SC_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SC_OK;
+}
+}  // namespace
+
+extern "C" sc_status_t sparse_conv_forward_static(const sparse_conv_plan_t* plan, const void* x_dev,
+                                                  void* y_dev, int32_t N, void* stream)
+{
+    if (!plan || !x_dev || !y_dev) return SC_ERR_NULL;
+    if (N <= 0) return SC_ERR_SHAPE;
+    const sc::Plan* p = reinterpret_cast<const sc::Plan*>(plan);
+    if (p->tuning.variant == SC_VARIANT_SLAB) return sc::launch_slab(*p, x_dev, y_dev, N, (hipStream_t)stream);
+    const size_t need = sc::gather_workspace_bytes(*p, N);
+    if (need > (size_t)SC_STATIC_WORKSPACE_BYTES) return SC_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need) {
+        const sc_status_t st = scratch_address(&ws);
+        if (st != SC_OK) return st;
+    }
+    // every byte of the padded copy (zeros included) is rewritten by the pad pass of this call, so
+    // what an earlier call left in the array never shows
+    return sc::launch_gather(*p, x_dev, y_dev, N, ws, need, (hipStream_t)stream);
+}
