@@ -78,9 +78,22 @@ enum {
                               positions (flat over sample, row, column); (theta, lambda) row in LDS;
                               input gathered from global memory (a padded copy in the workspace
                               when pad > 0) */
-    SC_VARIANT_SLAB = 2    /* one workgroup = one sample x an output tile x all output channels;
+    SC_VARIANT_SLAB = 2,   /* one workgroup = one sample x an output tile x all output channels;
                               the input tile (all C channels, halo and zero padding included) is
                               staged once in LDS and every row of (theta, lambda) is streamed over it */
+    SC_VARIANT_DENSE = 3   /* the densified tile on the matrix cores, for layers that are not sparse
+                              enough for the gather kernels to win (the per-layer choice of the
+                              paper's "Main scheme", whose dense side is here a kernel of the
+                              library): the stored entries are scattered once into a dense weight
+                              array in MFMA operand order, the input tile is staged in LDS
+                              channel-minor, and 16 x 16 blocks of (output channel, position) are
+                              accumulated by v_mfma_f32_16x16x32_f16 / v_mfma_i32_16x16x64_i8.
+                              SC_F16, SC_CB4_F16, SC_I8, SC_CB4_I8 only; not for tables that store a
+                              column twice in one row.  Integer results are exact.  Fields: tile_p =
+                              output rows per workgroup, sub_batch = samples per workgroup (whole
+                              planes only, up to 16), chunk_c = input channels per LDS chunk (a
+                              multiple of 32 for 16-bit, 64 for 8-bit activations), tile_d = output
+                              channels per workgroup (16, 32, 64 or 128), wg_per_cu; 0 = heuristic */
 };
 
 /* Launch shape of sparse_conv_forward; the analogue of the paper's per-layer choice of the

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "SC_OK", 1: "SC_ERR_NULL", 2: "SC_ERR_SHAPE", 3: "SC_ERR_CSR"
                 8: "SC_ERR_HIP"}
 SC_F32, SC_F16, SC_I8, SC_CB4_I8, SC_CB4_F16 = 0, 1, 2, 3, 4
 DTYPES = {"f32": SC_F32, "f16": SC_F16, "i8": SC_I8, "cb4": SC_CB4_I8, "cb4h": SC_CB4_F16}
-SC_VARIANT_AUTO, SC_VARIANT_GATHER, SC_VARIANT_SLAB = 0, 1, 2
+SC_VARIANT_AUTO, SC_VARIANT_GATHER, SC_VARIANT_SLAB, SC_VARIANT_DENSE = 0, 1, 2, 3
 SC_STATIC_WORKSPACE_BYTES = 32 << 20
 
 # every symbol include/sparse_conv.h declares

@@ -228,11 +228,64 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     return true;
 }
 
-sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom)
+// DENSE variant: fill the fields left 0 and derive the geometry.
+static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out, MfmaGeom* mgeom)
+{
+    const sc_layer_t& L = p.L;
+    if (p.dtype == SC_F32 || p.has_dup || p.n == 0) return SC_ERR_UNSUPPORTED;
+    if (t.wg_per_cu == 0) t.wg_per_cu = 2;
+    if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
+    if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q) return SC_ERR_UNSUPPORTED;
+    const int budget = kMaxLdsBytes / t.wg_per_cu;
+    const int CB = mfma_chan_block(p.dtype);
+    int DB = t.tile_d;
+    if (DB == 0) DB = L.D > 64 ? 128 : (L.D > 32 ? 64 : (L.D > 16 ? 32 : 16));
+    const int maxpos = (DB == 128 ? 2 : 4) * 4 * 16;          // positions the four waves can hold
+    int TP = t.tile_p, NS = t.sub_batch;
+    const bool fixed_tile = TP != 0 || NS != 0;
+    if (TP == 0 && NS == 0) {
+        if (p.P * p.Q <= maxpos) { TP = p.P; NS = std::max(1, std::min(16, maxpos / (p.P * p.Q))); }
+        else { TP = std::max(1, maxpos / p.Q); NS = 1; }
+    }
+    if (TP == 0) TP = p.P;
+    if (NS == 0) NS = 1;
+    MfmaGeom g{};
+    for (;;) {
+        bool ok = false;
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, budget, &g);
+        else
+            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, budget, &g);
+        if (ok) break;
+        if (fixed_tile) return SC_ERR_UNSUPPORTED;
+        // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
+        if (NS > 1) NS /= 2;
+        else if (TP > 1) TP = (TP + 1) / 2;
+        else return SC_ERR_UNSUPPORTED;
+    }
+    sc_tuning_t r{};
+    r.variant = SC_VARIANT_DENSE;
+    r.wg_threads = 256;
+    r.tile_p = g.TP;
+    r.sub_batch = g.NS;
+    r.chunk_c = g.CC;
+    r.tile_d = g.DB;
+    r.wg_per_cu = t.wg_per_cu;
+    *out = r;
+    *mgeom = g;
+    return SC_OK;
+}
+
+sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom, MfmaGeom* mgeom)
 {
     sc_tuning_t t = in;
     const sc_layer_t& L = p.L;
-    if (t.variant < SC_VARIANT_AUTO || t.variant > SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
+    if (t.variant < SC_VARIANT_AUTO || t.variant > SC_VARIANT_DENSE) return SC_ERR_UNSUPPORTED;
+    if (t.variant == SC_VARIANT_DENSE) {
+        *geom = SlabGeom{};
+        return resolve_dense(p, t, out, mgeom);
+    }
+    *mgeom = MfmaGeom{};
     if (t.wg_threads == 0) t.wg_threads = 256;
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
     if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
@@ -399,6 +452,10 @@ static void free_device(Plan* p)
     p->d_seg_off = p->d_first_j = nullptr;
     if (p->d_scales) (void)hipFree(p->d_scales);
     if (p->d_codebook) (void)hipFree(p->d_codebook);
+    if (p->d_wfrag) (void)hipFree(p->d_wfrag);
+    if (p->d_len) (void)hipFree(p->d_len);
+    p->d_wfrag = nullptr;
+    p->d_len = nullptr;
     p->d_col = p->d_lam = p->d_lam_slab = nullptr;
     p->d_theta = nullptr;
     p->d_scales = nullptr;
@@ -413,11 +470,22 @@ static sc_status_t hip_status(hipError_t e)
 
 // Build the tables of tuning `t` beside the ones in use and swap them in only when every step has
 // succeeded: on any error the plan keeps its previous tuning, geometry and tables untouched.
-static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom& g, hipStream_t stream)
+static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom& g, const MfmaGeom& mg, hipStream_t stream)
 {
+    if (t.variant == SC_VARIANT_DENSE && !p->d_wfrag) {
+        // dense weights in MFMA operand order: built on first use, the same for every tile shape
+        hipError_t e;
+        unsigned char* w = nullptr;
+        if ((e = hipMalloc((void**)&w, mfma_weight_bytes(*p))) != hipSuccess) return hip_status(e);
+        sc_status_t st = mfma_densify(*p, w, stream);
+        if (st == SC_OK && hipStreamSynchronize(stream) != hipSuccess) st = SC_ERR_HIP;
+        if (st != SC_OK) { (void)hipFree(w); return st; }
+        p->d_wfrag = w;
+    }
     if (t.variant != SC_VARIANT_SLAB) {
         p->tuning = t;
         p->geom = g;
+        p->mg = mg;
         return SC_OK;
     }
     const size_t cnt = (size_t)p->L.D * p->n;
@@ -497,6 +565,7 @@ static sc_status_t install_tuning(Plan* p, const sc_tuning_t& t, const SlabGeom&
     }
     p->tuning = t;
     p->geom = g;
+    p->mg = mg;
     return SC_OK;
 }
 
@@ -514,12 +583,18 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     // weights by scalar loads where the layer allows it, otherwise whatever the heuristic resolves
     sc_tuning_t t{};
     SlabGeom g{};
+    MfmaGeom mg{};
     sc_tuning_t want{};
     want.wg_threads = 1024;
     want.wsrc = is_codebook(p->dtype) ? 0 : 1;
-    sc_status_t st = resolve_tuning(*p, want, &t, &g);
-    if (st != SC_OK) st = resolve_tuning(*p, sc_tuning_t{}, &t, &g);
+    sc_status_t st = resolve_tuning(*p, want, &t, &g, &mg);
+    if (st != SC_OK) st = resolve_tuning(*p, sc_tuning_t{}, &t, &g, &mg);
     if (st != SC_OK) return st;
+    // a column stored twice in one row: legal (the entries add up), but such a table has no exact
+    // dense image in the weights' own width, so the DENSE variant is not offered for it
+    for (int d = 0; d < p->L.D && !p->has_dup; ++d)
+        for (int j = 1; j < p->h_len[d]; ++j)
+            if ((p->h_col[(size_t)d * p->n + j] & 0x7fffffff) == (p->h_col[(size_t)d * p->n + j - 1] & 0x7fffffff)) { p->has_dup = true; break; }
 
     std::vector<uint8_t> packed;
     const uint8_t* theta_src = tab.val.data();
@@ -549,6 +624,9 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
         if ((e = hipMemcpyAsync(p->d_theta, theta_src, theta_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess)
             return hip_status(e);
     }
+    if ((e = hipMalloc((void**)&p->d_len, std::max<size_t>(p->h_len.size(), 1) * 4)) != hipSuccess) return hip_status(e);
+    if (!p->h_len.empty() && (e = hipMemcpyAsync(p->d_len, p->h_len.data(), p->h_len.size() * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
+        return hip_status(e);
     if (scales) {
         if ((e = hipMalloc((void**)&p->d_scales, (size_t)p->L.D * 4)) != hipSuccess) return hip_status(e);
         if ((e = hipMemcpyAsync(p->d_scales, scales, (size_t)p->L.D * 4, hipMemcpyHostToDevice, stream)) != hipSuccess)
@@ -565,7 +643,7 @@ static sc_status_t finish_create(Plan* p, HostTable& tab, const float* scales, c
     if (st != SC_OK) return st;
     // the host staging buffers must outlive the async copies
     if (hipStreamSynchronize(stream) != hipSuccess) return SC_ERR_HIP;
-    return install_tuning(p, t, g, stream);
+    return install_tuning(p, t, g, mg, stream);
 }
 
 }  // namespace sc
@@ -734,6 +812,9 @@ sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t
     if (p->tuning.variant == SC_VARIANT_SLAB) {
         info->lds_bytes = p->geom.lds_bytes;
         info->grid_size = p->last_N ? slab_grid_size(*p, p->geom, p->last_N) : 0;
+    } else if (p->tuning.variant == SC_VARIANT_DENSE) {
+        info->lds_bytes = p->mg.lds_bytes;
+        info->grid_size = p->last_N ? mfma_grid_size(*p, p->mg, p->last_N) : 0;
     } else {
         info->lds_bytes = 1024 * 8;
         info->grid_size = p->last_N ? gather_grid_size(*p, p->tuning, p->last_N) : 0;
@@ -759,9 +840,10 @@ sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tunin
     Plan* p = reinterpret_cast<Plan*>(plan);
     sc_tuning_t t{};
     SlabGeom g{};
-    sc_status_t st = resolve_tuning(*p, *tuning, &t, &g);
+    MfmaGeom mg{};
+    sc_status_t st = resolve_tuning(*p, *tuning, &t, &g, &mg);
     if (st != SC_OK) return st;
-    return install_tuning(p, t, g, (hipStream_t)stream);
+    return install_tuning(p, t, g, mg, (hipStream_t)stream);
 }
 
 sc_status_t sparse_conv_plan_get_tuning(const sparse_conv_plan_t* plan, sc_tuning_t* tuning)
@@ -795,6 +877,7 @@ sc_status_t sparse_conv_forward(const sparse_conv_plan_t* plan, const void* x_de
     if (N <= 0) return SC_ERR_SHAPE;
     const Plan* p = reinterpret_cast<const Plan*>(plan);
     if (p->tuning.variant == SC_VARIANT_SLAB) return launch_slab(*p, x_dev, y_dev, N, (hipStream_t)stream);
+    if (p->tuning.variant == SC_VARIANT_DENSE) return launch_mfma(*p, x_dev, y_dev, N, (hipStream_t)stream);
     return launch_gather(*p, x_dev, y_dev, N, workspace_dev, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -805,7 +888,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     auto push = [&](sc_tuning_t t) {
         sc_tuning_t r{};
         SlabGeom g{};
-        if (resolve_tuning(p, t, &r, &g) != SC_OK) return;
+        MfmaGeom mg{};
+        if (resolve_tuning(p, t, &r, &g, &mg) != SC_OK) return;
         for (const sc_tuning_t& o : *out)
             if (std::memcmp(&o, &r, sizeof(r)) == 0) return;
         out->push_back(r);
@@ -817,6 +901,20 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             t.sub_batch = sb;
             t.split_n = ns;
             push(t);
+        }
+    }
+    // the densified tile on the matrix cores (16- and 8-bit activations): output-channel block x
+    // tile of positions (rows of one sample, or whole planes of several) x workgroups per CU
+    if (p.dtype != SC_F32 && !p.has_dup && p.n > 0) {
+        for (int db : {32, 64, 128}) for (int wpc : {1, 2, 3, 4}) {
+            { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; push(t); }
+            for (int tp : {1, 2, 4, 7, 8, 14}) {
+                if (tp >= p.P) continue;
+                sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; t.tile_p = tp; push(t);
+            }
+            for (int ns : {1, 2, 4, 8, 16}) {
+                sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; t.tile_p = p.P; t.sub_batch = ns; push(t);
+            }
         }
     }
     const bool pw = is_pointwise(p.L);

@@ -53,6 +53,20 @@ struct SlabGeom {
     int rpw;                   // output channels per consumer wave, ceil(DTW / consumers)
 };
 
+// Geometry of the DENSE (matrix-core) variant for one (plan, tuning) pair.
+struct MfmaGeom {
+    int TP, NS;            // output rows and samples per workgroup (NS > 1 only with whole planes)
+    int tiles_p;           // row tiles per sample
+    int Hs, Ws;            // staged input rows / columns of one sample (halo and padding included)
+    int npos_s, npos;      // staged positions and output positions per workgroup
+    int NCB;               // channel blocks of 32 (f16) / 64 (i8) input channels, ceil(C / block)
+    int CC, nchunks;       // input channels per LDS chunk (a multiple of the block), chunks
+    int pitch;             // bytes per staged position
+    int DB, ndb;           // output channels per workgroup, blocks of them
+    int WM, MW, NW;        // waves along the output channels; 16-row / 16-column blocks per wave
+    int lds_bytes;
+};
+
 struct Plan {
     sc_layer_t L;
     sc_dtype_t dtype;
@@ -76,13 +90,17 @@ struct Plan {
     int2* d_wl32 = nullptr;         // [D*np] {theta widened to 32 bits, slab byte offset} for scalar loads
     float* d_scales = nullptr;      // [D]
     void* d_codebook = nullptr;     // [16] i8 or f16 centroids
+    unsigned char* d_wfrag = nullptr;  // dense weights in MFMA operand order (DENSE variant), built on first use
+    int32_t* d_len = nullptr;       // [D] stored entries of every row before unification (device copy of h_len)
+    bool has_dup = false;           // some row stores a column twice (such a table cannot be densified exactly)
     sc_tuning_t tuning{};
     SlabGeom geom{};
+    MfmaGeom mg{};
     int last_N = 0;
 };
 
 // plan.hip
-sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom);
+sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* out, SlabGeom* geom, MfmaGeom* mgeom);
 sc_status_t launch_stretch(const Plan& p, int32_t* d_out, int nsh, int nsw, int s_h, int s_w,
                            int chan_pitch, int sub_pitch, int row_pitch, int scale, int chan_mod,
                            hipStream_t stream);
@@ -102,5 +120,13 @@ sc_status_t expand_weights(const Plan& p, const int32_t* lam_slab, int2* wl32_ou
 sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32_t* lam_slab, const int32_t* seg_off,
                                    const int32_t* first_j, int2* wlc_out, hipStream_t stream);
 constexpr int kMaxRowsPerWave = 8;
+
+// dense_mfma.hip
+int mfma_chan_block(sc_dtype_t dt);
+size_t mfma_weight_bytes(const Plan& p);
+sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream);
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int lds_budget, MfmaGeom* out);
+int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N);
+sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 
 }  // namespace sc

@@ -56,7 +56,12 @@ def _both_variants(plan):
                                                 "tile_q": 64, "tile_d": 5, "pack": 2}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 1024}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
-                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96})):
+                           (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96}),
+                           (B.SC_VARIANT_DENSE, {}),
+                           (B.SC_VARIANT_DENSE, {"tile_d": 16, "tile_p": 1, "wg_per_cu": 4}),
+                           (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2, "chunk_c": 64}),
+                           (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 2}),
+                           (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 3, "wg_per_cu": 1})):
         try:
             plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
         except B.SparseConvError as e:
@@ -815,3 +820,57 @@ def test_samples_interleaved_in_the_lds_word(dtype):
             assert t["pack"] == 3 and t["chunk_c"] == extra["chunk_c"]
             print("case", l.name, dtype, t, flush=True)
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8", "cb4", "cb4h"])
+def test_dense_variant_on_the_matrix_cores(dtype):
+    """The densified tile (MFMA) against the oracle: several channel blocks and LDS chunks, output
+    channels that do not fill a 16-row block, batches that do not fill a sample group, strides,
+    paddings, rectangular filters; integer dtypes bit-exact."""
+    shapes = [("deep_3x3", 150, 70, 9, 11, 3, 3, 1, 1, 1, 1, 5, 0.8),
+              ("deep_pointwise", 200, 37, 7, 7, 1, 1, 1, 1, 0, 0, 7, 0.7),
+              ("stride2", 70, 20, 13, 12, 3, 3, 2, 2, 1, 1, 3, 0.5),
+              ("rect_pad", 40, 130, 6, 17, 2, 3, 1, 2, 0, 2, 2, 0.6),
+              ("tiny_plane", 96, 48, 2, 2, 3, 3, 1, 1, 1, 1, 19, 0.9)]
+    for name, C, D, H, W, R, S, sh, sw, ph, pw, N, sp in shapes:
+        l = wl.Layer(name, C, D, H, W, R, S, sh, sw, ph, pw, N=N, sparsity=sp, dtype=dtype, seed=777)
+        data = wl.prepare(l)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        ran = 0
+        for extra in ({}, {"tile_d": 16}, {"tile_d": 32, "tile_p": 1}, {"tile_d": 64, "tile_p": 2, "chunk_c": 64},
+                      {"tile_d": 128, "wg_per_cu": 1}, {"tile_d": 64, "tile_p": 1000, "sub_batch": 4},
+                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
+            try:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, **extra)
+            except B.SparseConvError as e:
+                assert e.status == 4
+                continue
+            t = plan.get_tuning()
+            assert t.variant == B.SC_VARIANT_DENSE and t.wg_threads == 256
+            print("case dense", name, dtype, t.as_dict(), flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense {extra}")
+            ran += 1
+        assert ran >= 3, (name, ran)
+        plan.destroy()
+
+
+def test_dense_variant_is_refused_where_it_does_not_apply():
+    l = wl.Layer("refuse", 8, 4, 6, 6, N=1, sparsity=0.5, dtype="f32", seed=5)
+    data = wl.prepare(l)
+    plan = G.make_plan(l, data)
+    with pytest.raises(B.SparseConvError) as e:
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE)       # 32-bit activations
+    assert e.value.status == 4
+    plan.destroy()
+    # a column stored twice in one row adds up in the gather kernels; it has no exact dense image
+    l = l.replace(dtype="i8")
+    data = wl.prepare(l)
+    rp, ci, va = data["rowptr"], data["colidx"].copy(), data["values"]
+    ci[rp[1] + 1] = ci[rp[1]]
+    plan = B.Plan.create_csr(G.layer_desc(l), B.DTYPES["i8"], rp, ci, va, data["scales"], None)
+    before = plan.get_tuning().as_dict()
+    with pytest.raises(B.SparseConvError) as e:
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE)
+    assert e.value.status == 4 and plan.get_tuning().as_dict() == before
+    plan.destroy()
