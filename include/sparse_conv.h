@@ -93,7 +93,7 @@ enum {
                               output rows per workgroup, sub_batch = samples per workgroup (whole
                               planes only, up to 16), chunk_c = input channels per LDS chunk (a
                               multiple of 32 for 16-bit, 64 for 8-bit activations), tile_d = output
-                              channels per workgroup (16, 32, 64 or 128), wg_per_cu; 0 = heuristic */
+                              channels per workgroup (16, 32, 64 or 128), waves_m, wg_per_cu; 0 = heuristic */
 };
 
 /* Launch shape of sparse_conv_forward; the analogue of the paper's per-layer choice of the
@@ -154,6 +154,9 @@ typedef struct {
                            LDS word (128 bits; 32 bits for i8) holds the same element of each, so every
                            offset is a whole word on any layer shape -- one LDS read per stored weight
                            feeds that many samples; at most 8 / word-size positions per lane */
+    int32_t waves_m;    /* DENSE: how many of the workgroup's four waves lie along the output channels
+                           (1, 2 or 4; the others along the positions).  A wave then owns tile_d / waves_m
+                           output channels (16, 32 or 64) and up to 128 positions.  0 = heuristic */
 } sc_tuning_t;
 
 typedef struct {

@@ -25,23 +25,9 @@
 //     CU overlap the staging of one with the multiplication of another.
 // Integer results are exact (bit-identical to the gather kernels); f16 results differ from them in
 // summation order only.
-#include <mutex>
-#include <type_traits>
-
-#include "sc_device.h"
-#include "sc_internal.h"
+#include "dense_mfma_kernel.h"
 
 namespace sc {
-
-typedef _Float16 half8v __attribute__((ext_vector_type(8)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef int int4v_ __attribute__((ext_vector_type(4)));
-typedef unsigned uint4w __attribute__((ext_vector_type(4)));
-
-template <sc_dtype_t DT> constexpr bool kIntActs = DT == SC_I8 || DT == SC_CB4_I8;
-// input channels contracted by one MFMA, and held by one lane (16 bytes)
-template <sc_dtype_t DT> constexpr int kChanBlock = kIntActs<DT> ? 64 : 32;
-template <sc_dtype_t DT> constexpr int kChanVec = kIntActs<DT> ? 16 : 8;
 
 int mfma_chan_block(sc_dtype_t dt) { return (dt == SC_I8 || dt == SC_CB4_I8) ? 64 : 32; }
 
@@ -117,7 +103,7 @@ sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream)
 // ------------------------------------------------------------------------------------------------
 // Geometry of one (plan, tuning) pair, derived on the host.
 // ------------------------------------------------------------------------------------------------
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int lds_budget, MfmaGeom* out)
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out)
 {
     const sc_layer_t& L = p.L;
     MfmaGeom g{};
@@ -137,275 +123,30 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int lds_budget
     g.pitch = g.CC * p.ex + 16;                   // bytes per staged position: a multiple of 16, odd in units of 16
     g.DB = DB;
     g.ndb = (L.D + DB - 1) / DB;
-    g.WM = DB == 128 ? 2 : 1;
-    g.MW = DB / (16 * g.WM);
-    const int WN = 4 / g.WM;
+    // the four waves: WM along the output channels (MW 16-row blocks each), 4 / WM along the
+    // positions (NW 16-column blocks each, at most 8)
+    if (WM != 1 && WM != 2 && WM != 4) return false;
+    g.WM = WM;
+    if (DB % (16 * WM)) return false;
+    g.MW = DB / (16 * WM);
+    if (g.MW != 1 && g.MW != 2 && g.MW != 4) return false;
+    const int WN = 4 / WM;
     const int NB = (g.npos + 15) / 16;
     const int nw = (NB + WN - 1) / WN;
-    g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : 4);
-    if (nw > 4) return false;
-    const int64_t lds = (int64_t)g.npos_s * g.pitch + (int64_t)g.npos_s * 4;      // the tile and its source-offset table
+    if (nw > 8) return false;
+    g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : (nw <= 4 ? 4 : 8));
+    if (g.NW == 8 && g.MW == 4) return false;     // 32 accumulator blocks per wave: not instantiated
+    const int64_t lds = (int64_t)g.npos_s * g.pitch;
     if (lds > lds_budget || lds > kMaxLdsBytes) return false;
     g.lds_bytes = (int)((lds + 15) / 16 * 16);
     *out = g;
     return true;
 }
 
-struct MfmaArgs {
-    int C, D, N, H, W, P, Q, S, RS, s_h, s_w, pad_h, pad_w;
-    int TP, NS, tiles_p, Hs, Ws, npos_s, npos, CC, nchunks, NCB, pitch, DB, ndb, tile_bytes;
-    float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q, inv_S;
-};
-
-// floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
-// product at least 1/(2d) away from every integer, well above the two float roundings)
-__device__ inline int fdiv19(int e, float inv) { return (int)(((float)e + 0.5f) * inv); }
-
-template <sc_dtype_t DT, int MW, int NW, int WM>
-__global__ void __launch_bounds__(256)
-mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
-                 const uint4w* __restrict__ wfrag, const MfmaArgs a)
-{
-    using X = typename Types<DT>::X;
-    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
-    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WM, wn = wave / WM;
-    const int n16 = lane & 15, kg = lane >> 4;
-
-    // workgroup -> (sample group, row tile, output-channel block); the blocks of one tile are
-    // neighbours so that they find the tile in the L2 their siblings loaded.  Workgroups are dealt
-    // round-robin to the 8 XCDs: number them so that each XCD gets a contiguous run.
-    const int grid = gridDim.x;
-    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int bt = fdiv19(wg, a.inv_ndb);
-    const int db = wg - bt * a.ndb;
-    const int bg = fdiv19(bt, a.inv_tiles_p);
-    const int tpi = bt - bg * a.tiles_p;
-    const int b0 = bg * a.NS, p0 = tpi * a.TP;
-    const int row0 = p0 * a.s_h - a.pad_h, col0 = -a.pad_w;
-    const int plane = a.H * a.W, PQ = a.P * a.Q;
-
-    // positions of this lane's NW column blocks: byte offset of the staged position in LDS (plus
-    // the lane's k group) and element offset of the output inside y, or -1
-    int bbase[NW];
-    int64_t yoff[NW];
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const int f = ((wn * NW + i) * 16 + n16);
-        const int sm = fdiv19(f, a.inv_TPQ);
-        const int rem = f - sm * (a.TP * a.Q);
-        const int tp = fdiv19(rem, a.inv_Q);
-        const int tq = rem - tp * a.Q;
-        const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
-        bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
-        yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
-    }
-
-    Acc acc[MW][NW];
-#pragma unroll
-    for (int m = 0; m < MW; ++m)
-#pragma unroll
-        for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
-
-    const int mblk0 = db * (a.DB >> 4) + wm * MW;            // first 16-row block of this wave
-    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
-
-    // Where every staged position lies in the input (element offset inside channel 0 of sample b0),
-    // or -1 where it shows padding or a sample past the batch: worked out once, kept in LDS behind
-    // the tile, so that copying a chunk costs one table read, CV loads and one 16-byte LDS write
-    // per channel group of a position
-    int* srctab = reinterpret_cast<int*>(lds + a.tile_bytes);
-    for (int pos = tid; pos < a.npos_s; pos += 256) {
-        const int sm = fdiv19(pos, a.inv_HsWs);
-        const int rem = pos - sm * (a.Hs * a.Ws);
-        const int i = fdiv19(rem, a.inv_Ws);
-        const int w = rem - i * a.Ws;
-        const int row = row0 + i, col = col0 + w;
-        const bool in = row >= 0 && row < a.H && col >= 0 && col < a.W && b0 + sm < a.N;
-        srctab[pos] = in ? sm * a.C * plane + row * a.W + col : -1;
-    }
-    const X* xb = x + (int64_t)b0 * a.C * plane;
-    const uint4w* wbase[MW];
-#pragma unroll
-    for (int m = 0; m < MW; ++m) wbase[m] = wfrag + (int64_t)(mblk0 + m) * a.RS * a.NCB * 64 + lane;
-    // vectors (position, channel group) are dealt to the threads position-fastest: thread t takes
-    // t, t + 256, ...; the step of 256 is q256 whole channel groups plus r256 positions
-    const int q256 = 256 / a.npos_s, r256 = 256 - q256 * a.npos_s;
-    const int cg_first = fdiv19(tid, 1.0f / (float)a.npos_s), pos_first = tid - cg_first * a.npos_s;
-
-    for (int ch = 0; ch < a.nchunks; ++ch) {
-        const int c0 = ch * a.CC;
-        __syncthreads();                 // table written / the previous chunk has been multiplied
-        // ------------------------------------------------------------ stage the chunk, transposed:
-        // one 16-byte LDS write = CV consecutive channels of one staged position; consecutive
-        // threads hold consecutive positions, so each of the CV loads of a wave covers contiguous
-        // runs of a channel plane
-        {
-            const int cleft = a.C - c0;                      // channels of the layer from c0 on
-            const X* xc = xb + (int64_t)c0 * plane;
-            int cg = cg_first, pos = pos_first;
-            while (cg < cgroups) {
-                // (branch-free: a position that shows padding and a channel past the layer's last
-                // load a valid element all the same and drop it, so that the CV loads are issued
-                // back to back)
-                const int so = srctab[pos];
-                const int sofs = so >= 0 ? so : 0;
-                X val[CV];
-#pragma unroll
-                for (int j = 0; j < CV; ++j) {
-                    const int c = cg * CV + j;
-                    const X v = xc[sofs + (c < cleft ? c : 0) * plane];
-                    val[j] = (so >= 0 && c < cleft) ? v : X(0);
-                }
-                uint4w pk;
-                __builtin_memcpy(&pk, val, 16);
-                *reinterpret_cast<uint4w*>(lds + pos * a.pitch + cg * 16) = pk;
-                cg += q256;
-                pos += r256;
-                if (pos >= a.npos_s) { pos -= a.npos_s; ++cg; }
-            }
-        }
-        __syncthreads();
-        // ------------------------------------------------------------ multiply: one step = one
-        // filter tap x one block of CB channels.  The weights come from L2 (latency of several
-        // hundred clocks, against 16 clocks per MFMA): the operands of the next PF steps are kept
-        // in flight in a ring of registers; the tile operands, which come from LDS, one step ahead.
-        const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
-        const int gcb0 = c0 / CB;
-        const int ksteps = a.RS * cbs;
-        const float inv_cbs = 1.0f / (float)cbs;
-        auto decode = [&](int ks, int& toff, int& woff) {
-            const int tap = fdiv19(ks, inv_cbs);
-            const int cb = ks - tap * cbs;
-            const int r = fdiv19(tap, a.inv_S), sx = tap - r * a.S;
-            toff = (r * a.Ws + sx) * a.pitch + cb * (CB * (int)sizeof(X));
-            woff = (tap * a.NCB + gcb0 + cb) * 64;
-        };
-        auto fetch_w = [&](int ks, uint4w (&av)[MW]) {
-            int toff, woff;
-            decode(ks, toff, woff);
-#pragma unroll
-            for (int m = 0; m < MW; ++m) av[m] = wbase[m][woff];
-        };
-        auto fetch_x = [&](int ks, uint4w (&bv)[NW]) {
-            int toff, woff;
-            decode(ks, toff, woff);
-#pragma unroll
-            for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
-        };
-        auto multiply = [&](const uint4w (&av)[MW], const uint4w (&bv)[NW]) {
-#pragma unroll
-            for (int m = 0; m < MW; ++m)
-#pragma unroll
-                for (int i = 0; i < NW; ++i) {
-                    if constexpr (kIntActs<DT>)
-                        acc[m][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av[m]),
-                                                                          __builtin_bit_cast(int4v_, bv[i]), acc[m][i], 0, 0, 0);
-                    else
-                        acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av[m]),
-                                                                           __builtin_bit_cast(half8v, bv[i]), acc[m][i], 0, 0, 0);
-                }
-        };
-        constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
-        uint4w aq[PF][MW], bq[2][NW];
-        const int last = ksteps - 1;
-#pragma unroll
-        for (int u = 0; u < PF; ++u) fetch_w(min(u, last), aq[u]);
-        fetch_x(0, bq[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        const int main_steps = ksteps / PF * PF;
-        for (int ks = 0; ks < main_steps; ks += PF) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                // Step ks + u: request the tile operands of the next step, multiply, then refill
-                // this step's slot of the weight ring with the weights of step ks + u + PF -- after
-                // the MFMAs that read the slot, so that the slot keeps its registers from one
-                // round of the ring to the next.  Indices past the end are clamped (a few redundant
-                // loads instead of branches: the body stays straight-line code with static wait
-                // counts); the scheduling barriers keep the compiler from sinking the loads of
-                // later steps down to their first use, which would put the L2 latency back on the
-                // critical path.
-                fetch_x(min(ks + u + 1, last), bq[(u + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(aq[u], bq[u & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch_w(min(ks + u + PF, last), aq[u]);
-            }
-        }
-        uint4w (&bcur)[NW] = bq[0];
-        for (int ks = main_steps; ks < ksteps; ++ks) {       // at most PF - 1 steps
-            uint4w acur[MW];
-            fetch_w(ks, acur);
-            fetch_x(ks, bcur);
-            multiply(acur, bcur);
-        }
-    }
-    // ---------------------------------------------------------------- store: a lane holds, for its
-    // position (column n16 of the block), the four output channels 4 * kg .. 4 * kg + 3 of each row block
-#pragma unroll
-    for (int m = 0; m < MW; ++m) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int d = (mblk0 + m) * 16 + 4 * kg + j;
-            if (d < a.D) {
-#pragma unroll
-                for (int i = 0; i < NW; ++i)
-                    if (yoff[i] >= 0) store_out(y + yoff[i] + (int64_t)d * PQ, narrow<DT>(acc[m][i][j]));
-            }
-        }
-    }
-}
-
 int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N)
 {
     (void)p;
     return ((N + g.NS - 1) / g.NS) * g.tiles_p * g.ndb;
-}
-
-template <sc_dtype_t DT, int MW, int NW, int WM>
-static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
-{
-    using X = typename Types<DT>::X;
-    using Y = typename Types<DT>::Y;
-    auto kernel = mfma_conv_kernel<DT, MW, NW, WM>;
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [&] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-    });
-    if (attr_err != hipSuccess) return SC_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.mg.lds_bytes, stream, static_cast<const X*>(x),
-                       static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
-    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
-}
-
-template <sc_dtype_t DT, int MW, int WM>
-static sc_status_t launch_mfma_nw(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
-{
-    switch (p.mg.NW) {
-        case 1: return launch_mfma_one<DT, MW, 1, WM>(p, a, x, y, grid, stream);
-        case 2: return launch_mfma_one<DT, MW, 2, WM>(p, a, x, y, grid, stream);
-        case 4: return launch_mfma_one<DT, MW, 4, WM>(p, a, x, y, grid, stream);
-    }
-    return SC_ERR_UNSUPPORTED;
-}
-
-template <sc_dtype_t DT>
-static sc_status_t launch_mfma_dt(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
-{
-    if (p.mg.WM == 2) return launch_mfma_nw<DT, 4, 2>(p, a, x, y, grid, stream);
-    switch (p.mg.MW) {
-        case 1: return launch_mfma_nw<DT, 1, 1>(p, a, x, y, grid, stream);
-        case 2: return launch_mfma_nw<DT, 2, 1>(p, a, x, y, grid, stream);
-        case 4: return launch_mfma_nw<DT, 4, 1>(p, a, x, y, grid, stream);
-    }
-    return SC_ERR_UNSUPPORTED;
 }
 
 sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
@@ -420,17 +161,21 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     a.S = p.L.S; a.RS = p.L.R * p.L.S; a.s_h = p.L.stride_h; a.s_w = p.L.stride_w; a.pad_h = p.L.pad_h; a.pad_w = p.L.pad_w;
     a.TP = g.TP; a.NS = g.NS; a.tiles_p = g.tiles_p; a.Hs = g.Hs; a.Ws = g.Ws; a.npos_s = g.npos_s; a.npos = g.npos;
     a.CC = g.CC; a.nchunks = g.nchunks; a.NCB = g.NCB; a.pitch = g.pitch; a.DB = g.DB; a.ndb = g.ndb;
-    a.tile_bytes = g.npos_s * g.pitch;
-    a.inv_ndb = 1.0f / (float)g.ndb; a.inv_tiles_p = 1.0f / (float)g.tiles_p; a.inv_S = 1.0f / (float)p.L.S;
+    // elements per staging load: the widest power of two (up to 16 bytes) that divides the row length
+    // and the caller's pointer
+    a.epv = 1;
+    for (int e = 16 / p.ex; e > 1; e >>= 1)
+        if (p.L.W % e == 0 && reinterpret_cast<uintptr_t>(x) % (uintptr_t)(e * p.ex) == 0) { a.epv = e; break; }
+    a.inv_ndb = 1.0f / (float)g.ndb; a.inv_tiles_p = 1.0f / (float)g.tiles_p;
     a.inv_HsWs = 1.0f / (float)(g.Hs * g.Ws); a.inv_Ws = 1.0f / (float)g.Ws;
     a.inv_TPQ = 1.0f / (float)(g.TP * p.Q); a.inv_Q = 1.0f / (float)p.Q;
     if (g.npos_s >= (1 << 19)) return SC_ERR_UNSUPPORTED;
     switch (p.dtype) {
-        case SC_F16: return launch_mfma_dt<SC_F16>(p, a, x, y, (int)grid, stream);
         // (the codebook variants were decoded when the weights were densified: same arithmetic)
-        case SC_CB4_F16: return launch_mfma_dt<SC_F16>(p, a, x, y, (int)grid, stream);
-        case SC_I8: return launch_mfma_dt<SC_I8>(p, a, x, y, (int)grid, stream);
-        case SC_CB4_I8: return launch_mfma_dt<SC_I8>(p, a, x, y, (int)grid, stream);
+        case SC_F16:
+        case SC_CB4_F16: return launch_mfma_f16(p, a, x, y, (int)grid, stream);
+        case SC_I8:
+        case SC_CB4_I8: return launch_mfma_i8(p, a, x, y, (int)grid, stream);
         default: return SC_ERR_UNSUPPORTED;
     }
 }

@@ -1,0 +1,353 @@
+// Kernel of the DENSE variant (the densified tile on the matrix cores) and its typed launcher;
+// included by dense_mfma.hip (host side) and by the two translation units that instantiate it for
+// 16-bit and 8-bit activations.  See dense_mfma.hip for the formulation.
+#pragma once
+
+#include <mutex>
+#include <type_traits>
+
+#include "sc_device.h"
+#include "sc_internal.h"
+
+namespace sc {
+
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef int int4v_ __attribute__((ext_vector_type(4)));
+typedef unsigned uint4w __attribute__((ext_vector_type(4)));
+
+// (Measured on this chip: the 16 x 16 block instructions used here sustain 1.3 PFLOP/s in fp16
+// with four waves per SIMD and 0.8 with one, the 32 x 32 ones 2.3 and 2.0.  The layers this
+// variant serves are too small for the wave tiles of 64 x 128 outputs that the 32 x 32 form needs
+// to be fed from LDS and L2 at that rate: built that way it was 10 - 40 % slower on every layer
+// tried, so the blocks stay 16 x 16.)
+template <sc_dtype_t DT> constexpr bool kIntActs = DT == SC_I8 || DT == SC_CB4_I8;
+// input channels contracted by one MFMA, and held by one lane (16 bytes)
+template <sc_dtype_t DT> constexpr int kChanBlock = kIntActs<DT> ? 64 : 32;
+template <sc_dtype_t DT> constexpr int kChanVec = kIntActs<DT> ? 16 : 8;
+
+struct MfmaArgs {
+    int C, D, N, H, W, P, Q, S, RS, s_h, s_w, pad_h, pad_w;
+    int TP, NS, tiles_p, Hs, Ws, npos_s, npos, CC, nchunks, NCB, pitch, DB, ndb, epv;
+    float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q;
+};
+
+sc_status_t launch_mfma_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+
+// floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
+// product at least 1/(2d) away from every integer, well above the two float roundings)
+__device__ inline int fdiv19(int e, float inv) { return (int)(((float)e + 0.5f) * inv); }
+
+// ------------------------------------------------------------------------------------------------
+// Staging of one chunk of CC input channels of the tile, transposed on the way: global memory is
+// channel-major (NCHW), the LDS tile channel-minor.  One block = CV consecutive channels x EPV
+// consecutive columns of one input row: CV loads of EPV elements each (the widest load the row
+// length and the pointer allow: 16, 8, 4, 2 or 1 bytes), transposed in registers, written as EPV
+// 16-byte LDS words (one staged position each).  Blocks are dealt to the threads column-group
+// fastest, so the loads of a wave run along input rows; VB blocks per round, all loads of a round
+// issued before the first is used.  Channels past the layer's last are written as zeros; positions
+// that show padding (or samples past the batch) are zeroed by a second, cheap loop.
+// ------------------------------------------------------------------------------------------------
+struct StageArgs {
+    int nsv;               // samples of this workgroup inside the batch
+    int ilo, nrows;        // staged rows that lie inside the input: [ilo, ilo + nrows)
+    int rlo;               // input row of staged row ilo
+    int wcols;             // input columns that are staged: [0, wcols)
+};
+
+template <typename X, int CV, int EPV>
+__device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned char* lds, int tid, int cgroups, int cleft,
+                                            const StageArgs& sa, const MfmaArgs& a, int plane)
+{
+    struct alignas(EPV * sizeof(X)) Vec { X e[EPV]; };
+    constexpr int VB = EPV >= 8 ? 1 : (EPV >= 2 ? 2 : 4);
+    const int G = (sa.wcols + EPV - 1) / EPV;
+    const int rowsG = sa.nrows * G, per_cg = sa.nsv * rowsG;
+    const int nblocks = cgroups * per_cg;
+    const float inv_per_cg = 1.0f / (float)max(per_cg, 1), inv_rowsG = 1.0f / (float)max(rowsG, 1), inv_G = 1.0f / (float)max(G, 1);
+    for (int v0 = tid; v0 < nblocks; v0 += 256 * VB) {
+        Vec val[VB][CV];
+        int dst[VB], vcg[VB], col[VB];
+#pragma unroll
+        for (int u = 0; u < VB; ++u) {
+            const int v = v0 + u * 256;
+            const int vv = v < nblocks ? v : 0;            // (past the end: block 0 again, not written)
+            const int cg = fdiv19(vv, inv_per_cg);
+            const int rb = vv - cg * per_cg;
+            const int sm = fdiv19(rb, inv_rowsG);
+            const int r2 = rb - sm * rowsG;
+            const int ii = fdiv19(r2, inv_G);
+            const int g = r2 - ii * G;
+            vcg[u] = v < nblocks ? cg : -1;
+            col[u] = g * EPV;
+            dst[u] = ((sm * a.Hs + sa.ilo + ii) * a.Ws + a.pad_w + g * EPV) * a.pitch + cg * 16;
+            const X* src = xc + sm * a.C * plane + (sa.rlo + ii) * a.W + g * EPV;
+#pragma unroll
+            for (int j = 0; j < CV; ++j) {
+                const int c = cg * CV + j;
+                val[u][j] = *reinterpret_cast<const Vec*>(src + (c < cleft ? c : 0) * plane);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < VB; ++u) {
+            if (vcg[u] < 0) continue;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                X o[CV];
+#pragma unroll
+                for (int j = 0; j < CV; ++j) o[j] = (vcg[u] * CV + j < cleft) ? val[u][j].e[e] : X(0);
+                uint4w pk;
+                __builtin_memcpy(&pk, o, 16);
+                if (col[u] + e < sa.wcols) *reinterpret_cast<uint4w*>(lds + dst[u] + e * a.pitch) = pk;
+            }
+        }
+    }
+    // padding: staged positions outside the input or past the batch
+    for (int pos = tid; pos < a.npos_s; pos += 256) {
+        const int sm = fdiv19(pos, a.inv_HsWs);
+        const int rem = pos - sm * (a.Hs * a.Ws);
+        const int i = fdiv19(rem, a.inv_Ws);
+        const int w = rem - i * a.Ws;
+        const bool inside = sm < sa.nsv && i >= sa.ilo && i < sa.ilo + sa.nrows && w >= a.pad_w && w < a.pad_w + sa.wcols;
+        if (!inside)
+            for (int cg = 0; cg < cgroups; ++cg) *reinterpret_cast<uint4w*>(lds + pos * a.pitch + cg * 16) = uint4w{0u, 0u, 0u, 0u};
+    }
+}
+
+// One step of the contraction = one filter tap x one block of CB input channels of the resident
+// chunk.  The step counter and everything derived from it are wave-uniform and advance by scalar
+// arithmetic; past the last step the counter stays where it is (the operand prefetch then reloads
+// the last step's operands instead of branching).
+struct StepCursor {
+    int cb, r, s, tap;
+    __device__ __forceinline__ void advance(int cbs, int S, bool more)
+    {
+        if (!more) return;
+        if (++cb == cbs) {
+            cb = 0;
+            ++tap;
+            if (++s == S) { s = 0; ++r; }
+        }
+    }
+};
+
+template <sc_dtype_t DT, int MW, int NW, int WM>
+__global__ void __launch_bounds__(256)
+mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                 const uint4w* __restrict__ wfrag, const MfmaArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
+    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
+    constexpr int WN = 4 / WM;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int n16 = lane & 15, kg = lane >> 4;
+
+    // workgroup -> (sample group, row tile, output-channel block); the blocks of one tile are
+    // neighbours so that they find the tile in the L2 their siblings loaded.  Workgroups are dealt
+    // round-robin to the 8 XCDs: number them so that each XCD gets a contiguous run.
+    const int grid = gridDim.x;
+    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int bt = fdiv19(wg, a.inv_ndb);
+    const int db = wg - bt * a.ndb;
+    const int bg = fdiv19(bt, a.inv_tiles_p);
+    const int tpi = bt - bg * a.tiles_p;
+    const int b0 = bg * a.NS, p0 = tpi * a.TP;
+    const int row0 = p0 * a.s_h - a.pad_h;
+    const int plane = a.H * a.W, PQ = a.P * a.Q;
+
+    // positions of this lane's NW column blocks: byte offset of the staged position in LDS (plus
+    // the lane's k group) and element offset of the output inside y, or -1
+    int bbase[NW];
+    int64_t yoff[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int f = ((wn * NW + i) * 16 + n16);
+        const int sm = fdiv19(f, a.inv_TPQ);
+        const int rem = f - sm * (a.TP * a.Q);
+        const int tp = fdiv19(rem, a.inv_Q);
+        const int tq = rem - tp * a.Q;
+        const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
+        bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+        yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
+    }
+
+    Acc acc[MW][NW];
+#pragma unroll
+    for (int m = 0; m < MW; ++m)
+#pragma unroll
+        for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
+
+    const int mblk0 = db * (a.DB >> 4) + wm * MW;            // first 16-row block of this wave
+    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
+
+    StageArgs sa;
+    sa.nsv = min(a.NS, a.N - b0);
+    sa.ilo = max(0, -row0);
+    sa.nrows = max(0, min(a.Hs, a.H - row0) - sa.ilo);
+    sa.rlo = row0 + sa.ilo;
+    sa.wcols = min(a.W, a.Ws - a.pad_w);
+    const X* xb = x + (int64_t)b0 * a.C * plane;
+    // the weights of row block m of this wave: a wave-uniform base, the lane adds its 16 bytes
+    const int wrow = a.RS * a.NCB * 64;                      // 16-byte words per 16-row block
+
+    auto multiply = [&](const uint4w (&av)[MW], const uint4w (&bv)[NW]) {
+#pragma unroll
+        for (int m = 0; m < MW; ++m)
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                if constexpr (kIntActs<DT>)
+                    acc[m][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av[m]),
+                                                                      __builtin_bit_cast(int4v_, bv[i]), acc[m][i], 0, 0, 0);
+                else
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av[m]),
+                                                                       __builtin_bit_cast(half8v, bv[i]), acc[m][i], 0, 0, 0);
+            }
+    };
+
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const int c0 = ch * a.CC;
+        const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
+        const int gcb0 = c0 / CB;
+        const int ksteps = a.RS * cbs;
+        const int last = ksteps - 1;
+        // The weights come from L2 (several hundred clocks away, against 32 clocks per MFMA): the
+        // operands of the next PF steps are kept in flight in a ring of registers.  The ring is
+        // filled before the chunk is staged, so that its latency hides behind the copy.
+        constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
+        uint4w aq[PF][MW], bq[2][NW];
+        StepCursor wc{0, 0, 0, 0}, xc_{0, 0, 0, 0};
+        int wk = 0;                                          // step the weight cursor stands on
+        auto fetch_w = [&](uint4w (&av)[MW]) {
+            const uint4w* wu = wfrag + ((int64_t)mblk0 * wrow + (wc.tap * a.NCB + gcb0 + wc.cb) * 64);
+#pragma unroll
+            for (int m = 0; m < MW; ++m) av[m] = wu[m * wrow + lane];
+            wc.advance(cbs, a.S, wk < last);
+            wk += wk < last ? 1 : 0;
+        };
+        int xk = 0;
+        auto fetch_x = [&](uint4w (&bv)[NW]) {
+            const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
+#pragma unroll
+            for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+            xc_.advance(cbs, a.S, xk < last);
+            xk += xk < last ? 1 : 0;
+        };
+#pragma unroll
+        for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
+        if (ch > 0) __syncthreads();     // the previous chunk has been multiplied
+        // ------------------------------------------------------------ stage the chunk, transposed
+        {
+            const X* xc = xb + (int64_t)c0 * plane;
+            const int cleft = a.C - c0;                      // channels of the layer from c0 on
+            switch (a.epv) {
+                case 16: if constexpr (sizeof(X) == 1) { stage_chunk<X, CV, 16>(xc, lds, tid, cgroups, cleft, sa, a, plane); } break;
+                case 8: stage_chunk<X, CV, 8>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                case 4: stage_chunk<X, CV, 4>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                case 2: stage_chunk<X, CV, 2>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                default: stage_chunk<X, CV, 1>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+            }
+        }
+        __syncthreads();
+        // ------------------------------------------------------------ multiply
+        fetch_x(bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int main_steps = ksteps / PF * PF;
+        for (int ks = 0; ks < main_steps; ks += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                // Step ks + u: request the tile operands of the next step (from LDS), multiply,
+                // then refill this step's slot of the weight ring with the weights of step
+                // ks + u + PF -- after the MFMAs that read the slot, so that the slot keeps its
+                // registers from one round of the ring to the next.  The scheduling barriers keep
+                // the compiler from sinking the loads of later steps down to their first use, which
+                // would put the L2 latency back on the critical path.
+                fetch_x(bq[(u + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(aq[u], bq[u & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_w(aq[u]);
+            }
+        }
+        // the last ksteps % PF steps: their weights are in the first slots of the ring (the cursor
+        // stopped at the last step), their tile operands alternate as before
+#pragma unroll
+        for (int u = 0; u < PF - 1; ++u) {
+            if (main_steps + u < ksteps) {
+                fetch_x(bq[(u + 1) & 1]);
+                multiply(aq[u], bq[u & 1]);
+            }
+        }
+    }
+    // ---------------------------------------------------------------- store: a lane holds, for its
+    // position (column n16 of the block), the four output channels 4 * kg .. 4 * kg + 3 of each row block
+#pragma unroll
+    for (int m = 0; m < MW; ++m) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int d = (mblk0 + m) * 16 + 4 * kg + j;
+            if (d < a.D) {
+#pragma unroll
+                for (int i = 0; i < NW; ++i)
+                    if (yoff[i] >= 0) store_out(y + yoff[i] + (int64_t)d * PQ, narrow<DT>(acc[m][i][j]));
+            }
+        }
+    }
+}
+
+template <sc_dtype_t DT, int MW, int NW, int WM>
+static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+{
+    using X = typename Types<DT>::X;
+    using Y = typename Types<DT>::Y;
+    auto kernel = mfma_conv_kernel<DT, MW, NW, WM>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    });
+    if (attr_err != hipSuccess) return SC_ERR_HIP;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.mg.lds_bytes, stream, static_cast<const X*>(x),
+                       static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int MW, int WM>
+static sc_status_t launch_mfma_nw(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+{
+    switch (p.mg.NW) {
+        case 1: return launch_mfma_one<DT, MW, 1, WM>(p, a, x, y, grid, stream);
+        case 2: return launch_mfma_one<DT, MW, 2, WM>(p, a, x, y, grid, stream);
+        case 4: return launch_mfma_one<DT, MW, 4, WM>(p, a, x, y, grid, stream);
+        case 8:
+            if constexpr (MW <= 2) return launch_mfma_one<DT, MW, 8, WM>(p, a, x, y, grid, stream);
+            break;
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+template <sc_dtype_t DT>
+static sc_status_t launch_mfma_typed(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+{
+    const int key = p.mg.WM * 10 + p.mg.MW;
+    switch (key) {
+        case 11: return launch_mfma_nw<DT, 1, 1>(p, a, x, y, grid, stream);
+        case 12: return launch_mfma_nw<DT, 2, 1>(p, a, x, y, grid, stream);
+        case 14: return launch_mfma_nw<DT, 4, 1>(p, a, x, y, grid, stream);
+        case 21: return launch_mfma_nw<DT, 1, 2>(p, a, x, y, grid, stream);
+        case 22: return launch_mfma_nw<DT, 2, 2>(p, a, x, y, grid, stream);
+        case 24: return launch_mfma_nw<DT, 4, 2>(p, a, x, y, grid, stream);
+        case 41: return launch_mfma_nw<DT, 1, 4>(p, a, x, y, grid, stream);
+        case 42: return launch_mfma_nw<DT, 2, 4>(p, a, x, y, grid, stream);
+    }
+    return SC_ERR_UNSUPPORTED;
+}
+
+}  // namespace sc

@@ -239,9 +239,17 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q) return SC_ERR_UNSUPPORTED;
     const int budget = kMaxLdsBytes / t.wg_per_cu;
     const int CB = mfma_chan_block(p.dtype);
+    if (t.waves_m != 0 && t.waves_m != 1 && t.waves_m != 2 && t.waves_m != 4) return SC_ERR_UNSUPPORTED;
     int DB = t.tile_d;
     if (DB == 0) DB = L.D > 64 ? 128 : (L.D > 32 ? 64 : (L.D > 16 ? 32 : 16));
-    const int maxpos = (DB == 128 ? 2 : 4) * 4 * 16;          // positions the four waves can hold
+    // waves along the output channels: by default as many as still leave every wave 32 channels
+    // (two 16-row blocks), so that the weights, which every wave fetches for itself from L2, are
+    // fetched by few waves each
+    int WM = t.waves_m;
+    if (WM == 0) WM = DB >= 128 ? 4 : (DB >= 64 ? 2 : 1);
+    if (DB % (16 * WM) || DB / (16 * WM) < 1 || DB / (16 * WM) > 4) return SC_ERR_UNSUPPORTED;
+    const int MWv = DB / (16 * WM);
+    const int maxpos = (4 / WM) * (MWv == 4 ? 4 : 8) * 16;    // positions the four waves can hold
     int TP = t.tile_p, NS = t.sub_batch;
     const bool fixed_tile = TP != 0 || NS != 0;
     if (TP == 0 && NS == 0) {
@@ -253,9 +261,9 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     MfmaGeom g{};
     for (;;) {
         bool ok = false;
-        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, budget, &g);
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g);
         else
-            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, budget, &g);
+            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g);
         if (ok) break;
         if (fixed_tile) return SC_ERR_UNSUPPORTED;
         // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
@@ -270,6 +278,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     r.sub_batch = g.NS;
     r.chunk_c = g.CC;
     r.tile_d = g.DB;
+    r.waves_m = g.WM;
     r.wg_per_cu = t.wg_per_cu;
     *out = r;
     *mgeom = g;
@@ -286,6 +295,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         return resolve_dense(p, t, out, mgeom);
     }
     *mgeom = MfmaGeom{};
+    if (t.waves_m) return SC_ERR_UNSUPPORTED;
     if (t.wg_threads == 0) t.wg_threads = 256;
     if (t.wg_threads < 64 || t.wg_threads > 1024 || t.wg_threads % 64) return SC_ERR_UNSUPPORTED;
     if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
@@ -906,14 +916,16 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     // the densified tile on the matrix cores (16- and 8-bit activations): output-channel block x
     // tile of positions (rows of one sample, or whole planes of several) x workgroups per CU
     if (p.dtype != SC_F32 && !p.has_dup && p.n > 0) {
-        for (int db : {32, 64, 128}) for (int wpc : {1, 2, 3, 4}) {
-            { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; push(t); }
-            for (int tp : {1, 2, 4, 7, 8, 14}) {
+        for (int db : {32, 64, 128}) for (int wm : {1, 2, 4}) for (int wpc : {1, 2, 3}) {
+            if (db % (16 * wm) || db / (16 * wm) > 4 || (db > 32 && db >= 2 * p.L.D)) continue;
+            auto base = [&]() { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.waves_m = wm; t.wg_per_cu = wpc; return t; };
+            push(base());
+            for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
                 if (tp >= p.P) continue;
-                sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; t.tile_p = tp; push(t);
+                sc_tuning_t t = base(); t.tile_p = tp; push(t);
             }
             for (int ns : {1, 2, 4, 8, 16}) {
-                sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.wg_per_cu = wpc; t.tile_p = p.P; t.sub_batch = ns; push(t);
+                sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
             }
         }
     }

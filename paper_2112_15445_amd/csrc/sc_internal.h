@@ -125,7 +125,7 @@ constexpr int kMaxRowsPerWave = 8;
 int mfma_chan_block(sc_dtype_t dt);
 size_t mfma_weight_bytes(const Plan& p);
 sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream);
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int lds_budget, MfmaGeom* out);
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out);
 int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N);
 sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 

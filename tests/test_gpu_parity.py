@@ -58,7 +58,7 @@ def _both_variants(plan):
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 192, "tile_q": 64}),
                            (B.SC_VARIANT_SLAB, {"wsrc": 1, "pipeline": 2, "wg_threads": 448, "tile_q": 96}),
                            (B.SC_VARIANT_DENSE, {}),
-                           (B.SC_VARIANT_DENSE, {"tile_d": 16, "tile_p": 1, "wg_per_cu": 4}),
+                           (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 1, "wg_per_cu": 4, "waves_m": 1}),
                            (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2, "chunk_c": 64}),
                            (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 2}),
                            (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 3, "wg_per_cu": 1})):
@@ -840,6 +840,9 @@ def test_dense_variant_on_the_matrix_cores(dtype):
         ran = 0
         for extra in ({}, {"tile_d": 16}, {"tile_d": 32, "tile_p": 1}, {"tile_d": 64, "tile_p": 2, "chunk_c": 64},
                       {"tile_d": 128, "wg_per_cu": 1}, {"tile_d": 64, "tile_p": 1000, "sub_batch": 4},
+                      {"tile_d": 128, "waves_m": 2, "tile_p": 2}, {"tile_d": 128, "waves_m": 4}, {"tile_d": 64, "waves_m": 1, "tile_p": 3},
+                      {"tile_d": 64, "waves_m": 2, "chunk_c": 64},
+                      {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
                       {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
             try:
                 plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, **extra)
