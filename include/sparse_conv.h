@@ -285,6 +285,49 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
  * caller instead of allocating it (an upper bound over the alignments x_dev / y_dev may have). */
 sc_status_t sparse_conv_autotune_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
 
+/* Which implementation sparse_conv_forward runs for a plan. */
+enum {
+    SC_PATH_SPARSE = 0,   /* the gather kernels (SC_VARIANT_GATHER / SC_VARIANT_SLAB) */
+    SC_PATH_DENSE = 1,    /* the library's densified tile on the matrix cores (SC_VARIANT_DENSE) */
+    SC_PATH_LIBRARY = 2   /* the dense library's convolution (MIOpen, looked up at run time) */
+};
+
+/* Record of sparse_conv_plan_dispatch: milliseconds per forward pass of each contender (-1: not
+ * available for this layer or machine), the launch shapes of the two in-library contenders, and
+ * the choice that was installed. */
+typedef struct {
+    int32_t choice;              /* SC_PATH_* */
+    float sparse_ms;             /* gather kernels, tuned, cold ring */
+    float dense_ms;              /* densified MFMA tile, tuned, cold ring */
+    float library_ms;            /* dense library on the caller's buffer pair (cache-warm) */
+    sc_tuning_t sparse_tuning;
+    sc_tuning_t dense_tuning;
+} sc_dispatch_t;
+
+/* Per-layer dispatch: steps 3 and 4 of the paper's "Main scheme" -- compare the layer's time in the
+ * sparse kernel with the dense convolution's, then configure the network layer by layer.  Tunes the
+ * gather kernels and (16- / 8-bit activations) the densified MFMA tile like
+ * sparse_conv_plan_autotune, each over the cold ring, sets up the dense library's convolution of
+ * the same layer from the plan's weights (fp32 / fp16 layers, when a MIOpen is in the process or
+ * can be loaded; NCHW buffers, whatever layout changes the library makes are inside its time) and
+ * times it on the caller's buffers, records all three in *out and installs the fastest (the
+ * library only when it wins by more than 10 %, its figure being cache-warm).  sparse_conv_forward
+ * then runs that path; with SC_PATH_LIBRARY it must be called with the N given here and a workspace
+ * of sparse_conv_workspace_size bytes.  A later sparse_conv_plan_set_tuning / _autotune goes back
+ * to the library's own kernels.  y_dev is overwritten; synchronises; workspace as for
+ * sparse_conv_plan_autotune (the library's own workspace is allocated for the measurement if the
+ * caller's is too small).
+ * Errors: as sparse_conv_plan_autotune. */
+sc_status_t sparse_conv_plan_dispatch(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t N,
+                                      void* workspace_dev, size_t workspace_bytes, void* stream,
+                                      sc_dispatch_t* out);
+
+/* After sparse_conv_plan_dispatch: run another of the contenders it measured (its recorded launch
+ * shape, or the dense library with the algorithm it picked) -- the "configure the network" step of
+ * the paper's main scheme done by hand.  SC_ERR_UNSUPPORTED if there was no dispatch yet or that
+ * contender was not available. */
+sc_status_t sparse_conv_plan_set_path(sparse_conv_plan_t* plan, int32_t path, void* stream);
+
 /* Number of candidates sparse_conv_plan_autotune would time for this plan, and the i-th of them
  * (for tests that check that every candidate computes the same result). */
 sc_status_t sparse_conv_plan_num_candidates(const sparse_conv_plan_t* plan, int32_t* count);

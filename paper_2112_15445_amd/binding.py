@@ -24,13 +24,14 @@ SC_F32, SC_F16, SC_I8, SC_CB4_I8, SC_CB4_F16 = 0, 1, 2, 3, 4
 DTYPES = {"f32": SC_F32, "f16": SC_F16, "i8": SC_I8, "cb4": SC_CB4_I8, "cb4h": SC_CB4_F16}
 SC_VARIANT_AUTO, SC_VARIANT_GATHER, SC_VARIANT_SLAB, SC_VARIANT_DENSE = 0, 1, 2, 3
 SC_STATIC_WORKSPACE_BYTES = 32 << 20
+SC_PATH_SPARSE, SC_PATH_DENSE, SC_PATH_LIBRARY = 0, 1, 2
 
 # every symbol include/sparse_conv.h declares
 EXPORTS = [
     "sparse_conv_plan_create_csr", "sparse_conv_plan_create_ell", "sparse_conv_plan_destroy",
     "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning",
     "sparse_conv_plan_get_tuning", "sparse_conv_workspace_size", "sparse_conv_workspace_size_max",
-    "sparse_conv_forward", "sparse_conv_forward_static", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size",
+    "sparse_conv_forward", "sparse_conv_forward_static", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size", "sparse_conv_plan_dispatch", "sparse_conv_plan_set_path",
     "sparse_conv_plan_num_candidates",
     "sparse_conv_plan_candidate", "sparse_conv_quantize_pow2", "sparse_conv_status_string",
 ]
@@ -52,6 +53,16 @@ class sc_tuning_t(ctypes.Structure):
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_}
+
+
+class sc_dispatch_t(ctypes.Structure):
+    _fields_ = [("choice", ctypes.c_int32), ("sparse_ms", ctypes.c_float), ("dense_ms", ctypes.c_float),
+                ("library_ms", ctypes.c_float), ("sparse_tuning", sc_tuning_t), ("dense_tuning", sc_tuning_t)]
+
+    def as_dict(self):
+        return {"choice": ("sparse", "dense", "library")[self.choice], "sparse_ms": self.sparse_ms,
+                "dense_ms": self.dense_ms, "library_ms": self.library_ms,
+                "sparse_tuning": self.sparse_tuning.as_dict(), "dense_tuning": self.dense_tuning.as_dict()}
 
 
 class sc_plan_info_t(ctypes.Structure):
@@ -101,6 +112,8 @@ def lib() -> ctypes.CDLL:
     L.sparse_conv_forward_static.argtypes = [vp, vp, vp, i32, vp]
     L.sparse_conv_plan_autotune.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.sparse_conv_autotune_workspace_size.argtypes = [vp, i32, P(sz)]
+    L.sparse_conv_plan_dispatch.argtypes = [vp, vp, vp, i32, vp, sz, vp, P(sc_dispatch_t)]
+    L.sparse_conv_plan_set_path.argtypes = [vp, i32, vp]
     L.sparse_conv_plan_num_candidates.argtypes = [vp, P(i32)]
     L.sparse_conv_plan_candidate.argtypes = [vp, i32, P(sc_tuning_t)]
     L.sparse_conv_quantize_pow2.argtypes = [vp, sz, i32, ctypes.c_float, vp, P(i32)]
@@ -228,6 +241,17 @@ class Plan:
         _check(lib().sparse_conv_workspace_size_max(self._h, N, ctypes.byref(b)),
                "sparse_conv_workspace_size_max")
         return int(b.value)
+
+    def dispatch(self, x_ptr: int, y_ptr: int, N: int, ws_ptr: int = 0, ws_bytes: int = 0, stream: int = 0):
+        rec = sc_dispatch_t()
+        _check(lib().sparse_conv_plan_dispatch(self._h, ctypes.c_void_p(x_ptr), ctypes.c_void_p(y_ptr), N,
+                                               ctypes.c_void_p(ws_ptr), ws_bytes, ctypes.c_void_p(stream),
+                                               ctypes.byref(rec)),
+               "sparse_conv_plan_dispatch")
+        return rec
+
+    def set_path(self, path: int, stream: int = 0):
+        _check(lib().sparse_conv_plan_set_path(self._h, path, ctypes.c_void_p(stream)), "sparse_conv_plan_set_path")
 
     def autotune_workspace_size(self, N: int) -> int:
         b = ctypes.c_size_t()

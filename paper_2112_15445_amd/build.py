@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparseconv.so")
-SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip"]
+SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip", "dense_library.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -39,7 +39,7 @@ def build(verbose: bool = False, jobs: int = 4, incremental: bool = False) -> st
             _drain(procs)
     _drain(procs)
     tmp = LIB + f".tmp{os.getpid()}"
-    subprocess.check_call([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
+    subprocess.check_call([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs + ["-ldl"])
     os.replace(tmp, LIB)
     return LIB
 

@@ -225,6 +225,7 @@ extern "C" sc_status_t sparse_conv_forward_static(const sparse_conv_plan_t* plan
     if (!plan || !x_dev || !y_dev) return SC_ERR_NULL;
     if (N <= 0) return SC_ERR_SHAPE;
     const sc::Plan* p = reinterpret_cast<const sc::Plan*>(plan);
+    if (p->path == SC_PATH_LIBRARY) return SC_ERR_UNSUPPORTED;      // the dense library brings its own workspace needs
     if (p->tuning.variant == SC_VARIANT_SLAB) return sc::launch_slab(*p, x_dev, y_dev, N, (hipStream_t)stream);
     if (p->tuning.variant == SC_VARIANT_DENSE) return sc::launch_mfma(*p, x_dev, y_dev, N, (hipStream_t)stream);
     const size_t need = sc::gather_workspace_bytes(*p, N);

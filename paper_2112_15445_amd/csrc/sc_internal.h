@@ -67,6 +67,8 @@ struct MfmaGeom {
     int lds_bytes;
 };
 
+struct LibraryConv;   // dense_library.hip: the dense library's convolution of this layer (per-layer dispatch)
+
 struct Plan {
     sc_layer_t L;
     sc_dtype_t dtype;
@@ -93,6 +95,9 @@ struct Plan {
     unsigned char* d_wfrag = nullptr;  // dense weights in MFMA operand order (DENSE variant), built on first use
     int32_t* d_len = nullptr;       // [D] stored entries of every row before unification (device copy of h_len)
     bool has_dup = false;           // some row stores a column twice (such a table cannot be densified exactly)
+    LibraryConv* libconv = nullptr; // set by sparse_conv_plan_dispatch when it measured the dense library
+    int path = 0;                   // SC_PATH_*: which implementation sparse_conv_forward runs
+    sc_dispatch_t dispatch{};       // the last record of sparse_conv_plan_dispatch (choice -1 before the first)
     sc_tuning_t tuning{};
     SlabGeom geom{};
     MfmaGeom mg{};
@@ -120,6 +125,13 @@ sc_status_t expand_weights(const Plan& p, const int32_t* lam_slab, int2* wl32_ou
 sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32_t* lam_slab, const int32_t* seg_off,
                                    const int32_t* first_j, int2* wlc_out, hipStream_t stream);
 constexpr int kMaxRowsPerWave = 8;
+
+// dense_library.hip
+sc_status_t library_conv_create(const Plan& p, const void* x, void* y, int N, hipStream_t stream, LibraryConv** out);
+sc_status_t library_conv_forward(LibraryConv* c, const void* x, void* y, int N, void* ws, size_t ws_bytes, hipStream_t stream);
+size_t library_conv_workspace(const LibraryConv* c);
+int library_conv_batch(const LibraryConv* c);
+void library_conv_destroy(LibraryConv* c);
 
 // dense_mfma.hip
 int mfma_chan_block(sc_dtype_t dt);

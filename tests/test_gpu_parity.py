@@ -877,3 +877,63 @@ def test_dense_variant_is_refused_where_it_does_not_apply():
         plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE)
     assert e.value.status == 4 and plan.get_tuning().as_dict() == before
     plan.destroy()
+
+
+@pytest.mark.parametrize("dtype,sparsity", [("f16", 0.5), ("f32", 0.9), ("i8", 0.8)])
+def test_per_layer_dispatch_records_three_contenders_and_forward_honours_the_choice(dtype, sparsity):
+    """sparse_conv_plan_dispatch: the gather kernels, the densified MFMA tile and the dense library timed
+    on one layer; every contender that was available gives the oracle's result through
+    sparse_conv_forward."""
+    import torch
+    l = wl.Layer("dispatch", 96, 80, 14, 14, 3, 3, 1, 1, 1, 1, N=8, sparsity=sparsity, dtype=dtype, seed=31)
+    data = wl.prepare(l)
+    ref = G.oracle_out(l, data)
+    plan = G.make_plan(l, data)
+    with pytest.raises(B.SparseConvError) as e:
+        plan.set_path(B.SC_PATH_SPARSE)                      # nothing measured yet
+    assert e.value.status == 4
+    xd = G.to_device(data["x"])
+    y = torch.empty((l.N, l.D, l.P, l.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
+    ws = torch.empty(plan.autotune_workspace_size(l.N), dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    rec = plan.dispatch(xd.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), st)
+    print("dispatch", dtype, rec.as_dict(), flush=True)
+    assert rec.sparse_ms > 0
+    assert (rec.dense_ms > 0) == (dtype != "f32")
+    if dtype == "i8":
+        assert rec.library_ms < 0                            # the dense library is used for floating point only
+    times = {B.SC_PATH_SPARSE: rec.sparse_ms}
+    if rec.dense_ms > 0:
+        times[B.SC_PATH_DENSE] = rec.dense_ms
+    best = min(times, key=times.get)
+    assert rec.choice in (best, B.SC_PATH_LIBRARY)
+    if rec.choice == B.SC_PATH_LIBRARY:
+        assert 0 < rec.library_ms < 0.9 * times[best]
+
+    def run():
+        y.view(torch.uint8).fill_(0x7f)
+        need = plan.workspace_size(l.N)
+        w2 = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        plan.forward(xd.data_ptr(), y.data_ptr(), l.N, w2.data_ptr(), w2.numel(), st)
+        torch.cuda.synchronize()
+        return G.to_host(y)
+
+    if rec.choice != B.SC_PATH_LIBRARY:
+        G.check(l, run(), ref, f"dispatch {dtype}: installed choice {rec.choice}")
+    for path in (B.SC_PATH_SPARSE, B.SC_PATH_DENSE, B.SC_PATH_LIBRARY):
+        try:
+            plan.set_path(path)
+        except B.SparseConvError as e:
+            assert e.status == 4
+            assert path != B.SC_PATH_SPARSE
+            continue
+        print("case dispatch path", dtype, path, flush=True)
+        if path == B.SC_PATH_LIBRARY:
+            # the dense library picks its own algorithm (possibly a transform-domain one): its
+            # rounding is its own, so this leg is held to 1e-3 (fp32) / 2e-2 (fp16), not to the
+            # library's own kernels' 1e-5
+            got = run()
+            assert G.rel_err(got, ref) <= (1e-3 if dtype == "f32" else 2e-2), G.rel_err(got, ref)
+        else:
+            G.check(l, run(), ref, f"dispatch {dtype}: path {path}")
+    plan.destroy()
