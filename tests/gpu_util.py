@@ -49,13 +49,13 @@ def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
     return num / den if den > 0 else num
 
 
-def check(l: wl.Layer, y: np.ndarray, ref: np.ndarray, what: str = ""):
+def check(l: wl.Layer, y: np.ndarray, ref: np.ndarray, what: str = "", tol=None):
     assert y.shape == ref.shape, (what, y.shape, ref.shape)
     if l.dtype in ("i8", "cb4"):
         assert np.array_equal(y, ref), f"{what}: integer outputs differ in {np.count_nonzero(y != ref)} places"
     else:
         assert np.all(np.isfinite(y.astype(np.float64))), what
-        tol = TOL[l.dtype]
+        tol = TOL[l.dtype] if tol is None else tol
         e = rel_err(y, ref)
         assert e <= tol, f"{what}: rel err {e:.3e} > {tol:.1e}"
         yd, rd = y.astype(np.float64), ref.astype(np.float64)
@@ -83,7 +83,7 @@ def run_gpu(plan: B.Plan, x: np.ndarray, poison: bool = True) -> np.ndarray:
     return to_host(y)
 
 
-def full_batch_parity(l: wl.Layer, data, plan: B.Plan, x_dev=None, ws=None, group: int = 16):
+def full_batch_parity(l: wl.Layer, data, plan: B.Plan, x_dev=None, ws=None, group: int = 16, tol=None):
     """The installed launch shape on the FULL batch against the oracle on sampled outputs: samples
     0..group-1 (one whole group of every multi-sample launch shape: up to 16 samples share a
     workgroup) and the last one, every element of those.  Returns {"ok", "samples", "rel_err"} or
@@ -104,7 +104,7 @@ def full_batch_parity(l: wl.Layer, data, plan: B.Plan, x_dev=None, ws=None, grou
     got = to_host(y[idx].contiguous())
     ref = oracle_out(l, data, samples=idx)
     try:
-        check(l, got, ref, l.name)
+        check(l, got, ref, l.name, tol=tol)
     except AssertionError as e:
         return {"ok": False, "samples": idx, "error": str(e)[:300]}
     return {"ok": True, "samples": idx, "rel_err": rel_err(got, ref)}
