@@ -227,3 +227,36 @@ def quantise_pow2(x: np.ndarray, total_bits: int = 8, saturate_at: float = 1.0) 
     code = np.rint(np.clip(xd, -m, m) / sigma)
     code = np.clip(code, -(2 ** (total_bits - 1)), 2 ** (total_bits - 1) - 1)
     return code.astype(np.int8), frac_bits
+
+
+def epilogue(y: np.ndarray, relu: bool = False, pool: int = 0, requant_scale: Optional[np.ndarray] = None,
+             out_dtype=None) -> np.ndarray:
+    """What follows the convolution inside one layer of a VGG-shaped stack (the network the paper's
+    main scheme configures layer by layer), applied to the accumulator-type output ``y`` [N, D, P, Q]
+    of ``sparse_conv_steps``: ReLU ``max(0, .)``; 2 x 2 max-pooling with stride 2 (an odd last row /
+    column is dropped); then either one rounding to ``out_dtype`` or, for integer accumulators,
+    requantisation to 8-bit codes for the next layer,
+    ``clip(round_half_even(float32(acc) * float32(scale[d])), -127, 127)``: the paper's linear
+    quantiser q = round(x / sigma) applied to the real value acc * s_w[d] * s_x with
+    scale[d] = s_w[d] * s_x / sigma_next, evaluated in single precision -- the conversion of the
+    accumulator, the product and the rounding are each one IEEE operation, so the code is a
+    deterministic function of (acc, scale[d])."""
+    v = np.asarray(y)
+    assert v.ndim == 4 and pool in (0, 2)
+    if relu:
+        v = np.maximum(v, 0)
+    if pool == 2:
+        N, D, P, Q = v.shape
+        Po, Qo = P // 2, Q // 2
+        out = np.empty((N, D, Po, Qo), dtype=v.dtype)
+        for pp in range(Po):
+            for qq in range(Qo):
+                win = v[:, :, 2 * pp:2 * pp + 2, 2 * qq:2 * qq + 2]
+                out[:, :, pp, qq] = win.reshape(N, D, 4).max(axis=2)
+        v = out
+    if requant_scale is not None:
+        assert np.issubdtype(v.dtype, np.integer)
+        sc = np.asarray(requant_scale, dtype=np.float32).reshape(1, -1, 1, 1)
+        q = np.rint(v.astype(np.float32) * sc)              # float32 x float32 -> float32, ties to even
+        return np.clip(q, -127.0, 127.0).astype(np.int8)
+    return v if out_dtype is None else _round_out(v, out_dtype)

@@ -440,3 +440,73 @@ def test_planted_mistakes_are_caught():
     th[:, -1] = 0
     assert np.abs(run(good, theta=th) - yd).max() > 1e-6, "dropped term"
     assert np.abs(run(good, theta=-st["theta"]) - yd).max() > 1e-6, "sign"
+
+
+# ------------------------------------------------------------------------------------------------
+# epilogue of a VGG-shaped layer: ReLU, 2 x 2 max-pool, requantisation
+# ------------------------------------------------------------------------------------------------
+def test_epilogue_relu_and_pool_against_torch():
+    import torch
+    rng = np.random.default_rng(5)
+    for shape in ((2, 3, 6, 8), (1, 4, 7, 5), (3, 2, 2, 2), (2, 2, 1, 9)):
+        y = rng.normal(size=shape)
+        t = torch.from_numpy(y)
+        assert np.array_equal(oracle.epilogue(y, relu=True), torch.relu(t).numpy())
+        if shape[2] >= 2 and shape[3] >= 2:
+            ref = torch.nn.functional.max_pool2d(t, 2).numpy()
+            assert np.array_equal(oracle.epilogue(y, pool=2), ref)
+            ref = torch.nn.functional.max_pool2d(torch.relu(t), 2).numpy()
+            assert np.array_equal(oracle.epilogue(y, relu=True, pool=2), ref)
+        else:
+            assert oracle.epilogue(y, pool=2).shape == (shape[0], shape[1], shape[2] // 2, shape[3] // 2)
+    yi = rng.integers(-500, 500, size=(2, 3, 4, 6)).astype(np.int32)
+    ref = torch.nn.functional.max_pool2d(torch.relu(torch.from_numpy(yi.astype(np.float64))), 2).numpy()
+    got = oracle.epilogue(yi, relu=True, pool=2)
+    assert got.dtype == np.int32 and np.array_equal(got, ref.astype(np.int32))
+
+
+def test_epilogue_pool_hand_values_and_dropped_odd_edges():
+    y = np.arange(15, dtype=np.float64).reshape(1, 1, 3, 5)      # rows 0..2, columns 0..4
+    out = oracle.epilogue(y, pool=2)
+    assert out.shape == (1, 1, 1, 2)                              # third row and fifth column dropped
+    assert out.tolist() == [[[[6.0, 8.0]]]]                      # max(0,1,5,6), max(2,3,7,8)
+    y = np.array([[[[-3.0, -1.0], [-2.0, -5.0]]]])
+    assert oracle.epilogue(y, pool=2).item() == -1.0
+    assert oracle.epilogue(y, relu=True, pool=2).item() == 0.0    # ReLU first, then the window maximum
+
+
+def test_epilogue_requantisation_hand_values():
+    acc = np.array([10, 14, -10, -14, 1000, -1000, 0, 3], dtype=np.int32).reshape(1, 1, 1, 8)
+    q = oracle.epilogue(acc, requant_scale=np.array([0.25], np.float32))
+    # 2.5 -> 2 and 3.5 -> 4 (ties to even), symmetric for negatives, saturation at +-127, 0.75 -> 1
+    assert q.dtype == np.int8 and q.reshape(-1).tolist() == [2, 4, -2, -4, 127, -127, 0, 1]
+    # per-channel scales, applied after ReLU and pooling
+    acc = np.array([[[[7, -9], [3, 5]]], [[[7, -9], [3, 5]]]], dtype=np.int32).reshape(1, 2, 2, 2)
+    q = oracle.epilogue(acc, relu=True, pool=2, requant_scale=np.array([1.0, 0.5], np.float32))
+    assert q.reshape(-1).tolist() == [7, 4]                       # 7 * 1 and 7 * 0.5 = 3.5 -> 4
+
+
+def test_epilogue_requantisation_is_single_precision_arithmetic():
+    """The code is rint(float32(acc) * float32(scale)) with every step rounded to single precision:
+    against the same three steps done one scalar at a time, and different from the double-precision
+    evaluation on an accumulator that single precision cannot hold exactly."""
+    rng = np.random.default_rng(11)
+    acc = rng.integers(-2 ** 26, 2 ** 26, size=(1, 3, 2, 50)).astype(np.int32)
+    sc = (rng.random(3) * 1e-5 + 1e-6).astype(np.float32)
+    q = oracle.epilogue(acc, requant_scale=sc)
+    for d in range(3):
+        for i, a in enumerate(acc[0, d].reshape(-1)):
+            v = np.float32(np.float32(a) * sc[d])
+            e = int(max(-127, min(127, np.rint(v))))
+            assert q[0, d].reshape(-1)[i] == e
+    big = np.array([2 ** 24 + 1], dtype=np.int32).reshape(1, 1, 1, 1)     # float32 rounds it to 2^24
+    assert oracle.epilogue(big, requant_scale=np.array([2.0 ** -18], np.float32)).item() == 64
+    assert np.float32(big.item()) == np.float32(2 ** 24)
+
+
+def test_epilogue_relu_commutes_with_pool_and_positive_scale():
+    rng = np.random.default_rng(12)
+    y = rng.normal(size=(2, 3, 6, 6))
+    a = oracle.epilogue(oracle.epilogue(y, relu=True), pool=2)
+    b = oracle.epilogue(oracle.epilogue(y, pool=2), relu=True)
+    assert np.array_equal(a, b)
