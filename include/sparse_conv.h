@@ -172,6 +172,8 @@ typedef struct {
     int32_t grid_size;             /* workgroups per launch for the N last used by set_tuning /
                                       autotune (0 if unknown) */
     sc_tuning_t tuning;            /* current tuning, heuristic defaults resolved */
+    int32_t out_P, out_Q;          /* extents of y (P, Q unless the epilogue pools) */
+    int32_t out_elem_bytes;        /* bytes per element of y (1 when the epilogue requantises) */
 } sc_plan_info_t;
 
 /* Build a plan from CSR weights (host arrays).
@@ -284,6 +286,28 @@ sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_de
 /* Bytes of workspace with which sparse_conv_plan_autotune takes its ring of scratch buffers from the
  * caller instead of allocating it (an upper bound over the alignments x_dev / y_dev may have). */
 sc_status_t sparse_conv_autotune_workspace_size(const sparse_conv_plan_t* plan, int32_t N, size_t* bytes);
+
+/* Fused epilogue of a layer of a network that the paper's main scheme configures layer by layer (its
+ * VGG-16 experiments: convolution, ReLU, 2 x 2 max-pooling between stages; its "Quantisation" section:
+ * activations re-quantised from layer to layer with q = round(x / sigma)).  Applied to the accumulator
+ * before the one store, in this order:
+ *   relu     1: max(0, .)
+ *   pool     2: 2 x 2 max-pooling with stride 2 (an odd last output row / column is dropped); 0: none
+ *   requant  1 (SC_I8 / SC_CB4_I8 only): the output is int8,
+ *               clamp(round_half_even(float32(acc) * requant_scale[d]), -127, 127),
+ *            every step in single precision (requant_scale[d] = s_w[d] * s_x / sigma_next, host [D])
+ * y_dev is then [N, D, P', Q'] with P' = P / 2, Q' = Q / 2 when pooling, in int8 when requantising
+ * (sc_plan_info_t.out_P / out_Q / out_elem_bytes).  Available in SC_VARIANT_GATHER (with split_n = 1;
+ * sub_batch is ignored) and SC_VARIANT_DENSE (with pooling: an even tile_p or whole planes); a plan
+ * with an epilogue refuses SC_VARIANT_SLAB tunings and the dense-library path, and the autotuner /
+ * dispatch only try what is left.  All-zero *ep removes the epilogue.
+ * Errors: SC_ERR_NULL, SC_ERR_UNSUPPORTED (bad field, requant on a floating-point plan or without
+ * scales, pooling a layer with P < 2 or Q < 2), SC_ERR_OOM, SC_ERR_HIP. */
+typedef struct {
+    int32_t relu, pool, requant;
+} sc_epilogue_t;
+sc_status_t sparse_conv_plan_set_epilogue(sparse_conv_plan_t* plan, const sc_epilogue_t* ep,
+                                          const float* requant_scale, void* stream);
 
 /* Which implementation sparse_conv_forward runs for a plan. */
 enum {

@@ -29,7 +29,7 @@ SC_PATH_SPARSE, SC_PATH_DENSE, SC_PATH_LIBRARY = 0, 1, 2
 # every symbol include/sparse_conv.h declares
 EXPORTS = [
     "sparse_conv_plan_create_csr", "sparse_conv_plan_create_ell", "sparse_conv_plan_destroy",
-    "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning",
+    "sparse_conv_plan_info", "sparse_conv_plan_debug_offsets", "sparse_conv_plan_set_tuning", "sparse_conv_plan_set_epilogue",
     "sparse_conv_plan_get_tuning", "sparse_conv_workspace_size", "sparse_conv_workspace_size_max",
     "sparse_conv_forward", "sparse_conv_forward_static", "sparse_conv_plan_autotune", "sparse_conv_autotune_workspace_size", "sparse_conv_plan_dispatch", "sparse_conv_plan_set_path",
     "sparse_conv_plan_num_candidates",
@@ -71,7 +71,12 @@ class sc_plan_info_t(ctypes.Structure):
                 ("macs_per_sample", ctypes.c_int64), ("useful_macs_per_sample", ctypes.c_int64),
                 ("act_bytes_per_sample", ctypes.c_int64), ("weight_bytes", ctypes.c_int64),
                 ("lds_bytes", ctypes.c_int32), ("grid_size", ctypes.c_int32),
-                ("tuning", sc_tuning_t)]
+                ("tuning", sc_tuning_t), ("out_P", ctypes.c_int32), ("out_Q", ctypes.c_int32),
+                ("out_elem_bytes", ctypes.c_int32)]
+
+
+class sc_epilogue_t(ctypes.Structure):
+    _fields_ = [("relu", ctypes.c_int32), ("pool", ctypes.c_int32), ("requant", ctypes.c_int32)]
 
 
 class SparseConvError(RuntimeError):
@@ -106,6 +111,7 @@ def lib() -> ctypes.CDLL:
     L.sparse_conv_plan_debug_offsets.argtypes = [vp, vp]
     L.sparse_conv_plan_set_tuning.argtypes = [vp, P(sc_tuning_t), vp]
     L.sparse_conv_plan_get_tuning.argtypes = [vp, P(sc_tuning_t)]
+    L.sparse_conv_plan_set_epilogue.argtypes = [vp, P(sc_epilogue_t), vp, vp]
     L.sparse_conv_workspace_size.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_workspace_size_max.argtypes = [vp, i32, P(sz)]
     L.sparse_conv_forward.argtypes = [vp, vp, vp, i32, vp, sz, vp]
@@ -230,6 +236,12 @@ class Plan:
             setattr(t, k, v)
         _check(lib().sparse_conv_plan_set_tuning(self._h, ctypes.byref(t), ctypes.c_void_p(stream)),
                "sparse_conv_plan_set_tuning")
+
+    def set_epilogue(self, relu: bool = False, pool: int = 0, requant_scale=None, stream: int = 0):
+        ep = sc_epilogue_t(int(bool(relu)), int(pool), int(requant_scale is not None))
+        rq = _host(requant_scale, np.float32)
+        _check(lib().sparse_conv_plan_set_epilogue(self._h, ctypes.byref(ep), _hp(rq), ctypes.c_void_p(stream)),
+               "sparse_conv_plan_set_epilogue")
 
     def workspace_size(self, N: int) -> int:
         b = ctypes.c_size_t()

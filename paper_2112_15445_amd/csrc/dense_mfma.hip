@@ -136,7 +136,13 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     if (nw > 8) return false;
     g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : (nw <= 4 ? 4 : 8));
     if (g.NW == 8 && g.MW == 4) return false;     // 32 accumulator blocks per wave: not instantiated
-    const int64_t lds = (int64_t)g.npos_s * g.pitch;
+    int64_t lds = (int64_t)g.npos_s * g.pitch;
+    if (has_epilogue(p)) {
+        // pooling windows must not straddle tiles; the accumulators are exchanged through LDS
+        if (p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
+        g.epi_pitch = (4 / g.WM) * g.NW * 16 + 1;
+        lds = std::max<int64_t>(lds, (int64_t)g.DB * g.epi_pitch * 4);
+    }
     if (lds > lds_budget || lds > kMaxLdsBytes) return false;
     g.lds_bytes = (int)((lds + 15) / 16 * 16);
     *out = g;
@@ -161,6 +167,9 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     a.S = p.L.S; a.RS = p.L.R * p.L.S; a.s_h = p.L.stride_h; a.s_w = p.L.stride_w; a.pad_h = p.L.pad_h; a.pad_w = p.L.pad_w;
     a.TP = g.TP; a.NS = g.NS; a.tiles_p = g.tiles_p; a.Hs = g.Hs; a.Ws = g.Ws; a.npos_s = g.npos_s; a.npos = g.npos;
     a.CC = g.CC; a.nchunks = g.nchunks; a.NCB = g.NCB; a.pitch = g.pitch; a.DB = g.DB; a.ndb = g.ndb;
+    a.epi = has_epilogue(p) ? 1 : 0; a.epi_relu = p.epi.relu; a.epi_pool = p.epi.pool; a.epi_pitch = g.epi_pitch;
+    a.Po = p.Po; a.Qo = p.Qo; a.requant = p.epi.requant ? p.d_requant : nullptr;
+    if ((int64_t)g.DB * g.NS * g.TP * p.Q >= (1 << 19)) return SC_ERR_UNSUPPORTED;
     // elements per staging load: the widest power of two (up to 16 bytes) that divides the row length
     // and the caller's pointer
     a.epv = 1;

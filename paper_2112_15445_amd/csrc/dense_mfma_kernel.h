@@ -30,6 +30,10 @@ struct MfmaArgs {
     int C, D, N, H, W, P, Q, S, RS, s_h, s_w, pad_h, pad_w;
     int TP, NS, tiles_p, Hs, Ws, npos_s, npos, CC, nchunks, NCB, pitch, DB, ndb, epv;
     float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q;
+    // fused epilogue (epi = 0: none): ReLU, 2 x 2 max-pooling, requantisation multipliers (or NULL),
+    // row pitch of the LDS exchange, extents of y
+    int epi, epi_relu, epi_pool, epi_pitch, Po, Qo;
+    const float* requant;
 };
 
 sc_status_t launch_mfma_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
@@ -284,6 +288,54 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
                 multiply(aq[u], bq[u & 1]);
             }
         }
+    }
+    if (a.epi) {
+        // ------------------------------------------------------------ fused epilogue: the waves
+        // put their accumulator blocks into LDS as [output channel][tile position] (the tile has
+        // been consumed), then every thread finishes elements of y: the maximum over its 2 x 2
+        // window (or the one value), ReLU, and the store -- as the layer's type or, requantised,
+        // as an 8-bit code.  The stores run along the rows of y.
+        using A = typename Types<DT>::A;
+        __syncthreads();
+        A* ex = reinterpret_cast<A*>(lds);
+#pragma unroll
+        for (int m = 0; m < MW; ++m)
+#pragma unroll
+            for (int i = 0; i < NW; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    ex[((wm * MW + m) * 16 + 4 * kg + j) * a.epi_pitch + (wn * NW + i) * 16 + n16] = acc[m][i][j];
+        __syncthreads();
+        const int pl = a.epi_pool ? 2 : 1;
+        const int TPo = a.TP / pl;                          // output rows of y per tile (TP is even, or the whole plane)
+        const int per_s = TPo * a.Qo, per_d = a.NS * per_s;
+        const int total = a.DB * per_d;
+        const float inv_per_d = 1.0f / (float)max(per_d, 1), inv_per_s = 1.0f / (float)max(per_s, 1), inv_Qo = 1.0f / (float)a.Qo;
+        const int prow0 = p0 / pl;
+        for (int t = tid; t < total; t += 256) {
+            const int dl = fdiv19(t, inv_per_d);
+            const int o = t - dl * per_d;
+            const int sm = fdiv19(o, inv_per_s);
+            const int r2 = o - sm * per_s;
+            const int tpo = fdiv19(r2, inv_Qo);
+            const int tqo = r2 - tpo * a.Qo;
+            const int d = db * a.DB + dl;
+            if (d >= a.D || b0 + sm >= a.N || prow0 + tpo >= a.Po) continue;
+            const A* src = ex + dl * a.epi_pitch + sm * (a.TP * a.Q) + (tpo * pl) * a.Q + tqo * pl;
+            A v = src[0];
+            if (a.epi_pool) v = max(max(src[0], src[1]), max(src[a.Q], src[a.Q + 1]));
+            if (a.epi_relu) v = max(v, A(0));
+            const int64_t off = (((int64_t)(b0 + sm) * a.D + d) * a.Po + prow0 + tpo) * a.Qo + tqo;
+            if constexpr (kIntActs<DT>) {
+                if (a.requant) {
+                    const float q = rintf(__int2float_rn(v) * a.requant[d]);
+                    reinterpret_cast<int8_t*>(y)[off] = (int8_t)(int)fminf(fmaxf(q, -127.0f), 127.0f);
+                    continue;
+                }
+            }
+            store_out(y + off, narrow<DT>(v));
+        }
+        return;
     }
     // ---------------------------------------------------------------- store: a lane holds, for its
     // position (column n16 of the block), the four output channels 4 * kg .. 4 * kg + 3 of each row block

@@ -10,6 +10,7 @@
 // tensor: when the layer has padding, a small pre-pass writes it into the caller's workspace first
 // (the paper feeds its kernel pre-padded inputs).
 #include <mutex>
+#include <type_traits>
 
 #include "sc_device.h"
 #include "sc_internal.h"
@@ -115,6 +116,76 @@ gather_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restri
     }
 }
 
+// The same gather with the layer's fused epilogue (ReLU, 2 x 2 max-pooling, requantisation): a thread
+// owns one element of y -- with pooling the four convolution outputs of its window, accumulated
+// side by side from the same (theta, lambda) reads -- and applies max / ReLU / the requantisation
+// multiplier of its channel before the one store.
+template <sc_dtype_t DT, bool POOL>
+__global__ void __launch_bounds__(256)
+gather_epi_kernel(const typename Types<DT>::X* __restrict__ xp, const void* __restrict__ theta,
+                  const int32_t* __restrict__ lam, const void* __restrict__ codebook, void* __restrict__ y,
+                  int64_t total_out, int D, int n, int Po, int Qo, int s_h, int s_w, int Wp, int64_t X_size,
+                  int relu, const float* __restrict__ requant)
+{
+    using A = typename Types<DT>::A;
+    using WL = typename Types<DT>::WL;
+    using Y = typename Types<DT>::Y;
+    __shared__ WL theta_s[kRowChunk];
+    __shared__ int32_t lam_s[kRowChunk];
+    __shared__ __attribute__((aligned(4))) unsigned char cb_s[32];
+    constexpr int NWIN = POOL ? 4 : 1;
+    const int d = blockIdx.y;
+    if constexpr (kCodebook<DT>) {
+        if (threadIdx.x < kCodebookBytes<DT>) cb_s[threadIdx.x] = static_cast<const unsigned char*>(codebook)[threadIdx.x];
+    }
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = g < total_out;
+    const int64_t gc = live ? g : 0;                  // (past the end: element 0 again, not stored)
+    const int PQo = Po * Qo;
+    const int64_t b = gc / PQo;
+    const int f = (int)(gc - b * PQo);
+    const int pp = f / Qo, qq = f - pp * Qo;
+    const typename Types<DT>::X* xs[NWIN];
+    A acc[NWIN];
+#pragma unroll
+    for (int w = 0; w < NWIN; ++w) {
+        const int p = POOL ? 2 * pp + (w >> 1) : pp, q = POOL ? 2 * qq + (w & 1) : qq;
+        xs[w] = xp + b * X_size + (int64_t)p * s_h * Wp + q * s_w;
+        acc[w] = A(0);
+    }
+    for (int j0 = 0; j0 < n; j0 += kRowChunk) {
+        const int jc = min(kRowChunk, n - j0);
+        __syncthreads();
+        for (int j = threadIdx.x; j < jc; j += 256) {
+            const int64_t i = (int64_t)d * n + j0 + j;
+            const int l = lam[i];
+            theta_s[j] = load_weight<DT>(theta, i, l, cb_s);
+            lam_s[j] = l & 0x7fffffff;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int j = 0; j < jc; ++j) {
+            const WL wgt = theta_s[j];
+            const int l = lam_s[j];
+#pragma unroll
+            for (int w = 0; w < NWIN; ++w) mac1<DT>(acc[w], wgt, xs[w][l]);
+        }
+    }
+    A v = acc[0];
+    if constexpr (POOL) v = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
+    if (relu) v = max(v, A(0));
+    if (!live) return;
+    const int64_t off = (b * D + d) * (int64_t)PQo + f;
+    if constexpr (std::is_same<A, int32_t>::value) {
+        if (requant) {
+            const float r = rintf(__int2float_rn(v) * requant[d]);
+            static_cast<int8_t*>(y)[off] = (int8_t)(int)fminf(fmaxf(r, -127.0f), 127.0f);
+            return;
+        }
+    }
+    store_out(static_cast<Y*>(y) + off, narrow<DT>(v));
+}
+
 size_t gather_workspace_bytes(const Plan& p, int N)
 {
     if (p.L.pad_h == 0 && p.L.pad_w == 0) return 0;
@@ -159,6 +230,22 @@ static sc_status_t launch_gather_t(const Plan& p, const void* x, void* y, int N,
         hipLaunchKernelGGL(pad_input_kernel<X>, dim3(blocks), dim3(256), 0, stream, xp,
                            static_cast<X*>(ws), total, p.L.H, p.L.W, p.Hp, p.Wp, p.L.pad_h, p.L.pad_w);
         xp = static_cast<const X*>(ws);
+    }
+    if (has_epilogue(p)) {
+        if (p.tuning.split_n != 1) return SC_ERR_UNSUPPORTED;
+        const int64_t total_out = (int64_t)N * p.Po * p.Qo;
+        const int64_t gx = (total_out + 255) / 256;
+        if (gx >= (1ll << 31) || p.L.D > 65535) return SC_ERR_UNSUPPORTED;
+        dim3 grid((unsigned)gx, p.L.D, 1);
+        if (p.epi.pool)
+            hipLaunchKernelGGL((gather_epi_kernel<DT, true>), grid, dim3(256), 0, stream, xp, p.d_theta, p.d_lam, p.d_codebook, y,
+                               total_out, p.L.D, p.n, p.Po, p.Qo, p.L.stride_h, p.L.stride_w, p.Wp, p.X_size, p.epi.relu,
+                               p.epi.requant ? p.d_requant : nullptr);
+        else
+            hipLaunchKernelGGL((gather_epi_kernel<DT, false>), grid, dim3(256), 0, stream, xp, p.d_theta, p.d_lam, p.d_codebook, y,
+                               total_out, p.L.D, p.n, p.Po, p.Qo, p.L.stride_h, p.L.stride_w, p.Wp, p.X_size, p.epi.relu,
+                               p.epi.requant ? p.d_requant : nullptr);
+        return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
     }
     const int64_t total = (int64_t)N * p.P * p.Q;
     const int vpt = p.tuning.sub_batch, ns = p.tuning.split_n;

@@ -309,7 +309,9 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.chunk_c == 0) t.ragged = 0;
     if (t.pack < 0 || t.pack > 3) return SC_ERR_UNSUPPORTED;
     if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
-    const bool want_slab = t.variant != SC_VARIANT_GATHER;
+    // (a fused epilogue lives in the GATHER and DENSE kernels only)
+    if (has_epilogue(p) && t.variant == SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
+    const bool want_slab = t.variant != SC_VARIANT_GATHER && !has_epilogue(p);
     if (want_slab) {
         const bool pw = is_pointwise(L);
         if (t.wg_per_cu == 0) t.wg_per_cu = t.pipeline >= 1 ? 1 : 2;
@@ -361,6 +363,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.split_n == 0) t.split_n = 1;
     if (t.split_n != 1 && t.split_n != 4 && t.split_n != 16 && t.split_n != 64)
         return SC_ERR_UNSUPPORTED;
+    if (has_epilogue(p) && t.split_n != 1) return SC_ERR_UNSUPPORTED;
     t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = t.ragged = 0;
     if (t.pack) return SC_ERR_UNSUPPORTED;
     *out = t;
@@ -394,6 +397,8 @@ static sc_status_t validate_layer(const sc_layer_t* L, sc_dtype_t dt, const floa
     p->Wp = (int)Wp;
     p->P = (int)P;
     p->Q = (int)Q;
+    p->Po = (int)P;
+    p->Qo = (int)Q;
     p->X_size = X_size;
     p->ex = elem_size_x(dt);
     p->ey = elem_size_y(dt);
@@ -462,6 +467,8 @@ static void free_device(Plan* p)
     p->d_seg_off = p->d_first_j = nullptr;
     if (p->d_scales) (void)hipFree(p->d_scales);
     if (p->d_codebook) (void)hipFree(p->d_codebook);
+    if (p->d_requant) (void)hipFree(p->d_requant);
+    p->d_requant = nullptr;
     if (p->d_wfrag) (void)hipFree(p->d_wfrag);
     if (p->d_len) (void)hipFree(p->d_len);
     p->d_wfrag = nullptr;
@@ -822,6 +829,9 @@ sc_status_t sparse_conv_plan_info(const sparse_conv_plan_t* plan, sc_plan_info_t
     if (p->d_scales) wb += (int64_t)p->L.D * 4;
     info->weight_bytes = wb;
     info->tuning = p->tuning;
+    info->out_P = p->Po;
+    info->out_Q = p->Qo;
+    info->out_elem_bytes = p->epi.requant ? 1 : p->ey;
     if (p->tuning.variant == SC_VARIANT_SLAB) {
         info->lds_bytes = p->geom.lds_bytes;
         info->grid_size = p->last_N ? slab_grid_size(*p, p->geom, p->last_N) : 0;
@@ -859,6 +869,47 @@ sc_status_t sparse_conv_plan_set_tuning(sparse_conv_plan_t* plan, const sc_tunin
     st = install_tuning(p, t, g, mg, (hipStream_t)stream);
     if (st == SC_OK) p->path = t.variant == SC_VARIANT_DENSE ? SC_PATH_DENSE : SC_PATH_SPARSE;
     return st;
+}
+
+sc_status_t sparse_conv_plan_set_epilogue(sparse_conv_plan_t* plan, const sc_epilogue_t* ep, const float* requant_scale, void* stream)
+{
+    if (!plan || !ep) return SC_ERR_NULL;
+    Plan* p = reinterpret_cast<Plan*>(plan);
+    if ((ep->relu != 0 && ep->relu != 1) || (ep->pool != 0 && ep->pool != 2) || (ep->requant != 0 && ep->requant != 1))
+        return SC_ERR_UNSUPPORTED;
+    if (ep->requant && ((p->dtype != SC_I8 && p->dtype != SC_CB4_I8) || !requant_scale)) return SC_ERR_UNSUPPORTED;
+    if (ep->pool && (p->P < 2 || p->Q < 2)) return SC_ERR_UNSUPPORTED;
+    float* d_rq = nullptr;
+    if (ep->requant) {
+        hipError_t e;
+        if ((e = hipMalloc((void**)&d_rq, (size_t)p->L.D * 4)) != hipSuccess) return hip_status(e);
+        if (hipMemcpy(d_rq, requant_scale, (size_t)p->L.D * 4, hipMemcpyHostToDevice) != hipSuccess) { (void)hipFree(d_rq); return SC_ERR_HIP; }
+    }
+    const sc_epilogue_t old_epi = p->epi;
+    const int old_Po = p->Po, old_Qo = p->Qo;
+    float* old_rq = p->d_requant;
+    p->epi = *ep;
+    p->d_requant = d_rq;
+    p->Po = ep->pool ? p->P / 2 : p->P;
+    p->Qo = ep->pool ? p->Q / 2 : p->Q;
+    // the installed launch shape may not carry an epilogue (SLAB) or not this one (DENSE with an odd
+    // tile under pooling): re-resolve it, falling back to the GATHER default
+    sc_status_t st = sparse_conv_plan_set_tuning(plan, &p->tuning, stream);
+    if (st == SC_ERR_UNSUPPORTED) {
+        sc_tuning_t g{};
+        g.variant = SC_VARIANT_GATHER;
+        g.split_n = 1;
+        st = sparse_conv_plan_set_tuning(plan, &g, stream);
+    }
+    if (st != SC_OK) {
+        p->epi = old_epi; p->d_requant = old_rq; p->Po = old_Po; p->Qo = old_Qo;
+        if (d_rq) (void)hipFree(d_rq);
+        return st;
+    }
+    if (old_rq) (void)hipFree(old_rq);
+    if (p->libconv) { library_conv_destroy(p->libconv); p->libconv = nullptr; }
+    p->dispatch.choice = -1;
+    return SC_OK;
 }
 
 sc_status_t sparse_conv_plan_get_tuning(const sparse_conv_plan_t* plan, sc_tuning_t* tuning)
@@ -1416,7 +1467,7 @@ sc_status_t sparse_conv_plan_dispatch(sparse_conv_plan_t* plan, const void* x_de
     // leg 3: the dense library on the same buffers, in the same regime as the other two: launches
     // back to back over the caller's pair after a warm-up
     if (p->libconv) { library_conv_destroy(p->libconv); p->libconv = nullptr; }
-    st = library_conv_create(*p, x_dev, y_dev, N, s, &p->libconv);
+    st = has_epilogue(*p) ? SC_ERR_UNSUPPORTED : library_conv_create(*p, x_dev, y_dev, N, s, &p->libconv);
     if (st == SC_OK) {
         const size_t lws = library_conv_workspace(p->libconv);
         void* d_ws = nullptr;

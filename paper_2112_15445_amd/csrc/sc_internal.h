@@ -65,6 +65,7 @@ struct MfmaGeom {
     int DB, ndb;           // output channels per workgroup, blocks of them
     int WM, MW, NW;        // waves along the output channels; 16-row / 16-column blocks per wave
     int lds_bytes;
+    int epi_pitch;         // elements per output-channel row of the LDS exchange of the fused epilogue
 };
 
 struct LibraryConv;   // dense_library.hip: the dense library's convolution of this layer (per-layer dispatch)
@@ -95,6 +96,9 @@ struct Plan {
     unsigned char* d_wfrag = nullptr;  // dense weights in MFMA operand order (DENSE variant), built on first use
     int32_t* d_len = nullptr;       // [D] stored entries of every row before unification (device copy of h_len)
     bool has_dup = false;           // some row stores a column twice (such a table cannot be densified exactly)
+    sc_epilogue_t epi{};            // fused epilogue (all zero: none)
+    float* d_requant = nullptr;     // [D] requantisation multipliers (epi.requant)
+    int Po = 0, Qo = 0;             // extents of y: (P, Q), halved when the epilogue pools
     LibraryConv* libconv = nullptr; // set by sparse_conv_plan_dispatch when it measured the dense library
     int path = 0;                   // SC_PATH_*: which implementation sparse_conv_forward runs
     sc_dispatch_t dispatch{};       // the last record of sparse_conv_plan_dispatch (choice -1 before the first)
@@ -138,6 +142,7 @@ int mfma_chan_block(sc_dtype_t dt);
 size_t mfma_weight_bytes(const Plan& p);
 sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream);
 bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out);
+inline bool has_epilogue(const Plan& p) { return p.epi.relu || p.epi.pool || p.epi.requant; }
 int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N);
 sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 

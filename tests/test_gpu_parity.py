@@ -937,3 +937,113 @@ def test_per_layer_dispatch_records_three_contenders_and_forward_honours_the_cho
         else:
             G.check(l, run(), ref, f"dispatch {dtype}: path {path}")
     plan.destroy()
+
+
+def _run_epi(plan, l, x, out_np_dtype):
+    import torch
+    inf = plan.info()
+    xd = G.to_device(np.ascontiguousarray(x))
+    tdt = {np.int8: torch.int8, np.int32: torch.int32, np.float16: torch.float16, np.float32: torch.float32}[out_np_dtype]
+    y = torch.empty((x.shape[0], l.D, inf.out_P, inf.out_Q), dtype=tdt, device="cuda")
+    y.view(torch.uint8).fill_(0x7f)
+    assert inf.out_elem_bytes == y.element_size()
+    need = plan.workspace_size(x.shape[0])
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    plan.forward(xd.data_ptr(), y.data_ptr(), x.shape[0], ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return G.to_host(y)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_fused_epilogue_relu_pool_requantise(dtype):
+    """ReLU / 2x2 max-pool / requantisation fused into the store of the GATHER and DENSE kernels,
+    against the oracle's epilogue applied to the oracle's accumulators; requantised codes bit-exact."""
+    import oracle
+    shapes = [("even", 20, 24, 8, 12, 3, 3, 1, 1, 1, 1, 5, 0.6),
+              ("odd_plane", 40, 36, 7, 9, 3, 3, 1, 1, 1, 1, 3, 0.7),
+              ("pointwise", 70, 18, 6, 6, 1, 1, 1, 1, 0, 0, 4, 0.5),
+              ("stride2", 12, 20, 13, 11, 3, 3, 2, 2, 1, 1, 2, 0.5),
+              ("tiny", 96, 33, 2, 2, 3, 3, 1, 1, 1, 1, 9, 0.9)]
+    integer = dtype in ("i8", "cb4")
+    rng = np.random.default_rng(3)
+    for name, C, D, H, W, R, S, sh, sw, ph, pw, N, sp in shapes:
+        l = wl.Layer(name, C, D, H, W, R, S, sh, sw, ph, pw, N=N, sparsity=sp, dtype=dtype, seed=123)
+        data = wl.prepare(l)
+        acc = oracle.sparse_conv_steps(data["x"], data["rowptr"], data["colidx"], data["values"], R, S, (sh, sw), (ph, pw),
+                                       codebook=data["codebook"])["y"]
+        plan = G.make_plan(l, data)
+        # multipliers that spread the codes over the int8 range
+        rq = (100.0 / max(1.0, float(np.abs(acc).max())) * (0.5 + rng.random(D))).astype(np.float32)
+        for relu, pool, requant in ((1, 0, 0), (0, 2, 0), (1, 2, 0), (1, 2, 1), (0, 0, 1), (1, 0, 1)):
+            if requant and not integer:
+                with pytest.raises(B.SparseConvError) as e:
+                    plan.set_epilogue(relu=relu, pool=pool, requant_scale=rq)
+                assert e.value.status == 4
+                continue
+            plan.set_epilogue(relu=relu, pool=pool, requant_scale=rq if requant else None)
+            out_dt = np.int8 if requant else G.NP_OUT[dtype]
+            ref = oracle.epilogue(acc, relu=bool(relu), pool=pool, requant_scale=rq if requant else None,
+                                  out_dtype=None if requant else G.NP_OUT[dtype])
+            with pytest.raises(B.SparseConvError) as e:
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=0)      # no epilogue in the slab kernels
+            assert e.value.status == 4
+            ran = 0
+            for variant, extra in ((B.SC_VARIANT_GATHER, {}), (B.SC_VARIANT_GATHER, {"sub_batch": 2}),
+                                   (B.SC_VARIANT_DENSE, {}), (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2}),
+                                   (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2}),
+                                   (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 4, "waves_m": 4, "chunk_c": 64})):
+                try:
+                    plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
+                except B.SparseConvError as e:
+                    assert e.status == 4
+                    continue
+                print("case epilogue", name, dtype, (relu, pool, requant), variant, extra, flush=True)
+                got = _run_epi(plan, l, data["x"], out_dt)
+                assert got.shape == ref.shape, (got.shape, ref.shape)
+                if requant or integer:
+                    assert np.array_equal(got, ref), (name, relu, pool, requant, variant, extra, np.count_nonzero(got != ref))
+                else:
+                    G.check(l, got, ref, f"{name} epilogue {(relu, pool)} {variant} {extra}")
+                ran += 1
+            assert ran >= 2 if dtype != "f32" else ran >= 1
+        plan.set_epilogue()                                      # and back to the plain convolution
+        G.check(l, G.run_gpu(plan, data["x"]), G.oracle_out(l, data), f"{name} epilogue removed")
+        plan.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["i8", "cb4"])
+def test_quantised_vgg_stack_chains_through_the_fused_epilogue(dtype):
+    """The VGG-16-shaped stack at batch 4 as ONE chain: every layer's int8 output (ReLU, max-pool at
+    the end of a stage, requantisation) is the next layer's input, on the GPU through the DENSE
+    kernel (first layer: GATHER) and in the oracle; the codes agree bit for bit after 13 layers."""
+    import oracle
+    import torch
+    layers = [l.replace(N=4) for l in wl.config5() if (l.dtype == dtype)]
+    assert len(layers) == 13
+    x_ref = wl.prepare(layers[0])["x"]
+    x_gpu = G.to_device(x_ref)
+    for k, l in enumerate(layers):
+        data = wl.prepare(l)
+        pool = 2 if (k + 1 < len(layers) and layers[k + 1].H * 2 == l.H) else 0
+        acc = oracle.sparse_conv_steps(x_ref, data["rowptr"], data["colidx"], data["values"], l.R, l.S,
+                                       (l.stride_h, l.stride_w), (l.pad_h, l.pad_w), codebook=data["codebook"])["y"]
+        post = oracle.epilogue(acc, relu=True, pool=pool)
+        rq = np.full(l.D, 120.0 / max(1.0, float(post.max())), dtype=np.float32)
+        x_next_ref = oracle.epilogue(acc, relu=True, pool=pool, requant_scale=rq)
+        plan = G.make_plan(l, data)
+        plan.set_epilogue(relu=True, pool=pool, requant_scale=rq)
+        try:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE)
+        except B.SparseConvError:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_GATHER)
+        inf = plan.info()
+        y = torch.empty((l.N, l.D, inf.out_P, inf.out_Q), dtype=torch.int8, device="cuda")
+        ws = torch.empty(max(plan.workspace_size(l.N), 16), dtype=torch.uint8, device="cuda")
+        plan.forward(x_gpu.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        print("case chain", dtype, k, l.name, "variant", plan.get_tuning().variant, "pool", pool, got.shape, flush=True)
+        assert np.array_equal(got, x_next_ref), (k, l.name, np.count_nonzero(got != x_next_ref))
+        assert np.count_nonzero(got) > 0
+        x_ref, x_gpu = x_next_ref, y
+        plan.destroy()
