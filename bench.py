@@ -271,6 +271,11 @@ def main():
     ap.add_argument("--report", default=None, help="also time every layer of all configs -> JSON file")
     ap.add_argument("--report-configs", default="1,2,3,4,5,6,7",
                     help="with --report: the workload configurations to cover (comma-separated)")
+    ap.add_argument("--table", nargs="+", default=None, metavar="REPORT.json",
+                    help="no GPU work: merge saved --report files and print the per-layer table")
+    ap.add_argument("--write-tunings", default=None, metavar="OUT.json",
+                    help="with --table: also write the recorded per-layer choices ({config, layer, dtype, path, tuning} "
+                         "rows, the data of tests/test_gpu_recorded_tunings.py and of --tunings)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark, run 20 plain 256 MiB device copies (the known-size "
                          "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled against)")
@@ -278,6 +283,16 @@ def main():
                     help="instead of the benchmark, time a few layers whose rows have uneven lengths with the "
                          "unified table and with the ragged one (tuning.ragged), same launch shape")
     args = ap.parse_args()
+    if args.table:
+        rows = [r for f in args.table for r in json.load(open(f))]
+        rows.sort(key=lambda r: r["config"])           # stable: layers keep their order inside a configuration
+        sys.stdout.write(report_table(rows))
+        if args.write_tunings:
+            rec = [{"config": r["config"], "layer": r["layer"], "dtype": r["dtype"], "path": r.get("path", "sparse"),
+                    "tuning": {k: v for k, v in r["tuning"].items() if v}} for r in rows]
+            with open(args.write_tunings, "w") as f:
+                f.write("[\n" + ",\n".join(" " + json.dumps(x) for x in rec) + "\n]\n")
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path would shard over the batch with "
               "no exchange step); --gpus must be 1", file=sys.stderr)
@@ -466,8 +481,10 @@ def report_table(rows):
         if not all(legs(r)[0] for r in rs):
             continue
         sp = sum(legs(r)[0] for r in rs) * 1e3
-        ch = sum(r["ms_events"] for r in rs) * 1e3
-        txt = f"# config {cfg}: sum over {len(rs)} layers: gather kernels only {sp:.1f} us, per-layer choice {ch:.1f} us"
+        ch = sum(min(v for v in legs(r) if v) for r in rs) * 1e3
+        timed = sum(r["ms_events"] for r in rs) * 1e3
+        txt = (f"# config {cfg}: sum over {len(rs)} layers: gather kernels only {sp:.1f} us, per-layer choice {ch:.1f} us "
+               f"(both as timed inside the dispatch; the installed choices timed again over the ring: {timed:.1f} us)")
         if all(torch_dense(r) for r in rs):
             txt += f", dense library (torch) only {sum(torch_dense(r) for r in rs) * 1e3:.1f} us"
         out.append(txt)

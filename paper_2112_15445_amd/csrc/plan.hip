@@ -1176,12 +1176,14 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     // 16- and 8-bit activations: the chunked one-shot form with packed positions (one LDS read per
     // 2 or 4 positions), tiles of up to 8 positions per lane
     if ((packable || wide) && p.n > 0) {
-        for (int wpc : {1, 2, 3}) for (int cc : {16, 32, 64, 128, 256, 384, 512}) {
+        for (int wpc : {1, 2, 3}) for (int cc : {16, 24, 32, 48, 64, 96, 128, 256, 384, 512}) {
+            const bool odd_cc = cc == 24 || cc == 48 || cc == 96;    // with interleaved samples only
             if ((cc > p.L.C && cc != 16) || (cc > 256 && wpc > 1)) continue;
             for (int td : {0, 16, 32, 64, 128}) {   // (16: with interleaved samples only -- enough workgroups on small layers)
                 if (td >= p.L.D && td != 0) continue;
                 for (int tile : {1, 2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2, 3}) {
                     if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3) || (td == 16 && pk != 3)) continue;
+                    if (odd_cc && pk != 3) continue;
                     sc_tuning_t t{};
                     t.variant = SC_VARIANT_SLAB;
                     t.wsrc = 1;
@@ -1193,6 +1195,9 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_d = td;
                     t.pack = pk;
                     push(t);
+                    // (twelve waves: two such workgroups share a CU where the registers allow, one
+                    // staging while the other multiplies)
+                    if (pk == 3 && p.dtype == SC_F32) { t.wg_threads = 768; push(t); }
                 }
             }
         }
