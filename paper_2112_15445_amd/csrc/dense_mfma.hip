@@ -137,9 +137,9 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : (nw <= 4 ? 4 : 8));
     if (g.NW == 8 && g.MW == 4) return false;     // 32 accumulator blocks per wave: not instantiated
     int64_t lds = (int64_t)g.npos_s * g.pitch;
-    if (has_epilogue(p)) {
+    if (has_epilogue(p) && p.epi.pool) {
         // pooling windows must not straddle tiles; the accumulators are exchanged through LDS
-        if (p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
+        if (g.TP < p.P && (g.TP & 1)) return false;
         g.epi_pitch = (4 / g.WM) * g.NW * 16 + 1;
         lds = std::max<int64_t>(lds, (int64_t)g.DB * g.epi_pitch * 4);
     }

@@ -289,12 +289,13 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
             }
         }
     }
-    if (a.epi) {
-        // ------------------------------------------------------------ fused epilogue: the waves
+    if (a.epi_pool) {
+        // ------------------------------------------------------------ fused epilogue with pooling: the waves
         // put their accumulator blocks into LDS as [output channel][tile position] (the tile has
         // been consumed), then every thread finishes elements of y: the maximum over its 2 x 2
-        // window (or the one value), ReLU, and the store -- as the layer's type or, requantised,
-        // as an 8-bit code.  The stores run along the rows of y.
+        // window, ReLU, and the store -- as the layer's type or, requantised, as an 8-bit code.
+        // The stores run along the rows of y.  (Without pooling the epilogue is elementwise and is
+        // applied where the accumulators are stored, below.)
         using A = typename Types<DT>::A;
         __syncthreads();
         A* ex = reinterpret_cast<A*>(lds);
@@ -308,46 +309,89 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         __syncthreads();
         const int pl = a.epi_pool ? 2 : 1;
         const int TPo = a.TP / pl;                          // output rows of y per tile (TP is even, or the whole plane)
-        const int per_s = TPo * a.Qo, per_d = a.NS * per_s;
-        const int total = a.DB * per_d;
-        const float inv_per_d = 1.0f / (float)max(per_d, 1), inv_per_s = 1.0f / (float)max(per_s, 1), inv_Qo = 1.0f / (float)a.Qo;
+        const int per_s = TPo * a.Qo, per_d = a.NS * per_s; // elements of y per output channel of the tile
+        const float inv_per_s = 1.0f / (float)max(per_s, 1), inv_Qo = 1.0f / (float)a.Qo;
         const int prow0 = p0 / pl;
-        for (int t = tid; t < total; t += 256) {
-            const int dl = fdiv19(t, inv_per_d);
-            const int o = t - dl * per_d;
+        // a thread keeps to one element position of the tile (decoded once) and walks over the
+        // output channels; the 256 threads are laid out as (channel group, position) with the
+        // positions a power of two wide, so that small tiles still use every thread and the
+        // stores of a wave run along the rows of y
+        int pw2 = 1;
+        while (pw2 < per_d && pw2 < 256) pw2 <<= 1;
+        const int dgroups = 256 / pw2;
+        const int o_first = tid & (pw2 - 1), dg = tid / pw2;
+        for (int o = o_first; o < per_d; o += pw2) {
             const int sm = fdiv19(o, inv_per_s);
             const int r2 = o - sm * per_s;
             const int tpo = fdiv19(r2, inv_Qo);
             const int tqo = r2 - tpo * a.Qo;
-            const int d = db * a.DB + dl;
-            if (d >= a.D || b0 + sm >= a.N || prow0 + tpo >= a.Po) continue;
-            const A* src = ex + dl * a.epi_pitch + sm * (a.TP * a.Q) + (tpo * pl) * a.Q + tqo * pl;
-            A v = src[0];
-            if (a.epi_pool) v = max(max(src[0], src[1]), max(src[a.Q], src[a.Q + 1]));
-            if (a.epi_relu) v = max(v, A(0));
-            const int64_t off = (((int64_t)(b0 + sm) * a.D + d) * a.Po + prow0 + tpo) * a.Qo + tqo;
-            if constexpr (kIntActs<DT>) {
-                if (a.requant) {
-                    const float q = rintf(__int2float_rn(v) * a.requant[d]);
-                    reinterpret_cast<int8_t*>(y)[off] = (int8_t)(int)fminf(fmaxf(q, -127.0f), 127.0f);
-                    continue;
+            if (b0 + sm >= a.N || prow0 + tpo >= a.Po) continue;
+            const A* src = ex + sm * (a.TP * a.Q) + (tpo * pl) * a.Q + tqo * pl;
+            const int64_t off0 = (((int64_t)(b0 + sm) * a.D) * a.Po + prow0 + tpo) * a.Qo + tqo;
+            const int64_t dstride = (int64_t)a.Po * a.Qo;
+            for (int dl = dg; dl < a.DB; dl += dgroups) {
+                const int d = db * a.DB + dl;
+                if (d >= a.D) break;
+                const A* sp = src + dl * a.epi_pitch;
+                A v = sp[0];
+                if (a.epi_pool) v = max(max(sp[0], sp[1]), max(sp[a.Q], sp[a.Q + 1]));
+                if (a.epi_relu) v = max(v, A(0));
+                const int64_t off = off0 + d * dstride;
+                if constexpr (kIntActs<DT>) {
+                    if (a.requant) {
+                        const float q = rintf(__int2float_rn(v) * a.requant[d]);
+                        reinterpret_cast<int8_t*>(y)[off] = (int8_t)(int)fminf(fmaxf(q, -127.0f), 127.0f);
+                        continue;
+                    }
                 }
+                store_out(y + off, narrow<DT>(v));
             }
-            store_out(y + off, narrow<DT>(v));
         }
         return;
     }
     // ---------------------------------------------------------------- store: a lane holds, for its
     // position (column n16 of the block), the four output channels 4 * kg .. 4 * kg + 3 of each row block
+    if (!a.epi) {
+#pragma unroll
+        for (int m = 0; m < MW; ++m) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int d = (mblk0 + m) * 16 + 4 * kg + j;
+                if (d < a.D) {
+#pragma unroll
+                    for (int i = 0; i < NW; ++i)
+                        if (yoff[i] >= 0) store_out(y + yoff[i] + (int64_t)d * PQ, narrow<DT>(acc[m][i][j]));
+                }
+            }
+        }
+        return;
+    }
+    // the same with an elementwise epilogue: ReLU and / or requantisation to 8-bit codes on the way
+    // (a branch of its own, so that the plain store above keeps its registers and schedule)
 #pragma unroll
     for (int m = 0; m < MW; ++m) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int d = (mblk0 + m) * 16 + 4 * kg + j;
             if (d < a.D) {
+                float rq = 0.0f;
+                if constexpr (kIntActs<DT>) {
+                    if (a.requant) rq = a.requant[d];
+                }
 #pragma unroll
-                for (int i = 0; i < NW; ++i)
-                    if (yoff[i] >= 0) store_out(y + yoff[i] + (int64_t)d * PQ, narrow<DT>(acc[m][i][j]));
+                for (int i = 0; i < NW; ++i) {
+                    if (yoff[i] < 0) continue;
+                    auto v = acc[m][i][j];
+                    if (a.epi_relu) v = max(v, decltype(v)(0));
+                    if constexpr (kIntActs<DT>) {
+                        if (a.requant) {
+                            const float q = rintf(__int2float_rn(v) * rq);
+                            reinterpret_cast<int8_t*>(y)[yoff[i] + (int64_t)d * PQ] = (int8_t)(int)fminf(fmaxf(q, -127.0f), 127.0f);
+                            continue;
+                        }
+                    }
+                    store_out(y + yoff[i] + (int64_t)d * PQ, narrow<DT>(v));
+                }
             }
         }
     }

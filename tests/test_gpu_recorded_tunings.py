@@ -35,12 +35,20 @@ def test_recorded_tuning_at_full_batch(row):
     plan.set_tuning(B.sc_tuning_t(), **row["tuning"])
     got = {k: v for k, v in plan.get_tuning().as_dict().items() if v}
     assert got == row["tuning"], (got, row["tuning"])        # installed exactly as recorded
-    tol = None
+    tol, x_dev = None, None
     if row.get("path") == "library":
-        # the dense library chooses its own algorithm and summation order: fp32 layers are held to
-        # 1e-3 of the output scale there, the other types to the tolerance of the own kernels
+        # the library leg exists once the dispatch has measured it on real buffers; then the recorded
+        # shape and path are installed over whatever that run chose.  The dense library chooses its
+        # own algorithm and summation order: fp32 layers are held to 1e-3 of the output scale there
+        import numpy as np
+        import torch
+        x_dev = G.to_device(np.ascontiguousarray(data["x"]))
+        inf = plan.info()
+        y = torch.empty((l.N, l.D, inf.P, inf.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
+        plan.dispatch(x_dev.data_ptr(), y.data_ptr(), l.N, 0, 0, torch.cuda.current_stream().cuda_stream)
+        plan.set_tuning(B.sc_tuning_t(), **row["tuning"])
         plan.set_path(B.SC_PATH_LIBRARY)
         tol = 1e-3 if l.dtype == "f32" else None
-    res = G.full_batch_parity(l, data, plan, tol=tol)
+    res = G.full_batch_parity(l, data, plan, x_dev=x_dev, tol=tol)
     plan.destroy()
     assert res["ok"], res
