@@ -418,6 +418,8 @@ def short_shape(t):
         sh += f" pl{t['pipeline']}"
     if t.get("producers"):
         sh += f" np{t['producers']}"
+    if t.get("buffers"):
+        sh += f" nb{t['buffers']}"
     sh += f" tp{t.get('tile_p', 1)} tq{t.get('tile_q', 0)} thr{t.get('wg_threads')} wpc{t.get('wg_per_cu', 1)} ws{t.get('wsrc', 0)}"
     if t.get("chunk_c"):
         sh += f" cc{t['chunk_c']} td{t.get('tile_d', 0)}"

@@ -157,6 +157,11 @@ typedef struct {
     int32_t waves_m;    /* DENSE: how many of the workgroup's four waves lie along the output channels
                            (1, 2 or 4; the others along the positions).  A wave then owns tile_d / waves_m
                            output channels (16, 32 or 64) and up to 128 positions.  0 = heuristic */
+    int32_t buffers;    /* SLAB with pipeline = 1 and chunk_c > 0: LDS chunk buffers.  0 (or 2) = two, the
+                           producer waves share the copy of every chunk; 3 .. 5 = producers + 1 buffers
+                           (producers is set to match when 0): every producer wave copies whole chunks by
+                           itself, so that as many chunks as there are producers are in flight while one
+                           is multiplied -- the memory latency of a chunk is spread over several phases */
 } sc_tuning_t;
 
 typedef struct {

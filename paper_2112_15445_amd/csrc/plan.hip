@@ -72,7 +72,7 @@ static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Derive the slab geometry for tile (TP, TQ); returns false if it cannot run.
 static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsrc, int pipeline, int producers,
-                          int chunk_c, int tile_d, int samples, int pack, int lds_budget, SlabGeom* g)
+                          int chunk_c, int tile_d, int samples, int pack, int lds_budget, SlabGeom* g, int buffers = 0)
 {
     const sc_layer_t& L = p.L;
     SlabGeom o{};
@@ -193,11 +193,19 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     // behind the weight stage and the codebook (full-channel form)
     o.lds_bytes = o.slab_bytes + o.wcap * 8 + 64 + round_up(o.chan_pitch * 4, 16);
     if (pipeline == 0 && chunk_c > 0) o.lds_bytes = o.slab_bytes + round_up(o.chan_pitch * 4, 16) + 64;
+    o.nbuf = 2;
     if (pipeline == 1) {
         // two tile buffers, no weight stage; only for pointwise layers whose rows can be copied
         // 16 bytes at a time, and the workgroup needs consumer waves besides the producers
+        // (with channel chunks: optionally producers + 1 buffers, a producer wave per chunk in flight)
         if (!pw || wsrc == 0 || o.nwaves < 8) return false;
-        o.lds_bytes = 2 * o.slab_bytes;
+        if (buffers > 2) {
+            if (chunk_c <= 0 || buffers != producers + 1 || buffers > 5) return false;
+            o.nbuf = buffers;
+        }
+        o.lds_bytes = o.nbuf * o.slab_bytes;
+    } else if (buffers > 2) {
+        return false;
     }
     // (a caller whose x is not aligned for the direct-to-LDS copies is served by the one-shot kernel
     // with this same allocation: it must also hold that kernel's tile plus its offset table)
@@ -236,7 +244,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu == 0) t.wg_per_cu = 2;
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
     const int budget = kMaxLdsBytes / t.wg_per_cu;
     const int CB = mfma_chan_block(p.dtype);
     if (t.waves_m != 0 && t.waves_m != 1 && t.waves_m != 2 && t.waves_m != 4) return SC_ERR_UNSUPPORTED;
@@ -301,6 +309,12 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.wsrc < 0 || t.wsrc > 3) return SC_ERR_UNSUPPORTED;
     if (t.wsrc != 0 && is_codebook(p.dtype)) return SC_ERR_UNSUPPORTED;  // indices are decoded in LDS
     if (t.pipeline < 0 || t.pipeline > 2) return SC_ERR_UNSUPPORTED;
+    if (t.buffers < 0 || t.buffers == 1 || t.buffers > 5) return SC_ERR_UNSUPPORTED;
+    if (t.buffers == 2) t.buffers = 0;
+    if (t.buffers > 2) {
+        if (t.pipeline != 1 || t.chunk_c <= 0) return SC_ERR_UNSUPPORTED;
+        if (t.producers == 0) t.producers = t.buffers - 1;
+    }
     if (t.pipeline == 1 && t.producers == 0) t.producers = 2;
     if (t.pipeline != 1) t.producers = 0;
     if (t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
@@ -308,7 +322,8 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
     if (t.ragged < 0 || t.ragged > 1) return SC_ERR_UNSUPPORTED;
     if (t.chunk_c == 0) t.ragged = 0;
     if (t.pack < 0 || t.pack > 3) return SC_ERR_UNSUPPORTED;
-    if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4) return SC_ERR_UNSUPPORTED;
+    if (t.producers != 0 && t.producers != 1 && t.producers != 2 && t.producers != 4 && !(t.producers == 3 && t.buffers == 4))
+        return SC_ERR_UNSUPPORTED;
     // (a fused epilogue lives in the GATHER and DENSE kernels only)
     if (has_epilogue(p) && t.variant == SC_VARIANT_SLAB) return SC_ERR_UNSUPPORTED;
     const bool want_slab = t.variant != SC_VARIANT_GATHER && !has_epilogue(p);
@@ -330,16 +345,16 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
                 const int hw = L.H * L.W;
                 for (int v = kMaxVpt; v >= 1 && !ok; --v) {
                     const int tq = std::min(hw, 64 * v);
-                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
+                    ok = slab_geometry(p, 1, tq, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g, t.buffers);
                 }
             } else {
                 for (int tp = (t.tile_p ? t.tile_p : p.P); tp >= 1 && !ok; --tp) {
-                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
+                    ok = slab_geometry(p, tp, p.Q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g, t.buffers);
                     if (t.tile_p) break;
                 }
             }
         } else {
-            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g);
+            ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g, t.buffers);
         }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
@@ -365,7 +380,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         return SC_ERR_UNSUPPORTED;
     if (has_epilogue(p) && t.split_n != 1) return SC_ERR_UNSUPPORTED;
     t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = t.ragged = 0;
-    if (t.pack) return SC_ERR_UNSUPPORTED;
+    if (t.pack || t.buffers) return SC_ERR_UNSUPPORTED;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -1066,6 +1081,37 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 push(t);
                 if (packable) { t.pack = 1; push(t); }
                 if (wide && (tq == 256 || tq == 512)) { t.pack = 2; push(t); t.wg_threads = 768; push(t); }
+            }
+        }
+    }
+    // the same form with producers + 1 chunk buffers (a producer wave per chunk in flight), also on
+    // tile widths that cut a plane into equal tiles of whole 16-byte words
+    if (pw && !is_codebook(p.dtype)) {
+        const int hw = p.L.H * p.L.W, words = 16 / p.ex;
+        std::vector<int> tqs = {256, 384, 512};
+        for (int k : {2, 3, 4, 6, 7, 8, 12, 14, 16}) {
+            const int tq = round_up((hw + k - 1) / k, words);
+            if (tq >= 128 && tq <= 512 && std::find(tqs.begin(), tqs.end(), tq) == tqs.end()) tqs.push_back(tq);
+        }
+        for (int nb : {3, 4}) for (int tq : tqs) for (int cc : {16, 32, 64}) {
+            if (cc >= p.L.C) continue;
+            for (int td : {0, 64, 128}) {
+                if (td >= p.L.D && td != 0) continue;
+                sc_tuning_t t{};
+                t.variant = SC_VARIANT_SLAB;
+                t.wsrc = 1;
+                t.pipeline = 1;
+                t.buffers = nb;
+                t.producers = nb - 1;
+                t.wg_per_cu = 1;
+                t.wg_threads = 1024;
+                t.tile_p = 1;
+                t.tile_q = tq;
+                t.chunk_c = cc;
+                t.tile_d = td;
+                push(t);
+                if (packable) { t.pack = 1; push(t); }
+                if (wide) { t.pack = 2; push(t); }
             }
         }
     }

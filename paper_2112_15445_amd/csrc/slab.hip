@@ -678,6 +678,21 @@ dma_tile(const X* tb, unsigned char* dst, int nch, int TQ, int Wf, int q0, int p
         }
         return;
     }
+    if (TQ % EPV == 0 && 2 * TQ > EW) {
+        // one channel row = ipc instructions, the last of them partly filled (its lanes past the
+        // end of the row copy nothing): a constant lane offset again, the base advances by rows
+        const int ipc = (TQ + EW - 1) / EW;
+        const int64_t cstride = (int64_t)Wf * (int64_t)sizeof(X);
+        for (int seg = 0; seg < ipc; ++seg) {
+            const int col = seg * EW + e;
+            if (col < TQ && q0 + col < Wf) {
+                const char* base = reinterpret_cast<const char*>(tb + seg * EW);
+                for (int c = pw; c < nch; c += nprod)
+                    dma16<HAND, BYTES>(base + c * cstride, (uint32_t)(e * (int)sizeof(X)), dst + (c * TQ + seg * EW) * (int)sizeof(X));
+            }
+        }
+        return;
+    }
     // generic: the (channel, column) of a lane's bytes advances by a fixed step from one
     // instruction to the next, so the division is done once and the rest is increments
     const int E = nch * TQ;
@@ -963,6 +978,7 @@ sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32
 
 struct ChunkArgs {
     int C, D, N, Wf, TQ, tiles, CC, nchunks, DTW, ndt, nprod, slab_bytes, dmab;
+    int nbuf;                                       // chunk buffers in LDS: 2, or nprod + 1
     float inv_tiles, inv_TQ, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -1011,6 +1027,40 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
                         lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, pw, nprod, lane,
                         a.inv_TQ);
         };
+        if (a.nbuf > 2) {
+            // nprod + 1 buffers: item i (a chunk of a tile) belongs to producer wave i % nprod, which
+            // copies it alone into buffer i % nbuf, so a wave never has more than one item in flight
+            // and "my item has landed" is vmcnt(0).  nprod items are in flight while one is
+            // multiplied: the HBM latency of a chunk is spread over nprod phases instead of one.
+            auto issue1 = [&](int u, int ch, int buf) {
+                int b, q0, dt;
+                decode(u, b, q0, dt);
+                const int c0 = ch * a.CC;
+                dma_tile<X>(x + (int64_t)b * a.x_sample_stride + q0 + (int64_t)c0 * a.Wf,
+                            lds + buf * a.slab_bytes, min(a.CC, a.C - c0), a.TQ, a.Wf, q0, 0, 1, lane,
+                            a.inv_TQ);
+            };
+            // item index -> (unit, chunk): items are numbered along this workgroup's units
+            auto item = [&](int i, int& u, int& ch) {
+                const int q = i / a.nchunks;          // (wave-uniform integer division, once per item)
+                ch = i - q * a.nchunks;
+                u = first + q * step;
+            };
+            int nunits = first < units ? (units - first + step - 1) / step : 0;
+            const int nitems = nunits * a.nchunks;
+            if (pw < nitems) { int u, ch; item(pw, u, ch); issue1(u, ch, pw % a.nbuf); }
+            int owner = 0, nxt_buf = nprod % a.nbuf;
+            for (int i = 0; i < nitems; ++i) {
+                if (owner == pw) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // item i has landed
+                // one barrier per phase: it says that item i is in LDS and that every consumer is
+                // done with item i - 1, whose buffer the next copy goes to
+                __syncthreads();
+                if (owner == pw && i + nprod < nitems) { int u, ch; item(i + nprod, u, ch); issue1(u, ch, nxt_buf); }
+                if (++owner == nprod) owner = 0;
+                if (++nxt_buf == a.nbuf) nxt_buf = 0;
+            }
+            return;
+        }
         if (first < units) issue(first, 0, 0);
         int it = 0;
         for (int u = first; u < units; u += step) {
@@ -1032,7 +1082,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
     static_assert(E == 1 || E * (int)sizeof(X) == 4 || E * (int)sizeof(X) == 16, "packed positions: 32- or 128-bit words");
     A acc[RPW][VPT][E];
     int out_off[VPT];
-    int it = 0;
+    int it = 0, cbuf = 0;
     for (int u = first; u < units; u += step) {
         int b, q0, dt;
         decode(u, b, q0, dt);
@@ -1050,7 +1100,8 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
         const int d0 = dt * a.DTW;
         const int dend = min(a.D, d0 + a.DTW);
         for (int ch = 0; ch < a.nchunks; ++ch, ++it) {
-            const unsigned char* lane_base = lds + (it & 1) * a.slab_bytes + lane * E * (int)sizeof(X);
+            const unsigned char* lane_base = lds + cbuf * a.slab_bytes + lane * E * (int)sizeof(X);
+            if (++cbuf == a.nbuf) cbuf = 0;
             __syncthreads();  // A
             // one segment per row and chunk, multiplied 8 entries at a time with no software
             // prefetch (the gathers of a group are then waited for one by one, and the other
@@ -1085,7 +1136,7 @@ slab_chunk_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT
                     }
                 }
             }
-            __syncthreads();  // B
+            if (a.nbuf == 2) __syncthreads();  // B (with three or more buffers barrier A of the next phase serves)
         }
         Y* yb = y + (int64_t)b * a.D * a.y_plane;
 #pragma unroll
@@ -1811,6 +1862,7 @@ static sc_status_t launch_chunk(const Plan& p, const void* x, void* y, int N, hi
     a.CC = g.CC; a.nchunks = g.nchunks; a.DTW = g.DTW; a.ndt = g.ndt; a.nprod = p.tuning.producers;
     a.slab_bytes = g.slab_bytes;
     a.dmab = g.dmab;
+    a.nbuf = g.nbuf > 2 ? g.nbuf : 2;
     a.inv_tiles = 1.0f / (float)g.tiles_q; a.inv_TQ = 1.0f / (float)g.TQ; a.inv_ndt = 1.0f / (float)g.ndt;
     a.x_sample_stride = (int64_t)p.L.C * g.Wf;
     a.y_plane = (int64_t)g.Qf;

@@ -1047,3 +1047,42 @@ def test_quantised_vgg_stack_chains_through_the_fused_epilogue(dtype):
         assert np.count_nonzero(got) > 0
         x_ref, x_gpu = x_next_ref, y
         plan.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_chunk_buffer_ring_of_the_producer_consumer_kernel(dtype):
+    """tuning.buffers = 3 .. 5: a producer wave per chunk in flight, one barrier per phase; with tile
+    widths whose rows are copied as whole instructions plus a partly filled one (not a power of two,
+    not a multiple of an instruction), ragged last tiles, a last chunk with fewer channels, more
+    workgroup units than workgroups, uneven rows, and the packed forms."""
+    for l in (wl.Layer("ring_a", 72, 50, 20, 28, 1, 1, 1, 1, 0, 0, N=5, sparsity=0.8, dtype=dtype, seed=71),
+              wl.Layer("ring_b", 40, 24, 28, 28, 1, 1, 1, 1, 0, 0, N=3, sparsity=0.9, dtype=dtype, seed=72)):
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        words16 = 16 // {"f32": 4, "f16": 2, "i8": 1}[dtype]
+        cases = [{"buffers": 3, "tile_q": 128, "chunk_c": 16}, {"buffers": 3, "tile_q": 392, "chunk_c": 24},
+                 {"buffers": 4, "tile_q": 448, "chunk_c": 8, "tile_d": 16}, {"buffers": 5, "tile_q": 192, "chunk_c": 7},
+                 {"buffers": 3, "producers": 2, "tile_q": 272, "chunk_c": 32, "wg_threads": 512, "tile_d": 24},
+                 {"buffers": 0, "producers": 2, "tile_q": 448, "chunk_c": 16},      # the partial-row copies with two buffers
+                 {"buffers": 0, "producers": 1, "tile_q": 400, "chunk_c": 24}]
+        if dtype != "f32":
+            cases += [{"buffers": 3, "tile_q": 384, "chunk_c": 16, "pack": 1}]
+        if dtype != "i8":
+            cases += [{"buffers": 3, "tile_q": 512, "chunk_c": 16, "pack": 2}, {"buffers": 4, "tile_q": 384 // words16 * words16, "chunk_c": 9, "pack": 2}]
+        for extra in cases:
+            kw = dict(variant=B.SC_VARIANT_SLAB, wsrc=1, pipeline=1, wg_threads=1024)
+            kw.update(extra)
+            kw["tile_q"] = -(-kw["tile_q"] // words16) * words16          # rows and tiles are whole 16-byte words
+            plan.set_tuning(B.sc_tuning_t(), **kw)
+            t = plan.get_tuning().as_dict()
+            assert t["buffers"] == extra["buffers"] and (not t["buffers"] or t["producers"] == t["buffers"] - 1)
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+        # refused: without channel chunks, outside the producer/consumer form, producers that do not match
+        for bad in ({"pipeline": 1, "buffers": 3}, {"pipeline": 2, "buffers": 3, "chunk_c": 16},
+                    {"pipeline": 0, "buffers": 3, "chunk_c": 16}, {"pipeline": 1, "buffers": 3, "producers": 1, "chunk_c": 16},
+                    {"pipeline": 1, "buffers": 6, "chunk_c": 16}, {"pipeline": 1, "buffers": 1, "chunk_c": 16}):
+            with pytest.raises(B.SparseConvError):
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, **bad)
+        plan.destroy()
