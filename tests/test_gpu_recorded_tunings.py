@@ -45,7 +45,8 @@ def test_recorded_tuning_at_full_batch(row):
         x_dev = G.to_device(np.ascontiguousarray(data["x"]))
         inf = plan.info()
         y = torch.empty((l.N, l.D, inf.P, inf.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
-        plan.dispatch(x_dev.data_ptr(), y.data_ptr(), l.N, 0, 0, torch.cuda.current_stream().cuda_stream)
+        ws = torch.empty(max(plan.workspace_size_max(l.N), 16), dtype=torch.uint8, device="cuda")
+        plan.dispatch(x_dev.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
         plan.set_tuning(B.sc_tuning_t(), **row["tuning"])
         plan.set_path(B.SC_PATH_LIBRARY)
         tol = 1e-3 if l.dtype == "f32" else None
