@@ -108,7 +108,10 @@ typedef struct {
                            64 positions, each scalar-loaded weight then feeds that many samples;
                            with pack >= 1, on pointwise layers and whole-plane tiles: 2..16 samples
                            whose planes lie end to end along the position axis of one packed tile,
-                           within pack's limit of 8 positions per lane) */
+                           within pack's limit of 8 positions per lane; with pack = 3: 2..8 groups of
+                           interleaved samples per workgroup, the lanes numbered over (group, position) --
+                           for planes so small that one group leaves most of a wave idle; the tile
+                           positions of all groups must fit the 64 lanes) */
     int32_t tile_p;     /* SLAB: output rows per tile (pointwise layers: ignored) */
     int32_t tile_q;     /* SLAB: output columns per tile (pointwise layers: pixels per tile) */
     int32_t wg_per_cu;  /* SLAB: workgroups the LDS budget is sized for (1..8) */
@@ -149,7 +152,7 @@ typedef struct {
                            positions.  0 = one position per LDS read.  With pipeline = 1 or 2 a lane's results
                            leave as one store and y must be aligned to it (4 bytes for pack = 1 with f16,
                            16 bytes otherwise); pack = 2 there needs 16-byte aligned rows.
-                           3 (SC_F32 / SC_F16 / SC_I8, pipeline = 0, chunk_c > 0, sub_batch = 0) = samples
+                           3 (SC_F32 / SC_F16 / SC_I8, pipeline = 0, chunk_c > 0) = samples
                            interleaved: a workgroup takes 4 (f32, i8) or 8 (f16) consecutive samples and an
                            LDS word (128 bits; 32 bits for i8) holds the same element of each, so every
                            offset is a whole word on any layer shape -- one LDS read per stored weight

@@ -94,7 +94,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
     o.chan_pitch = o.nsh * o.nsw * o.sub_pitch;
     o.F = o.TP * o.Qs;
     o.fs = 1;
-    if (samples > 1 && pack) {
+    if (samples > 1 && pack && pack != 3) {
         // small planes of a pointwise layer: the planes of `samples` consecutive samples laid end to
         // end form the tile's position axis (channel-major in LDS like any pointwise tile), so that
         // the lanes and the wide words of the packed forms fill up where one plane is smaller than
@@ -116,11 +116,19 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         // samples interleaved: an LDS word holds the same position of 4 (32-bit floats, 8-bit
         // integers) or 8 (16-bit floats) consecutive samples, so every offset is a whole word on
         // any layer shape; chunked one-shot form, weights by scalar loads
-        if (samples > 1 || pipeline != 0 || chunk_c <= 0 || wsrc != 1) return false;
+        if (pipeline != 0 || chunk_c <= 0 || wsrc != 1) return false;
         if (p.dtype != SC_F32 && p.dtype != SC_F16 && p.dtype != SC_I8) return false;
         o.si = 1;
         o.pack = p.dtype == SC_I8 ? 4 : 16 / p.ex;
         if (o.vpt * o.pack > 8) return false;
+        // small planes: `samples` such groups per workgroup, the lanes numbered over (group, position)
+        // -- a 4 x 4 plane with its halo column fills 24 of 64 lanes, two groups of it 48
+        o.sg = 1;
+        if (samples > 1) {
+            if (o.vpt != 1 || samples > 8 || samples * o.F > kWave) return false;
+            o.sg = samples;
+            samples = 1;
+        }
     } else if (pack) {
         // packed positions: chunked forms, one sample per workgroup; a lane owns the adjacent
         // positions of one 32-bit word (pack = 1: 16- or 8-bit activations) or of one 128-bit word
@@ -160,7 +168,7 @@ static bool slab_geometry(const Plan& p, int TP, int TQ, int wg_threads, int wsr
         if (pipeline != 0 || chunk_c <= 0 || o.vpt != 1 || samples > 4) return false;
         o.ns = samples;
     }
-    int64_t slab = (int64_t)o.ns * (o.si ? o.pack : 1) * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
+    int64_t slab = (int64_t)o.ns * (o.si ? o.pack * o.sg : 1) * o.CC * o.chan_pitch * p.ex + (int64_t)kWave * o.vpt * o.pack * p.ex;
     // packed positions read aligned 32-bit words only (unaligned LDS reads are several times
     // slower): unless every lambda is a whole number of words (pointwise layer, even channel
     // pitch), LDS holds `pack` images of the chunk, image s shifted by s elements, and an entry
@@ -360,7 +368,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.variant = SC_VARIANT_SLAB;
             t.tile_p = g.TP;
             t.tile_q = g.TQ;
-            t.sub_batch = g.ns > 1 ? g.ns : (g.fs > 1 ? g.fs : 0);
+            t.sub_batch = g.ns > 1 ? g.ns : (g.fs > 1 ? g.fs : (g.sg > 1 ? g.sg : 0));
             t.split_n = 0;
             if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
@@ -1225,10 +1233,10 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
         for (int wpc : {1, 2, 3}) for (int cc : {16, 24, 32, 48, 64, 96, 128, 256, 384, 512}) {
             const bool odd_cc = cc == 24 || cc == 48 || cc == 96;    // with interleaved samples only
             if ((cc > p.L.C && cc != 16) || (cc > 256 && wpc > 1)) continue;
-            for (int td : {0, 16, 32, 64, 128}) {   // (16: with interleaved samples only -- enough workgroups on small layers)
+            for (int td : {0, 4, 8, 16, 32, 64, 128}) {   // (4 .. 16: with interleaved samples only -- enough workgroups on small layers)
                 if (td >= p.L.D && td != 0) continue;
                 for (int tile : {1, 2, 4, 7, 8, 14, 16, 28}) for (int pk : {1, 2, 3}) {
-                    if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3) || (td == 16 && pk != 3)) continue;
+                    if ((pk == 1 && !packable) || (pk == 2 && !wide) || (pk == 3 && pw) || (tile == 1 && pk != 3) || (td != 0 && td <= 16 && pk != 3)) continue;
                     if (odd_cc && pk != 3) continue;
                     sc_tuning_t t{};
                     t.variant = SC_VARIANT_SLAB;
@@ -1241,6 +1249,15 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_d = td;
                     t.pack = pk;
                     push(t);
+                    // small planes: several sample groups along the lanes (refused unless they fit a wave)
+                    if (pk == 3 && tile * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 32) {
+                        for (int sg : {2, 4, 8}) {
+                            sc_tuning_t t2 = t;
+                            t2.sub_batch = sg;
+                            push(t2);
+                            if (p.L.D >= 256) { t2.wg_threads = 256; push(t2); t2.wg_threads = 512; push(t2); }
+                        }
+                    }
                     // (twelve waves: two such workgroups share a CU where the registers allow, one
                     // staging while the other multiplies)
                     if (pk == 3 && p.dtype == SC_F32) { t.wg_threads = 768; push(t); }

@@ -44,6 +44,7 @@ struct SlabGeom {
     int dmab;                  // bytes per lane of the direct-to-LDS copy the rows allow: 16, 4 or 0
     int ns;                    // samples per workgroup (chunked one-shot form, tiles of <= 64 positions)
     int si;                    // 1: an LDS word holds the same position of `pack` consecutive samples (tuning.pack = 3)
+    int sg;                    // ... and this many such sample groups per workgroup, laid along the lanes (tuning.sub_batch)
     int nbuf;                  // chunk buffers of the producer/consumer form with channel chunks (2, or producers + 1)
     int fs;                    // samples laid end to end along the tile's position axis (packed one-shot chunked form on pointwise layers); 1: off
     int nwaves;

@@ -59,6 +59,7 @@ struct SlabArgs {
     int SR;                              // rows of one channel image
     int FS;                              // samples laid end to end in one tile (1: off)
     int fs_vec;                          // ... and every sample's chunk is a 16-byte aligned block of whole 16-byte words
+    int SG;                              // interleaved samples: sample groups per workgroup, laid along the lanes (1: off)
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -1344,7 +1345,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // of them and slot k of a lane is position k * 64 + lane of each)
     constexpr bool FSM = SMODE == 1, SI = SMODE == 2;
     static_assert(SMODE == 0 || (E > 1 && !MS && !LANES && !FLAT && ROWB == 0), "several samples per packed tile: staged by table or by blocks");
-    const int b = MS ? bg * VPT : (FSM ? bg * a.FS : (SI ? bg * E : bg));
+    const int b = MS ? bg * VPT : (FSM ? bg * a.FS : (SI ? bg * E * a.SG : bg));
+    // (SI with several sample groups: lane = group * F + position, one slot per lane)
+    const int lgrp = (SI && a.SG > 1) ? min(fdiv(lane, 1.0f / (float)a.F), a.SG - 1) : 0;
+    const int lpos = (SI && a.SG > 1) ? lane - lgrp * a.F : lane;
+    const bool lane_on = !(SI && a.SG > 1) || lane < a.SG * a.F;
     const int tpi = fdiv(t, a.inv_tiles_q);
     const int tqi = t - tpi * a.tiles_q;
     const int p0 = tpi * a.TP, q0 = tqi * a.TQ;
@@ -1360,7 +1365,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     for (int k = 0; k < VPT; ++k) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            const int f = (MS || SI) ? (SI ? k * 64 + lane : lane) : (k * 64 + lane) * E + e;
+            const int f = (MS || SI) ? (SI ? k * 64 + lpos : lane) : (k * 64 + lane) * E + e;
             if constexpr (FSM) {
                 const int sm = fdiv(f, 1.0f / (float)a.Qf);
                 out_off[k][e] = (f < a.F && b + sm < a.N) ? sm * a.D * a.Qf + (f - sm * a.Qf) : -1;
@@ -1368,13 +1373,14 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             }
             const int tp = fdiv(f, a.inv_Qs);
             const int tq = f - tp * a.Qs;
-            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N) && (!SI || b + e < a.N);
+            const bool ok = f < a.F && tq < a.TQ && q0 + tq < a.Qf && p0 + tp < a.Pf && (!MS || b + k < a.N) &&
+                            (!SI || (lane_on && b + lgrp * E + e < a.N));
             out_off[k][e] = ok ? (p0 + tp) * a.Qf + q0 + tq : -1;
         }
     }
     const int img_elems = a.CC * a.chan_pitch;                       // one sample's chunk image
     const int koff = MS ? img_elems * (int)sizeof(X) : 64 * E * (int)sizeof(X);
-    const unsigned char* lane_base = lds + lane * E * (int)sizeof(X);
+    const unsigned char* lane_base = lds + (lgrp * img_elems + lpos) * E * (int)sizeof(X);
 
     // Offset of every element of one staged channel image inside the input plane, or -1 where the
     // image shows zero padding / lies outside the plane: computed once, so that staging a chunk
@@ -1486,9 +1492,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             // (zero where the image shows padding or the batch has ended)
             staged = true;
             struct alignas(E * sizeof(X)) Word { X e[E]; };
-            Word* wslab = reinterpret_cast<Word*>(lds);
-            const X* xc = xb + (int64_t)c0 * plane;
             constexpr int kWords = 2;
+            for (int sg = 0; sg < a.SG; ++sg) {
+            Word* wslab = reinterpret_cast<Word*>(lds) + sg * img_elems;
+            const X* xc = xb + (int64_t)sg * E * a.x_sample_stride + (int64_t)c0 * plane;
+            const int bs = b + sg * E;                           // first sample of this group
             for (int e0 = tid; e0 < elems; e0 += kWords * nthreads) {
                 Word v[kWords];
 #pragma unroll
@@ -1502,7 +1510,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                         if (o >= 0) {
 #pragma unroll
                             for (int sm = 0; sm < E; ++sm)
-                                if (b + sm < a.N) v[u].e[sm] = xc[(int64_t)sm * a.x_sample_stride + (int64_t)c * plane + o];
+                                if (bs + sm < a.N) v[u].e[sm] = xc[(int64_t)sm * a.x_sample_stride + (int64_t)c * plane + o];
                         }
                     }
                 }
@@ -1511,6 +1519,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                     const int e = e0 + u * nthreads;
                     if (e < elems) wslab[e] = v[u];
                 }
+            }
             }
         }
         if (!staged)
@@ -1686,7 +1695,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
                 for (int e = 0; e < E; ++e)
                     if (out_off[k][e] >= 0)
-                        store_out(yd + (int64_t)(MS ? k : (SI ? e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
+                        store_out(yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
                                   narrow<DT>(acc[r][k][e]));
         }
     }
@@ -2162,7 +2171,8 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
                         (g.CC * plane_bytes) % 16 == 0) ? 1 : 0;
         }
         a.inv_ndt = 1.0f / (float)g.ndt;
-        const int per_wg = g.si ? g.pack : (g.ns > 1 ? g.ns : g.fs);
+        const int per_wg = g.si ? g.pack * std::max(g.sg, 1) : (g.ns > 1 ? g.ns : g.fs);
+        a.SG = g.si ? std::max(g.sg, 1) : 1;
         const int64_t gridc = (int64_t)((N + per_wg - 1) / per_wg) * g.tiles_p * g.tiles_q * g.ndt;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
         switch (p.dtype) {

@@ -1086,3 +1086,38 @@ def test_chunk_buffer_ring_of_the_producer_consumer_kernel(dtype):
             with pytest.raises(B.SparseConvError):
                 plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=1024, **bad)
         plan.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_sample_groups_along_the_lanes_with_interleaved_samples(dtype):
+    """tuning.pack = 3 with tuning.sub_batch = 2 .. 8 on small planes: a workgroup takes that many groups
+    of 4 (8 for f16) samples and numbers its lanes over (group, position).  Batches that end inside a
+    word and inside a group, planes of 2 x 2 .. 5 x 3 with and without padding, stride 2, several
+    chunks with a short last one, output-channel blocks that leave waves without rows; and the refusals."""
+    cases = ((wl.Layer("sg2x2", 40, 24, 2, 2, 3, 3, 1, 1, 1, 1, N=37, sparsity=0.8, dtype=dtype, seed=81),
+              [dict(tile_p=2, sub_batch=8, chunk_c=16, tile_d=8, wg_threads=256), dict(tile_p=2, sub_batch=4, chunk_c=40, wg_threads=512),
+               dict(tile_p=1, sub_batch=2, chunk_c=7, tile_d=5, wg_threads=1024), dict(tile_p=2, sub_batch=3, chunk_c=24, tile_d=4, wg_threads=128)]),
+             (wl.Layer("sg4x4", 24, 20, 4, 4, 3, 3, 1, 1, 1, 1, N=21, sparsity=0.7, dtype=dtype, seed=82),
+              [dict(tile_p=4, sub_batch=2, chunk_c=8, tile_d=16, wg_threads=1024), dict(tile_p=2, sub_batch=5, chunk_c=24, wg_threads=256),
+               dict(tile_p=1, sub_batch=8, chunk_c=5, tile_d=7, wg_threads=512)]),
+             (wl.Layer("sg5x3s2", 16, 12, 9, 6, 3, 2, 2, 2, 1, 0, N=19, sparsity=0.6, dtype=dtype, seed=83),
+              [dict(tile_p=5, sub_batch=2, chunk_c=6, wg_threads=256), dict(tile_p=2, sub_batch=4, chunk_c=16, tile_d=4, wg_threads=512)]),
+             (wl.Layer("sg1x1", 32, 16, 3, 3, 1, 1, 1, 1, 0, 0, N=9, sparsity=0.5, dtype=dtype, seed=84),
+              []))
+    for l, tunings in cases:
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, **extra)
+            t = plan.get_tuning().as_dict()
+            assert t["pack"] == 3 and t["sub_batch"] == extra["sub_batch"]
+            print("case", l.name, dtype, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+        # refused: groups that do not fit a wave, more than one slot per lane, too many groups
+        for bad in (dict(tile_p=l.P, sub_batch=64 // max(l.P * (l.Q + (l.S - 1) // l.stride_w), 1) + 1, chunk_c=8),
+                    dict(tile_p=1, sub_batch=9, chunk_c=8)):
+            if bad["sub_batch"] > 1:
+                with pytest.raises(B.SparseConvError):
+                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, **bad)
+        plan.destroy()
