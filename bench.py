@@ -427,6 +427,8 @@ def short_shape(t):
         sh += f" ns{t['sub_batch']}"
     if t.get("pack"):
         sh += {1: " pk32", 2: " pk128", 3: " si"}.get(t["pack"], f" pk?{t['pack']}")
+    if t.get("split_n"):
+        sh += f" ks{t['split_n']}"
     if t.get("ragged"):
         sh += " ragged"
     return sh

@@ -120,7 +120,13 @@ typedef struct {
                            global memory (vector L1), software-pipelined; 3 = one entry per lane by
                            coalesced vector loads, broadcast with v_readlane */
     int32_t split_n;    /* GATHER: lanes that share one output, each summing every split_n-th stored
-                           entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64 */
+                           entry, combined by a wavefront-level shuffle reduction: 1, 4, 16 or 64.
+                           SLAB (given explicitly) with pipeline = 0 and chunk_c > 0, SC_F32 / SC_I8: 2..16 =
+                           the channel chunks of a tile are dealt to that many workgroups, which add their
+                           partial sums into y with atomic adds (y is cleared by a small kernel first) -- for
+                           layers with fewer tiles than CUs; at most as many as there are chunks.  fp32
+                           results of such a shape depend on the order in which the workgroups arrive
+                           (last bits, within the tolerance of the type); int8 results do not */
     int32_t pipeline;   /* SLAB, pointwise layers: 1 = persistent workgroups that stream tile i+1 into a
                            second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
                            tile i is multiplied; needs wsrc != 0.  2 = the same double buffering with

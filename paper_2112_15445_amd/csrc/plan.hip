@@ -364,12 +364,23 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         } else {
             ok = slab_geometry(p, pw ? 1 : (t.tile_p ? t.tile_p : 1), t.tile_q, t.wg_threads, t.wsrc, t.pipeline, t.producers, t.chunk_c, t.tile_d, samples, t.pack, budget, &g, t.buffers);
         }
+        // an explicit SLAB tuning with split_n > 1: the chunks of a tile are dealt to that many
+        // workgroups (chunked one-shot form; fp32 and int8, whose outputs are 32-bit and can be
+        // added atomically)
+        int ksplit = 1;
+        if (ok && in.variant == SC_VARIANT_SLAB && t.split_n > 1) {
+            if (t.pipeline != 0 || t.chunk_c <= 0 || t.split_n > 16 || (p.dtype != SC_F32 && p.dtype != SC_I8) ||
+                g.nchunks < t.split_n)
+                return SC_ERR_UNSUPPORTED;
+            ksplit = t.split_n;
+        }
         if (ok) {
             t.variant = SC_VARIANT_SLAB;
             t.tile_p = g.TP;
             t.tile_q = g.TQ;
             t.sub_batch = g.ns > 1 ? g.ns : (g.fs > 1 ? g.fs : (g.sg > 1 ? g.sg : 0));
-            t.split_n = 0;
+            t.split_n = ksplit > 1 ? ksplit : 0;
+            g.ksplit = ksplit;
             if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
             *out = t;
@@ -1249,6 +1260,15 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.tile_d = td;
                     t.pack = pk;
                     push(t);
+                    // layers with fewer tiles than CUs: the chunks of a tile dealt to several workgroups
+                    // (wide output-channel blocks, so that the input is staged few times)
+                    if ((p.dtype == SC_F32 || p.dtype == SC_I8) && p.P * p.Q <= 256 && (td == 0 || td >= 64) && cc < p.L.C) {
+                        for (int ks : {2, 4, 8}) {
+                            sc_tuning_t t2 = t;
+                            t2.split_n = ks;
+                            push(t2);
+                        }
+                    }
                     // small planes: several sample groups along the lanes (refused unless they fit a wave)
                     if (pk == 3 && tile * (p.Q + (p.L.S - 1) / p.L.stride_w) <= 32) {
                         for (int sg : {2, 4, 8}) {

@@ -80,6 +80,13 @@ __device__ inline void store_out(__half* p, __half v)
 {
     __builtin_nontemporal_store(__half_as_ushort(v), reinterpret_cast<unsigned short*>(p));
 }
+// Partial sums of one output from several workgroups meet in memory: hardware atomic adds (the
+// floating-point one returns nothing and rounds once per add: the order of the adds is the order in
+// which the workgroups arrive, so fp32 results of such a launch shape can differ in the last bits
+// from run to run; integer sums cannot).
+__device__ inline void add_out(float* p, float v) { unsafeAtomicAdd(p, v); }
+__device__ inline void add_out(int32_t* p, int32_t v) { atomicAdd(p, v); }
+__device__ inline void add_out(__half*, __half) {}      // (never selected: refused at tuning time)
 __device__ inline void store_out4(int32_t* p, int32_t a, int32_t b, int32_t c, int32_t d)
 {
     typedef int int4v __attribute__((ext_vector_type(4)));

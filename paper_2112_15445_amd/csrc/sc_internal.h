@@ -45,6 +45,7 @@ struct SlabGeom {
     int ns;                    // samples per workgroup (chunked one-shot form, tiles of <= 64 positions)
     int si;                    // 1: an LDS word holds the same position of `pack` consecutive samples (tuning.pack = 3)
     int sg;                    // ... and this many such sample groups per workgroup, laid along the lanes (tuning.sub_batch)
+    int ksplit;                // chunked one-shot form: workgroups that share the chunks of a tile (tuning.split_n; 1: off)
     int nbuf;                  // chunk buffers of the producer/consumer form with channel chunks (2, or producers + 1)
     int fs;                    // samples laid end to end along the tile's position axis (packed one-shot chunked form on pointwise layers); 1: off
     int nwaves;

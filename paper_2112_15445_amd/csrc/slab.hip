@@ -60,6 +60,8 @@ struct SlabArgs {
     int FS;                              // samples laid end to end in one tile (1: off)
     int fs_vec;                          // ... and every sample's chunk is a 16-byte aligned block of whole 16-byte words
     int SG;                              // interleaved samples: sample groups per workgroup, laid along the lanes (1: off)
+    int ksplit, cps;                     // chunks of a tile dealt to ksplit workgroups, cps chunks each (1: off)
+    float inv_ksplit;
     float inv_chan_pitch, inv_sub_pitch, inv_Qs, inv_tiles, inv_tiles_q, inv_ndt;
     int64_t x_sample_stride, y_plane;
 };
@@ -1334,8 +1336,14 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // a contiguous run, and the output-channel blocks of one tile share an L2)
     const int grid = gridDim.x;
     const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int bt = fdiv(wg, a.inv_ndt);
-    const int dt = wg - bt * a.ndt;
+    const int bt0 = fdiv(wg, a.inv_ndt);
+    const int dt = wg - bt0 * a.ndt;
+    // (split-K: the chunks of a tile are dealt to ksplit workgroups, each adding its partial sums to
+    // y, which the launcher has cleared)
+    const int bt = a.ksplit > 1 ? fdiv(bt0, a.inv_ksplit) : bt0;
+    const int ks = a.ksplit > 1 ? bt0 - bt * a.ksplit : 0;
+    const int ch_lo = a.ksplit > 1 ? ks * a.cps : 0;
+    const int ch_hi = a.ksplit > 1 ? min(a.nchunks, ch_lo + a.cps) : a.nchunks;
     const int bg = fdiv(bt, a.inv_tiles);
     const int t = bt - bg * tiles;
     // MS: the workgroup takes VPT samples of a tile of at most 64 positions (slot k of a lane is
@@ -1438,10 +1446,10 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[r][k][e] = A(0);
 
-    for (int ch = 0; ch < a.nchunks; ++ch) {
+    for (int ch = ch_lo; ch < ch_hi; ++ch) {
         const int c0 = ch * a.CC;
         const int elems = min(a.CC, a.C - c0) * a.chan_pitch;
-        if (ch > 0) __syncthreads();      // the previous chunk has been consumed
+        if (ch > ch_lo) __syncthreads();      // the previous chunk has been consumed
         // four elements per thread and pass, loads first, so that four loads are in flight
         bool staged = false;
         if constexpr (FSM) if (a.fs_vec) {
@@ -1694,9 +1702,11 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             for (int k = 0; k < VPT; ++k)
 #pragma unroll
                 for (int e = 0; e < E; ++e)
-                    if (out_off[k][e] >= 0)
-                        store_out(yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
-                                  narrow<DT>(acc[r][k][e]));
+                    if (out_off[k][e] >= 0) {
+                        Y* yp = yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e];
+                        if (a.ksplit > 1) add_out(yp, narrow<DT>(acc[r][k][e]));
+                        else store_out(yp, narrow<DT>(acc[r][k][e]));
+                    }
         }
     }
 }
@@ -2130,6 +2140,12 @@ static sc_status_t launch_dt(const Plan& p, const SlabArgs& a, const void* x, vo
     return launch_vpt<DT, 0>(p, a, x, y, grid, stream);
 }
 
+__global__ void __launch_bounds__(256) clear_kernel(uint32_t* __restrict__ dst, int64_t words)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) dst[i] = 0u;
+}
+
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
 {
     const SlabGeom& g = p.geom;
@@ -2173,8 +2189,20 @@ sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_
         a.inv_ndt = 1.0f / (float)g.ndt;
         const int per_wg = g.si ? g.pack * std::max(g.sg, 1) : (g.ns > 1 ? g.ns : g.fs);
         a.SG = g.si ? std::max(g.sg, 1) : 1;
-        const int64_t gridc = (int64_t)((N + per_wg - 1) / per_wg) * g.tiles_p * g.tiles_q * g.ndt;
+        a.ksplit = std::max(g.ksplit, 1);
+        a.cps = (g.nchunks + a.ksplit - 1) / a.ksplit;
+        a.inv_ksplit = 1.0f / (float)a.ksplit;
+        const int64_t gridc = (int64_t)((N + per_wg - 1) / per_wg) * g.tiles_p * g.tiles_q * g.ndt * a.ksplit;
         if (gridc >= (1 << 19)) return SC_ERR_UNSUPPORTED;
+        if (a.ksplit > 1) {
+            // partial sums are added into y: clear it first (a fill kernel, so that the launch can be
+            // captured in a graph)
+            const int64_t words = ((int64_t)N * p.L.D * g.Pf * g.Qf * p.ey + 3) / 4;
+            if (p.ey != 4) return SC_ERR_UNSUPPORTED;
+            hipLaunchKernelGGL(clear_kernel, dim3((unsigned)std::min<int64_t>((words + 1023) / 1024, 4096)), dim3(256), 0, stream,
+                               static_cast<uint32_t*>(y), words);
+            if (hipGetLastError() != hipSuccess) return SC_ERR_HIP;
+        }
         switch (p.dtype) {
             case SC_F32: return launch_cc<SC_F32>(p, a, x, y, (int)gridc, stream);
             case SC_F16: return launch_cc<SC_F16>(p, a, x, y, (int)gridc, stream);

@@ -1121,3 +1121,45 @@ def test_sample_groups_along_the_lanes_with_interleaved_samples(dtype):
                 with pytest.raises(B.SparseConvError):
                     plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, **bad)
         plan.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "i8"])
+def test_channel_chunks_dealt_to_several_workgroups(dtype):
+    """tuning.split_n = 2 .. 16 on the chunked one-shot slab kernel: the chunks of a tile go to that many
+    workgroups, which add their partial sums into y (cleared first) with atomic adds.  Splits that do
+    not divide the number of chunks, a short last chunk, every staging form of that kernel (table, row
+    runs, plain copy, interleaved samples with and without sample groups, several samples per
+    workgroup, lane-distributed weights); y poisoned before every launch; int8 sums stay exact."""
+    cases = ((wl.Layer("ks3x3", 40, 24, 9, 7, 3, 3, 1, 1, 1, 1, N=6, sparsity=0.7, dtype=dtype, seed=91),
+              [dict(chunk_c=8, split_n=2, tile_p=3), dict(chunk_c=6, split_n=7, tile_p=9, tile_d=8),
+               dict(chunk_c=4, split_n=10, tile_p=2, pack=3), dict(chunk_c=8, split_n=5, tile_p=1, pack=3, sub_batch=2, tile_d=16),
+               dict(chunk_c=7, split_n=3, tile_p=4, sub_batch=2), dict(chunk_c=5, split_n=4, tile_p=3, wsrc=3)]),
+             (wl.Layer("ks1x1", 96, 50, 7, 7, 1, 1, 1, 1, 0, 0, N=5, sparsity=0.8, dtype=dtype, seed=92),
+              [dict(chunk_c=16, split_n=6, tile_q=49, wg_threads=1024), dict(chunk_c=32, split_n=3, tile_q=49, tile_d=16, sub_batch=2),
+               dict(chunk_c=20, split_n=2, tile_q=32, wg_threads=512)]),
+             (wl.Layer("ks3x3s2", 32, 20, 14, 14, 3, 3, 2, 2, 1, 1, N=5, sparsity=0.6, dtype=dtype, seed=93),
+              [dict(chunk_c=8, split_n=4, tile_p=7), dict(chunk_c=4, split_n=8, tile_p=7, pack=3, tile_d=8)]))
+    for l, tunings in cases:
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            kw = dict(variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=256)
+            kw.update(extra)
+            plan.set_tuning(B.sc_tuning_t(), **kw)
+            t = plan.get_tuning().as_dict()
+            assert t["split_n"] == extra["split_n"] and t["chunk_c"] == extra["chunk_c"]
+            print("case", l.name, dtype, t, flush=True)
+            for _ in range(2):                         # twice: the second launch finds y full of the first result
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+        # refused: more workgroups than chunks, outside the chunked one-shot form, more than 16
+        for bad in (dict(chunk_c=l.C, split_n=2), dict(chunk_c=8, split_n=17), dict(chunk_c=0, split_n=2)):
+            with pytest.raises(B.SparseConvError):
+                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, wg_threads=256, **bad)
+        plan.destroy()
+    # 16-bit outputs cannot be added atomically with one rounding: refused
+    l = wl.Layer("ksf16", 32, 16, 6, 6, 3, 3, 1, 1, 1, 1, N=2, sparsity=0.5, dtype="f16", seed=94)
+    plan = G.make_plan(l, wl.prepare(l))
+    with pytest.raises(B.SparseConvError):
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, chunk_c=8, split_n=2)
+    plan.destroy()
