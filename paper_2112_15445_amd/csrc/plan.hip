@@ -1275,6 +1275,8 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                             sc_tuning_t t2 = t;
                             t2.sub_batch = sg;
                             push(t2);
+                            if ((p.dtype == SC_F32 || p.dtype == SC_I8) && (td == 0 || td >= 32) && cc < p.L.C)
+                                for (int ks : {2, 4, 8}) { sc_tuning_t t3 = t2; t3.split_n = ks; push(t3); }
                             if (p.L.D >= 256) { t2.wg_threads = 256; push(t2); t2.wg_threads = 512; push(t2); }
                         }
                     }
@@ -1428,20 +1430,26 @@ static sc_status_t autotune_impl(sparse_conv_plan_t* plan, const void* x_dev, vo
     int best_i = -1;
     if (st == SC_OK && !timed.empty()) {
         std::sort(timed.begin(), timed.end());
-        // finalists: the six fastest, and the fastest of every kernel family (variant, pipeline,
-        // packing, samples per workgroup) not among them -- near-identical shapes of one family
+        // finalists: the eight fastest, and the two fastest of every kernel family (variant, pipeline,
+        // packing, samples per workgroup, split) not among them -- near-identical shapes of one family
         // must not crowd out the family that wins once the buffers rotate
         {
             auto family = [&](int i) {
                 const sc_tuning_t& c = cands[i];
-                return (c.variant << 12) | (c.pipeline << 8) | (c.pack << 4) | (c.sub_batch > 1 ? 2 : 0) | (c.chunk_c > 0 ? 1 : 0);
+                // (shapes that deal the chunks of a tile to several workgroups, or keep a ring of chunk
+                // buffers, are families of their own)
+                const int split = (c.variant == SC_VARIANT_SLAB && c.split_n > 1) ? 1 : 0;
+                return (c.variant << 12) | (c.pipeline << 8) | (c.pack << 4) | (split << 3) | (c.buffers > 2 ? 4 : 0) |
+                       (c.sub_batch > 1 ? 2 : 0) | (c.chunk_c > 0 ? 1 : 0);
             };
+            // (two per family: the shape of a family that is fastest on cache-resident buffers is not
+            // always its fastest once they rotate)
             std::vector<int> seen;
-            size_t keep = std::min<size_t>(timed.size(), 6);
+            size_t keep = std::min<size_t>(timed.size(), 8);
             for (size_t k = 0; k < keep; ++k) seen.push_back(family(timed[k].second));
-            for (size_t k = keep; k < timed.size() && keep < 16; ++k) {
+            for (size_t k = keep; k < timed.size() && keep < 28; ++k) {
                 const int f = family(timed[k].second);
-                if (std::find(seen.begin(), seen.end(), f) != seen.end()) continue;
+                if (std::count(seen.begin(), seen.end(), f) >= 2) continue;
                 seen.push_back(f);
                 std::swap(timed[keep], timed[k]);
                 ++keep;

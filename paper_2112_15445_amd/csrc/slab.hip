@@ -1695,6 +1695,23 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
         }
     }
     Y* yd = y + ((int64_t)b * a.D + drow0) * a.y_plane;
+    if (a.ksplit > 1) {
+        // partial sums of this workgroup's chunks (a loop of its own: the plain stores below keep
+        // their registers and schedule)
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            if (r < nrows) {
+#pragma unroll
+                for (int k = 0; k < VPT; ++k)
+#pragma unroll
+                    for (int e = 0; e < E; ++e)
+                        if (out_off[k][e] >= 0)
+                            add_out(yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
+                                    narrow<DT>(acc[r][k][e]));
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         if (r < nrows) {
@@ -1702,11 +1719,9 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
             for (int k = 0; k < VPT; ++k)
 #pragma unroll
                 for (int e = 0; e < E; ++e)
-                    if (out_off[k][e] >= 0) {
-                        Y* yp = yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e];
-                        if (a.ksplit > 1) add_out(yp, narrow<DT>(acc[r][k][e]));
-                        else store_out(yp, narrow<DT>(acc[r][k][e]));
-                    }
+                    if (out_off[k][e] >= 0)
+                        store_out(yd + (int64_t)(MS ? k : (SI ? lgrp * E + e : 0)) * a.D * a.y_plane + (int64_t)r * a.y_plane + out_off[k][e],
+                                  narrow<DT>(acc[r][k][e]));
         }
     }
 }
