@@ -41,9 +41,9 @@ INFINITY_CACHE_BYTES = 256 << 20
 # the commands that produced them are under profiles/.  Keyed by (workload, launch shape): a run in
 # which the autotuner installs another shape reports no traffic figure rather than a stale one.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 50394.5 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25123.9 KiB x 1.000
+    # FETCH_SIZE 50408.0 KiB x 2.000 (copy-kernel calibration) + WRITE_SIZE 25127.5 KiB x 1.000
     ("s56_reduce1x1_sp90", "variant=2 wg_threads=1024 tile_p=1 tile_q=512 wg_per_cu=1 wsrc=1 pipeline=1 "
-     "producers=2 chunk_c=32 tile_d=64 pack=2"): int((50394.5 * 2.000 + 25123.9 * 1.000) * 1024),
+     "producers=2 chunk_c=32 tile_d=64 pack=2"): int((50408.0 * 2.000 + 25127.5 * 1.000) * 1024),
 }
 
 
