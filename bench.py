@@ -496,7 +496,19 @@ def report_table(rows):
         if r.get("graph_ms"):
             out.append(f"# {r['layer']} ({r['dtype']}): {r['ms_events']*1e3:.2f} us between events, "
                        f"{r['graph_ms']*1e3:.2f} us per launch inside a captured HIP graph (launch-limited)")
-    out.append("cfg layer                      dtype    n  choice   timed_us  alg_GB/s hbm_frac useful_TF | gather_us   mfma_us lib_us(warm) | "
+    # rows that run on the matrix cores: their bound is "mfma" -- dense flops (the tile multiplies every
+    # weight, stored or not) against 2.5 PFLOP/s (fp16) / 5.0 POP/s (int8)
+    from paper_2112_15445_amd import workloads as _wl
+    layers = {(l.name, l.dtype): l for c in _wl.CONFIGS for l in _wl.CONFIGS[c]()}
+
+    def mfma_frac(r):
+        l = layers.get((r["layer"], r["dtype"]))
+        if r.get("path") != "dense" or l is None:
+            return None
+        flops = 2.0 * l.N * l.D * l.P * l.Q * l.C * l.R * l.S
+        peak = 5.0e15 if r["dtype"] in ("i8", "cb4") else 2.5e15
+        return flops / (r["ms_events"] * 1e-3) / peak
+    out.append("cfg layer                      dtype    n  choice   timed_us  alg_GB/s hbm_frac useful_TF mfma_frac | gather_us   mfma_us lib_us(warm) | "
                "torch_cold torch_warm | parity | launch shape of the choice")
     for r in rows:
         sp, de, li = legs(r)
@@ -506,7 +518,8 @@ def report_table(rows):
         f = lambda v: f"{v*1e3:9.2f}" if v else f"{nan:9.2f}"
         shape = "dense library (MIOpen)" if r.get("path") == "library" else short_shape(r["tuning"])
         out.append(f"{r['config']:3d} {r['layer']:26s} {r['dtype']:4s} {r['n']:5d} {r.get('path', 'sparse'):7s} {r['ms_events']*1e3:9.2f} "
-                   f"{r['achieved_gbs']:9.0f} {r['hbm_frac']*100:7.1f}% {r['useful_gflops']/1e3:9.2f} | {f(sp)} {f(de)} {f(li)}    | "
+                   f"{r['achieved_gbs']:9.0f} {r['hbm_frac']*100:7.1f}% {r['useful_gflops']/1e3:9.2f} "
+                   f"{('%8.1f%%' % (mfma_frac(r) * 100)) if mfma_frac(r) is not None else '        -'} | {f(sp)} {f(de)} {f(li)}    | "
                    f"{f(dc)}  {f(dw)} | {ptxt:6s} | {shape}")
     return "\n".join(out) + "\n"
 
