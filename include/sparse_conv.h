@@ -291,6 +291,11 @@ sc_status_t sparse_conv_forward_static(const sparse_conv_plan_t* plan, const voi
  * Candidates that these pointers rule out (see sparse_conv_forward) are skipped, so the installed
  * shape is valid for buffers aligned like x_dev and y_dev.
  * On any error the tuning the plan had on entry is installed again before the call returns.
+ * On layers with fewer tiles than compute units the winner can be a shape that sums the partial
+ * results of several workgroups with atomic adds (SLAB with split_n > 1, see sc_tuning_t): an SC_F32
+ * result then depends on the arrival order of the workgroups in its last bits.  A caller that needs
+ * run-to-run identical bits reads the tuning back (sparse_conv_plan_get_tuning) and, if split_n > 1
+ * on a SLAB tuning, installs another one (any candidate of sparse_conv_plan_candidate without it).
  * Errors: SC_ERR_NULL, SC_ERR_SHAPE, SC_ERR_WORKSPACE, SC_ERR_UNSUPPORTED (no candidate runs),
  * SC_ERR_OOM, SC_ERR_HIP. */
 sc_status_t sparse_conv_plan_autotune(sparse_conv_plan_t* plan, const void* x_dev, void* y_dev,
