@@ -101,7 +101,9 @@ enum {
  * Fields that do not apply to a variant are ignored.  All-zero = SC_VARIANT_AUTO. */
 typedef struct {
     int32_t variant;    /* SC_VARIANT_* */
-    int32_t wg_threads; /* workgroup size: 64..1024, multiple of 64 */
+    int32_t wg_threads; /* workgroup size: 64..1024, multiple of 64.  DENSE: 256 (0 = that) or 512 -- with 512 two
+                           groups of four waves own the same outputs and take the even and the odd steps
+                           of the contraction (filter tap x channel block), meeting through LDS at the end */
     int32_t sub_batch;  /* GATHER: output positions per thread that share each (theta, lambda) read
                            from LDS (the role of sb_S), 1, 2, 4 or 8.  SLAB with pipeline = 0 and
                            chunk_c > 0: samples per workgroup (0 / 1 = one; 2..4 for tiles of at most

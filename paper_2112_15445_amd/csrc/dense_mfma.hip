@@ -103,7 +103,7 @@ sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream)
 // ------------------------------------------------------------------------------------------------
 // Geometry of one (plan, tuning) pair, derived on the host.
 // ------------------------------------------------------------------------------------------------
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out)
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG)
 {
     const sc_layer_t& L = p.L;
     MfmaGeom g{};
@@ -137,9 +137,12 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : (nw <= 4 ? 4 : 8));
     if (g.NW == 8 && g.MW == 4) return false;     // 32 accumulator blocks per wave: not instantiated
     int64_t lds = (int64_t)g.npos_s * g.pitch;
-    if (has_epilogue(p) && p.epi.pool) {
-        // pooling windows must not straddle tiles; the accumulators are exchanged through LDS
-        if (g.TP < p.P && (g.TP & 1)) return false;
+    if (KG != 1 && KG != 2) return false;
+    g.KG = KG;
+    // pooling windows must not straddle tiles
+    if (has_epilogue(p) && p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
+    if ((has_epilogue(p) && p.epi.pool) || KG == 2) {
+        // the accumulators are exchanged through LDS (between the two step groups, or for pooling)
         g.epi_pitch = (4 / g.WM) * g.NW * 16 + 1;
         lds = std::max<int64_t>(lds, (int64_t)g.DB * g.epi_pitch * 4);
     }

@@ -60,7 +60,7 @@ struct StageArgs {
     int wcols;             // input columns that are staged: [0, wcols)
 };
 
-template <typename X, int CV, int EPV>
+template <typename X, int CV, int EPV, int NT>
 __device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned char* lds, int tid, int cgroups, int cleft,
                                             const StageArgs& sa, const MfmaArgs& a, int plane)
 {
@@ -70,12 +70,12 @@ __device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned c
     const int rowsG = sa.nrows * G, per_cg = sa.nsv * rowsG;
     const int nblocks = cgroups * per_cg;
     const float inv_per_cg = 1.0f / (float)max(per_cg, 1), inv_rowsG = 1.0f / (float)max(rowsG, 1), inv_G = 1.0f / (float)max(G, 1);
-    for (int v0 = tid; v0 < nblocks; v0 += 256 * VB) {
+    for (int v0 = tid; v0 < nblocks; v0 += NT * VB) {
         Vec val[VB][CV];
         int dst[VB], vcg[VB], col[VB];
 #pragma unroll
         for (int u = 0; u < VB; ++u) {
-            const int v = v0 + u * 256;
+            const int v = v0 + u * NT;
             const int vv = v < nblocks ? v : 0;            // (past the end: block 0 again, not written)
             const int cg = fdiv19(vv, inv_per_cg);
             const int rb = vv - cg * per_cg;
@@ -108,7 +108,7 @@ __device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned c
         }
     }
     // padding: staged positions outside the input or past the batch
-    for (int pos = tid; pos < a.npos_s; pos += 256) {
+    for (int pos = tid; pos < a.npos_s; pos += NT) {
         const int sm = fdiv19(pos, a.inv_HsWs);
         const int rem = pos - sm * (a.Hs * a.Ws);
         const int i = fdiv19(rem, a.inv_Ws);
@@ -125,19 +125,27 @@ __device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned c
 // the last step's operands instead of branching).
 struct StepCursor {
     int cb, r, s, tap;
+    template <int STEPS = 1>
     __device__ __forceinline__ void advance(int cbs, int S, bool more)
     {
         if (!more) return;
-        if (++cb == cbs) {
-            cb = 0;
-            ++tap;
-            if (++s == S) { s = 0; ++r; }
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
+            if (++cb == cbs) {
+                cb = 0;
+                ++tap;
+                if (++s == S) { s = 0; ++r; }
+            }
         }
     }
 };
 
-template <sc_dtype_t DT, int MW, int NW, int WM>
-__global__ void __launch_bounds__(256)
+// KG = 2: eight waves.  The two groups of four waves own the same outputs and take the even and the odd
+// steps of the contraction; their accumulators meet through LDS at the end (a fixed order: the
+// result does not depend on timing).  Two waves then share a SIMD, which is what the matrix
+// instructions need to issue back to back, at no more traffic: every operand is still fetched once.
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+__global__ void __launch_bounds__(256 * KG)
 mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                  const uint4w* __restrict__ wfrag, const MfmaArgs a)
 {
@@ -147,9 +155,12 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     constexpr int WN = 4 / WM;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
+    constexpr int NT = 256 * KG;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kgrp = KG > 1 ? wave8 >> 2 : 0;               // which steps of the contraction this wave takes
+    const int wave = wave8 & 3;
     const int wm = wave % WM, wn = wave / WM;
     const int n16 = lane & 15, kg = lane >> 4;
 
@@ -219,7 +230,9 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const int c0 = ch * a.CC;
         const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
         const int gcb0 = c0 / CB;
-        const int ksteps = a.RS * cbs;
+        const int ksteps_all = a.RS * cbs;
+        // this wave's steps: kgrp, kgrp + KG, ... (local index 0 .. ksteps - 1)
+        const int ksteps = KG > 1 ? (ksteps_all - kgrp + KG - 1) / KG : ksteps_all;
         const int last = ksteps - 1;
         // The weights come from L2 (several hundred clocks away, against 32 clocks per MFMA): the
         // operands of the next PF steps are kept in flight in a ring of registers.  The ring is
@@ -227,12 +240,13 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
         uint4w aq[PF][MW], bq[2][NW];
         StepCursor wc{0, 0, 0, 0}, xc_{0, 0, 0, 0};
+        if (KG > 1 && kgrp) { wc.advance(cbs, a.S, ksteps > 0); xc_.advance(cbs, a.S, ksteps > 0); }
         int wk = 0;                                          // step the weight cursor stands on
         auto fetch_w = [&](uint4w (&av)[MW]) {
             const uint4w* wu = wfrag + ((int64_t)mblk0 * wrow + (wc.tap * a.NCB + gcb0 + wc.cb) * 64);
 #pragma unroll
             for (int m = 0; m < MW; ++m) av[m] = wu[m * wrow + lane];
-            wc.advance(cbs, a.S, wk < last);
+            wc.template advance<KG>(cbs, a.S, wk < last);
             wk += wk < last ? 1 : 0;
         };
         int xk = 0;
@@ -240,27 +254,30 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
             const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
 #pragma unroll
             for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
-            xc_.advance(cbs, a.S, xk < last);
+            xc_.template advance<KG>(cbs, a.S, xk < last);
             xk += xk < last ? 1 : 0;
         };
+        // (a wave without steps in this chunk -- the second group of a one-step chunk -- fetches nothing)
+        if (KG == 1 || ksteps > 0) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
+            for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
+        }
         if (ch > 0) __syncthreads();     // the previous chunk has been multiplied
         // ------------------------------------------------------------ stage the chunk, transposed
         {
             const X* xc = xb + (int64_t)c0 * plane;
             const int cleft = a.C - c0;                      // channels of the layer from c0 on
             switch (a.epv) {
-                case 16: if constexpr (sizeof(X) == 1) { stage_chunk<X, CV, 16>(xc, lds, tid, cgroups, cleft, sa, a, plane); } break;
-                case 8: stage_chunk<X, CV, 8>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                case 4: stage_chunk<X, CV, 4>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                case 2: stage_chunk<X, CV, 2>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                default: stage_chunk<X, CV, 1>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                case 16: if constexpr (sizeof(X) == 1) { stage_chunk<X, CV, 16, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); } break;
+                case 8: stage_chunk<X, CV, 8, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                case 4: stage_chunk<X, CV, 4, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                case 2: stage_chunk<X, CV, 2, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
+                default: stage_chunk<X, CV, 1, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
             }
         }
         __syncthreads();
         // ------------------------------------------------------------ multiply
-        fetch_x(bq[0]);
+        if (KG == 1 || ksteps > 0) fetch_x(bq[0]);
         __builtin_amdgcn_sched_barrier(0);
         const int main_steps = ksteps / PF * PF;
         for (int ks = 0; ks < main_steps; ks += PF) {
@@ -289,6 +306,34 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
             }
         }
     }
+    if constexpr (KG > 1) {
+        // ------------------------------------------------------------ the two step groups meet: the
+        // second puts its accumulator blocks into LDS (the tile has been consumed), the first adds them
+        using A = typename Types<DT>::A;
+        __syncthreads();
+        A* ex = reinterpret_cast<A*>(lds);
+        if (kgrp == 1) {
+#pragma unroll
+            for (int m = 0; m < MW; ++m)
+#pragma unroll
+                for (int i = 0; i < NW; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        ex[((wm * MW + m) * 16 + 4 * kg + j) * a.epi_pitch + (wn * NW + i) * 16 + n16] = acc[m][i][j];
+        }
+        __syncthreads();
+        if (kgrp == 1) {
+            if (!a.epi_pool) return;                       // (the pooling epilogue below needs every thread)
+        } else {
+#pragma unroll
+            for (int m = 0; m < MW; ++m)
+#pragma unroll
+                for (int i = 0; i < NW; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[m][i][j] += ex[((wm * MW + m) * 16 + 4 * kg + j) * a.epi_pitch + (wn * NW + i) * 16 + n16];
+        }
+    }
     if (a.epi_pool) {
         // ------------------------------------------------------------ fused epilogue with pooling: the waves
         // put their accumulator blocks into LDS as [output channel][tile position] (the tile has
@@ -299,13 +344,15 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         using A = typename Types<DT>::A;
         __syncthreads();
         A* ex = reinterpret_cast<A*>(lds);
+        if (kgrp == 0) {
 #pragma unroll
-        for (int m = 0; m < MW; ++m)
+            for (int m = 0; m < MW; ++m)
 #pragma unroll
-            for (int i = 0; i < NW; ++i)
+                for (int i = 0; i < NW; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    ex[((wm * MW + m) * 16 + 4 * kg + j) * a.epi_pitch + (wn * NW + i) * 16 + n16] = acc[m][i][j];
+                    for (int j = 0; j < 4; ++j)
+                        ex[((wm * MW + m) * 16 + 4 * kg + j) * a.epi_pitch + (wn * NW + i) * 16 + n16] = acc[m][i][j];
+        }
         __syncthreads();
         const int pl = a.epi_pool ? 2 : 1;
         const int TPo = a.TP / pl;                          // output rows of y per tile (TP is even, or the whole plane)
@@ -313,12 +360,12 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const float inv_per_s = 1.0f / (float)max(per_s, 1), inv_Qo = 1.0f / (float)a.Qo;
         const int prow0 = p0 / pl;
         // a thread keeps to one element position of the tile (decoded once) and walks over the
-        // output channels; the 256 threads are laid out as (channel group, position) with the
+        // output channels; the threads are laid out as (channel group, position) with the
         // positions a power of two wide, so that small tiles still use every thread and the
         // stores of a wave run along the rows of y
         int pw2 = 1;
-        while (pw2 < per_d && pw2 < 256) pw2 <<= 1;
-        const int dgroups = 256 / pw2;
+        while (pw2 < per_d && pw2 < NT) pw2 <<= 1;
+        const int dgroups = NT / pw2;
         const int o_first = tid & (pw2 - 1), dg = tid / pw2;
         for (int o = o_first; o < per_d; o += pw2) {
             const int sm = fdiv19(o, inv_per_s);
@@ -397,12 +444,12 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     }
 }
 
-template <sc_dtype_t DT, int MW, int NW, int WM>
-static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = mfma_conv_kernel<DT, MW, NW, WM>;
+    auto kernel = mfma_conv_kernel<DT, MW, NW, WM, KG>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -410,9 +457,16 @@ static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void*
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     });
     if (attr_err != hipSuccess) return SC_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.mg.lds_bytes, stream, static_cast<const X*>(x),
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG), p.mg.lds_bytes, stream, static_cast<const X*>(x),
                        static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+
+template <sc_dtype_t DT, int MW, int NW, int WM>
+static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
+{
+    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2>(p, a, x, y, grid, stream)
+                        : launch_mfma_kg<DT, MW, NW, WM, 1>(p, a, x, y, grid, stream);
 }
 
 template <sc_dtype_t DT, int MW, int WM>

@@ -255,6 +255,9 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
     const int budget = kMaxLdsBytes / t.wg_per_cu;
     const int CB = mfma_chan_block(p.dtype);
+    // 256 threads: four waves; 512: two groups of four that split the steps of the contraction
+    if (t.wg_threads != 0 && t.wg_threads != 256 && t.wg_threads != 512) return SC_ERR_UNSUPPORTED;
+    const int KG = t.wg_threads == 512 ? 2 : 1;
     if (t.waves_m != 0 && t.waves_m != 1 && t.waves_m != 2 && t.waves_m != 4) return SC_ERR_UNSUPPORTED;
     int DB = t.tile_d;
     if (DB == 0) DB = L.D > 64 ? 128 : (L.D > 32 ? 64 : (L.D > 16 ? 32 : 16));
@@ -277,9 +280,9 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     MfmaGeom g{};
     for (;;) {
         bool ok = false;
-        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g);
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG);
         else
-            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g);
+            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG);
         if (ok) break;
         if (fixed_tile) return SC_ERR_UNSUPPORTED;
         // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
@@ -289,7 +292,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     }
     sc_tuning_t r{};
     r.variant = SC_VARIANT_DENSE;
-    r.wg_threads = 256;
+    r.wg_threads = 256 * KG;
     r.tile_p = g.TP;
     r.sub_batch = g.NS;
     r.chunk_c = g.CC;
@@ -1012,14 +1015,16 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     if (p.dtype != SC_F32 && !p.has_dup && p.n > 0) {
         for (int db : {32, 64, 128}) for (int wm : {1, 2, 4}) for (int wpc : {1, 2, 3}) {
             if (db % (16 * wm) || db / (16 * wm) > 4 || (db > 32 && db >= 2 * p.L.D)) continue;
-            auto base = [&]() { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.waves_m = wm; t.wg_per_cu = wpc; return t; };
-            push(base());
-            for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
-                if (tp >= p.P) continue;
-                sc_tuning_t t = base(); t.tile_p = tp; push(t);
-            }
-            for (int ns : {1, 2, 4, 8, 16}) {
-                sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
+            for (int thr : {256, 512}) {
+                auto base = [&]() { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.waves_m = wm; t.wg_per_cu = wpc; t.wg_threads = thr; return t; };
+                push(base());
+                for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
+                    if (tp >= p.P) continue;
+                    sc_tuning_t t = base(); t.tile_p = tp; push(t);
+                }
+                for (int ns : {1, 2, 4, 8, 16}) {
+                    sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
+                }
             }
         }
     }

@@ -831,7 +831,8 @@ def test_dense_variant_on_the_matrix_cores(dtype):
               ("deep_pointwise", 200, 37, 7, 7, 1, 1, 1, 1, 0, 0, 7, 0.7),
               ("stride2", 70, 20, 13, 12, 3, 3, 2, 2, 1, 1, 3, 0.5),
               ("rect_pad", 40, 130, 6, 17, 2, 3, 1, 2, 0, 2, 2, 0.6),
-              ("tiny_plane", 96, 48, 2, 2, 3, 3, 1, 1, 1, 1, 19, 0.9)]
+              ("tiny_plane", 96, 48, 2, 2, 3, 3, 1, 1, 1, 1, 19, 0.9),
+              ("one_step", 24, 40, 9, 8, 1, 1, 1, 1, 0, 0, 3, 0.5)]      # one channel block, one tap: a single step
     for name, C, D, H, W, R, S, sh, sw, ph, pw, N, sp in shapes:
         l = wl.Layer(name, C, D, H, W, R, S, sh, sw, ph, pw, N=N, sparsity=sp, dtype=dtype, seed=777)
         data = wl.prepare(l)
@@ -844,17 +845,19 @@ def test_dense_variant_on_the_matrix_cores(dtype):
                       {"tile_d": 64, "waves_m": 2, "chunk_c": 64},
                       {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
                       {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
-            try:
-                plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, **extra)
-            except B.SparseConvError as e:
-                assert e.status == 4
-                continue
-            t = plan.get_tuning()
-            assert t.variant == B.SC_VARIANT_DENSE and t.wg_threads == 256
-            print("case dense", name, dtype, t.as_dict(), flush=True)
-            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense {extra}")
-            ran += 1
-        assert ran >= 3, (name, ran)
+            # four waves, and eight (two groups that split the steps of the contraction and meet in LDS)
+            for threads in (256, 512):
+                try:
+                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, **extra)
+                except B.SparseConvError as e:
+                    assert e.status == 4
+                    continue
+                t = plan.get_tuning()
+                assert t.variant == B.SC_VARIANT_DENSE and t.wg_threads == threads
+                print("case dense", name, dtype, t.as_dict(), flush=True)
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense {extra} {threads}")
+                ran += 1
+        assert ran >= 6, (name, ran)
         plan.destroy()
 
 
@@ -991,7 +994,9 @@ def test_fused_epilogue_relu_pool_requantise(dtype):
             for variant, extra in ((B.SC_VARIANT_GATHER, {}), (B.SC_VARIANT_GATHER, {"sub_batch": 2}),
                                    (B.SC_VARIANT_DENSE, {}), (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2}),
                                    (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2}),
-                                   (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 4, "waves_m": 4, "chunk_c": 64})):
+                                   (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 4, "waves_m": 4, "chunk_c": 64}),
+                                   (B.SC_VARIANT_DENSE, {"wg_threads": 512}), (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2, "wg_threads": 512}),
+                                   (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2, "wg_threads": 512})):
                 try:
                     plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
                 except B.SparseConvError as e:
