@@ -1168,3 +1168,43 @@ def test_channel_chunks_dealt_to_several_workgroups(dtype):
     with pytest.raises(B.SparseConvError):
         plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, chunk_c=8, split_n=2)
     plan.destroy()
+
+
+def test_forward_captured_in_a_hip_graph_replays_correctly():
+    """The forward path records kernels only (no memset, no allocation), so a caller may capture it:
+    a gather-kernel shape with its padding pre-pass, a split-K shape with its clear kernel, and the
+    matrix-core tile, each captured once and replayed three times with eager launches and
+    synchronisations in between; every replay is checked against the oracle on poisoned outputs."""
+    import torch
+    cases = (("f32", dict(variant=B.SC_VARIANT_GATHER, sub_batch=2)),
+             ("f32", dict(variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, chunk_c=8, split_n=3, tile_p=3, wg_threads=256)),
+             ("i8", dict(variant=B.SC_VARIANT_SLAB, wsrc=1, chunk_c=8, split_n=2, tile_p=3, wg_threads=256)),
+             ("f16", dict(variant=B.SC_VARIANT_DENSE, wg_threads=512)))
+    for dtype, tuning in cases:
+        l = wl.Layer("graph", 40, 24, 9, 7, 3, 3, 1, 1, 1, 1, N=6, sparsity=0.7, dtype=dtype, seed=101)
+        data = wl.prepare(l)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        plan.set_tuning(B.sc_tuning_t(), **tuning)
+        x = G.to_device(np.ascontiguousarray(data["x"]))
+        inf = plan.info()
+        y = torch.empty((l.N, l.D, inf.P, inf.Q), dtype=B.torch_out_dtype(plan.dtype), device="cuda")
+        ws = torch.empty(max(plan.workspace_size(l.N), 16), dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            plan.forward(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), side.cuda_stream)   # warm-up outside capture
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                plan.forward(x.data_ptr(), y.data_ptr(), l.N, ws.data_ptr(), ws.numel(), side.cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            y.view(torch.uint8).fill_(0x7f)                  # eager work between the replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            print("case graph", dtype, tuning, "replay", rep, flush=True)
+            G.check(l, G.to_host(y), ref, f"graph replay {rep} {dtype} {tuning}")
+        del g
+        plan.destroy()
