@@ -429,6 +429,8 @@ def short_shape(t):
         sh += {1: " pk32", 2: " pk128", 3: " si"}.get(t["pack"], f" pk?{t['pack']}")
     if t.get("split_n"):
         sh += f" ks{t['split_n']}"
+    if t.get("stage_rows"):
+        sh += " rows"
     if t.get("ragged"):
         sh += " ragged"
     return sh

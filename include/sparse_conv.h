@@ -173,6 +173,12 @@ typedef struct {
                            (producers is set to match when 0): every producer wave copies whole chunks by
                            itself, so that as many chunks as there are producers are in flight while one
                            is multiplied -- the memory latency of a chunk is spread over several phases */
+    int32_t stage_rows; /* SLAB with pack = 3, SC_F32: 1 = the interleaved samples are staged by rows -- a thread
+                           loads the same 16 (or 8) bytes of an input row of each of the 4 samples and
+                           writes 4 (2) LDS words -- instead of one table look-up and 4 element loads per
+                           word.  For unit strides (or strides of two) with tiles as wide as the plane
+                           and rows that are whole 16- or 8-byte loads; a caller whose x is not 16-byte
+                           aligned is served by the table form.  0 = by table */
 } sc_tuning_t;
 
 typedef struct {

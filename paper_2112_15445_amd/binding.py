@@ -49,7 +49,8 @@ class sc_tuning_t(ctypes.Structure):
                 ("wsrc", ctypes.c_int32), ("split_n", ctypes.c_int32),
                 ("pipeline", ctypes.c_int32), ("producers", ctypes.c_int32),
                 ("chunk_c", ctypes.c_int32), ("tile_d", ctypes.c_int32), ("ragged", ctypes.c_int32), ("pack", ctypes.c_int32),
-                ("waves_m", ctypes.c_int32), ("buffers", ctypes.c_int32)]
+                ("waves_m", ctypes.c_int32), ("buffers", ctypes.c_int32),
+                ("stage_rows", ctypes.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_}

@@ -252,7 +252,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu == 0) t.wg_per_cu = 2;
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q || t.buffers || t.stage_rows) return SC_ERR_UNSUPPORTED;
     const int budget = kMaxLdsBytes / t.wg_per_cu;
     const int CB = mfma_chan_block(p.dtype);
     // 256 threads: four waves; 512: two groups of four that split the steps of the contraction
@@ -384,6 +384,10 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
             t.sub_batch = g.ns > 1 ? g.ns : (g.fs > 1 ? g.fs : (g.sg > 1 ? g.sg : 0));
             t.split_n = ksplit > 1 ? ksplit : 0;
             g.ksplit = ksplit;
+            if (t.stage_rows) {
+                if (t.stage_rows != 1 || !g.si || p.dtype != SC_F32 || !slab_rows_stageable(p, g)) return SC_ERR_UNSUPPORTED;
+                g.srow = 1;
+            }
             if (t.pipeline >= 1) t.wg_per_cu = 1;
             if (t.chunk_c > 0) { t.chunk_c = g.CC; t.tile_d = g.DTW; }
             *out = t;
@@ -402,7 +406,7 @@ sc_status_t resolve_tuning(const Plan& p, const sc_tuning_t& in, sc_tuning_t* ou
         return SC_ERR_UNSUPPORTED;
     if (has_epilogue(p) && t.split_n != 1) return SC_ERR_UNSUPPORTED;
     t.tile_p = t.tile_q = t.wg_per_cu = t.wsrc = t.pipeline = t.producers = t.chunk_c = t.tile_d = t.ragged = 0;
-    if (t.pack || t.buffers) return SC_ERR_UNSUPPORTED;
+    if (t.pack || t.buffers || t.stage_rows) return SC_ERR_UNSUPPORTED;
     *out = t;
     *geom = SlabGeom{};
     return SC_OK;
@@ -1245,6 +1249,11 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
     }
     // 16- and 8-bit activations: the chunked one-shot form with packed positions (one LDS read per
     // 2 or 4 positions), tiles of up to 8 positions per lane
+    // (interleaved samples in fp32: every shape also with the samples staged by rows)
+    auto pushr = [&](sc_tuning_t t) {
+        push(t);
+        if (t.pack == 3 && p.dtype == SC_F32) { t.stage_rows = 1; push(t); }
+    };
     if ((packable || wide) && p.n > 0) {
         for (int wpc : {1, 2, 3}) for (int cc : {16, 24, 32, 48, 64, 96, 128, 256, 384, 512}) {
             const bool odd_cc = cc == 24 || cc == 48 || cc == 96;    // with interleaved samples only
@@ -1264,14 +1273,14 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     t.chunk_c = cc;
                     t.tile_d = td;
                     t.pack = pk;
-                    push(t);
+                    pushr(t);
                     // layers with fewer tiles than CUs: the chunks of a tile dealt to several workgroups
                     // (wide output-channel blocks, so that the input is staged few times)
                     if ((p.dtype == SC_F32 || p.dtype == SC_I8) && p.P * p.Q <= 256 && (td == 0 || td >= 64) && cc < p.L.C) {
                         for (int ks : {2, 4, 8}) {
                             sc_tuning_t t2 = t;
                             t2.split_n = ks;
-                            push(t2);
+                            pushr(t2);
                         }
                     }
                     // small planes: several sample groups along the lanes (refused unless they fit a wave)
@@ -1279,15 +1288,15 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                         for (int sg : {2, 4, 8}) {
                             sc_tuning_t t2 = t;
                             t2.sub_batch = sg;
-                            push(t2);
+                            pushr(t2);
                             if ((p.dtype == SC_F32 || p.dtype == SC_I8) && (td == 0 || td >= 32) && cc < p.L.C)
-                                for (int ks : {2, 4, 8}) { sc_tuning_t t3 = t2; t3.split_n = ks; push(t3); }
-                            if (p.L.D >= 256) { t2.wg_threads = 256; push(t2); t2.wg_threads = 512; push(t2); }
+                                for (int ks : {2, 4, 8}) { sc_tuning_t t3 = t2; t3.split_n = ks; pushr(t3); }
+                            if (p.L.D >= 256) { t2.wg_threads = 256; pushr(t2); t2.wg_threads = 512; pushr(t2); }
                         }
                     }
                     // (twelve waves: two such workgroups share a CU where the registers allow, one
                     // staging while the other multiplies)
-                    if (pk == 3 && p.dtype == SC_F32) { t.wg_threads = 768; push(t); }
+                    if (pk == 3 && p.dtype == SC_F32) { t.wg_threads = 768; pushr(t); }
                 }
             }
         }
@@ -1444,7 +1453,7 @@ static sc_status_t autotune_impl(sparse_conv_plan_t* plan, const void* x_dev, vo
                 // (shapes that deal the chunks of a tile to several workgroups, or keep a ring of chunk
                 // buffers, are families of their own)
                 const int split = (c.variant == SC_VARIANT_SLAB && c.split_n > 1) ? 1 : 0;
-                return (c.variant << 12) | (c.pipeline << 8) | (c.pack << 4) | (split << 3) | (c.buffers > 2 ? 4 : 0) |
+                return (c.variant << 13) | (c.stage_rows << 12) | (c.pipeline << 8) | (c.pack << 4) | (split << 3) | (c.buffers > 2 ? 4 : 0) |
                        (c.sub_batch > 1 ? 2 : 0) | (c.chunk_c > 0 ? 1 : 0);
             };
             // (two per family: the shape of a family that is fastest on cache-resident buffers is not

@@ -45,6 +45,7 @@ struct SlabGeom {
     int ns;                    // samples per workgroup (chunked one-shot form, tiles of <= 64 positions)
     int si;                    // 1: an LDS word holds the same position of `pack` consecutive samples (tuning.pack = 3)
     int sg;                    // ... and this many such sample groups per workgroup, laid along the lanes (tuning.sub_batch)
+    int srow;                  // interleaved samples staged by rows (tuning.stage_rows)
     int ksplit;                // chunked one-shot form: workgroups that share the chunks of a tile (tuning.split_n; 1: off)
     int nbuf;                  // chunk buffers of the producer/consumer form with channel chunks (2, or producers + 1)
     int fs;                    // samples laid end to end along the tile's position axis (packed one-shot chunked form on pointwise layers); 1: off
@@ -129,6 +130,7 @@ sc_status_t launch_gather(const Plan& p, const void* x, void* y, int N, void* ws
 // slab.hip
 sc_status_t launch_slab(const Plan& p, const void* x, void* y, int N, hipStream_t stream);
 int slab_grid_size(const Plan& p, const SlabGeom& g, int N);
+bool slab_rows_stageable(const Plan& p, const SlabGeom& g);   // tuning.stage_rows applies to this layer and tile
 sc_status_t expand_weights(const Plan& p, const int32_t* lam_slab, int2* wl32_out, hipStream_t stream);
 sc_status_t expand_weights_chunked(const Plan& p, const SlabGeom& g, const int32_t* lam_slab, const int32_t* seg_off,
                                    const int32_t* first_j, int2* wlc_out, hipStream_t stream);

@@ -1352,7 +1352,7 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
     // to end.  SMODE 2, SI: the workgroup takes E samples, an LDS word holds the same element of all
     // of them and slot k of a lane is position k * 64 + lane of each)
     constexpr bool FSM = SMODE == 1, SI = SMODE == 2;
-    static_assert(SMODE == 0 || (E > 1 && !MS && !LANES && !FLAT && ROWB == 0), "several samples per packed tile: staged by table or by blocks");
+    static_assert(SMODE == 0 || (E > 1 && !MS && !LANES && !FLAT && (ROWB == 0 || SMODE == 2)), "several samples per packed tile: staged by table, by blocks or (interleaved samples) by rows");
     const int b = MS ? bg * VPT : (FSM ? bg * a.FS : (SI ? bg * E * a.SG : bg));
     // (SI with several sample groups: lane = group * F + position, one slot per lane)
     const int lgrp = (SI && a.SG > 1) ? min(fdiv(lane, 1.0f / (float)a.F), a.SG - 1) : 0;
@@ -1495,7 +1495,59 @@ slab_cc_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::
                 }
             }
         }
-        if constexpr (SI) {
+        if constexpr (SI && ROWB > 0) {
+            // interleaved samples staged by rows: a thread loads the same ROWB bytes (RV adjacent
+            // columns of one input row) of each of the E samples and writes them into RV words, word j
+            // holding column j of every sample.  Two index divisions per E loads instead of one per
+            // word and load, wide loads along the rows; the padding words were cleared once.
+            staged = true;
+            struct alignas(ROWB) Vec { X e[RV]; };
+            struct alignas(E * sizeof(X)) Word { X e[E]; };
+            const int nvec = min(a.CC, a.C - c0) * per_c;
+            for (int sg = 0; sg < a.SG; ++sg) {
+                Word* wslab = reinterpret_cast<Word*>(lds) + sg * img_elems;
+                const X* xc = xb + (int64_t)sg * E * a.x_sample_stride + (int64_t)c0 * plane;
+                const int bs = b + sg * E;                       // first sample of this group
+                for (int i = tid; i < nvec; i += nthreads) {
+                    const int c = fdiv(i, inv_per_c);
+                    const int r2 = i - c * per_c;
+                    const int ir = fdiv(r2, inv_vpr);
+                    const int vv = r2 - ir * vpr;
+                    const X* src = xc + (int64_t)c * plane + (rlo + ir) * a.Wf + vv * RV;
+                    const int t_r = rlo - row0 + ir;
+                    const int tc0 = a.pad_w + vv * RV;
+                    const int dsti = a.s_h == 1 ? c * a.chan_pitch + t_r * a.Qs + tc0
+                                                : c * a.chan_pitch + (t_r & 1) * 2 * a.sub_pitch + (t_r >> 1) * a.Qs;
+                    // all E loads first, then RV word stores.  Lane l writes its columns in the order
+                    // (j + l / 4) mod RV: the words of one lane are RV words apart, so without the
+                    // rotation every fourth lane would meet on the same LDS banks
+                    Vec v[E];
+#pragma unroll
+                    for (int sm = 0; sm < E; ++sm) {
+#pragma unroll
+                        for (int j = 0; j < RV; ++j) v[sm].e[j] = X(0);
+                        if (bs + sm < a.N) v[sm] = *reinterpret_cast<const Vec*>(src + (int64_t)sm * a.x_sample_stride);
+                    }
+                    const int rot = (lane >> 2) & (RV - 1);
+#pragma unroll
+                    for (int j = 0; j < RV; ++j) {
+                        const int jj = (j + rot) & (RV - 1);
+                        Word w;
+#pragma unroll
+                        for (int sm = 0; sm < E; ++sm) {
+                            X val = v[sm].e[0];
+#pragma unroll
+                            for (int q = 1; q < RV; ++q) val = jj == q ? v[sm].e[q] : val;
+                            w.e[sm] = val;
+                        }
+                        const int t_c = tc0 + jj;
+                        const int dst = a.s_h == 1 ? dsti + jj : dsti + (t_c & 1) * a.sub_pitch + (t_c >> 1);
+                        wslab[dst] = w;
+                    }
+                }
+            }
+        }
+        if constexpr (SI && ROWB == 0) {
             // one word per element of the chunk image: that element of each of the E samples
             // (zero where the image shows padding or the batch has ended)
             staged = true;
@@ -1747,10 +1799,9 @@ static sc_status_t launch_cc_w(const Plan& p, const SlabArgs& a, const void* x, 
 
 // Bytes per load of the row-run staging this layer, tile and pointer allow (0: stage by table):
 // unit strides, a tile as wide as the plane, rows that are a whole number of such loads.
-static int row_run_bytes(const Plan& p, const void* x)
+static int row_run_bytes_geom(const Plan& p, const SlabGeom& g, const void* x, bool interleaved)
 {
-    const SlabGeom& g = p.geom;
-    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1 || g.fs != 1 || g.si) return 0;
+    if (g.tiles_q != 1 || g.TQ != g.Qf || g.ns != 1 || g.fs != 1 || (g.si != 0) != interleaved) return 0;
     if (g.Hf == 1) return 0;                                      // flattened pointwise layers
     if (p.L.stride_h == 1 && p.L.stride_w == 1) {
         if (g.Qs != g.Wf + 2 * p.L.pad_w) return 0;
@@ -1766,6 +1817,8 @@ static int row_run_bytes(const Plan& p, const void* x)
         if (b > p.ex && row_bytes % b == 0) return b;
     return 0;
 }
+static int row_run_bytes(const Plan& p, const void* x, bool interleaved = false) { return row_run_bytes_geom(p, p.geom, x, interleaved); }
+bool slab_rows_stageable(const Plan& p, const SlabGeom& g) { return row_run_bytes_geom(p, g, nullptr, true) >= 8; }
 
 template <sc_dtype_t DT, int VPT, bool MS, int E = 1>
 static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x, void* y, int grid,
@@ -1780,7 +1833,14 @@ static sc_status_t launch_cc_one(const Plan& p, const SlabArgs& a, const void* x
         return SC_ERR_UNSUPPORTED;
     }
     if (p.geom.si) {
-        // the same position of E samples in one word: its own instantiation, staged by table
+        // the same position of E samples in one word: its own instantiation, staged by table or
+        // (32-bit activations, rows that are whole 16- or 8-byte loads) by rows
+        if constexpr (DT == SC_F32 && E == 4 && !MS) {
+            switch (p.geom.srow ? row_run_bytes(p, x, true) : 0) {
+                case 16: return launch_cc_w<DT, VPT, MS, E, false, false, 16, 2>(p, a, x, y, grid, stream);
+                case 8: return launch_cc_w<DT, VPT, MS, E, false, false, 8, 2>(p, a, x, y, grid, stream);
+            }
+        }
         if constexpr (E > 1 && !MS) return launch_cc_w<DT, VPT, MS, E, false, false, 0, 2>(p, a, x, y, grid, stream);
         return SC_ERR_UNSUPPORTED;
     }

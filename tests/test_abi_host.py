@@ -51,7 +51,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     assert c == [ctypes.sizeof(B.sc_layer_t), ctypes.sizeof(B.sc_tuning_t), ctypes.sizeof(B.sc_plan_info_t),
                  B.sc_plan_info_t.tuning.offset, B.sc_tuning_t.ragged.offset, B.sc_tuning_t.pack.offset,
                  B.sc_plan_info_t.weight_bytes.offset]
-    assert ctypes.sizeof(B.sc_layer_t) == 40 and ctypes.sizeof(B.sc_tuning_t) == 16 * 4
+    assert ctypes.sizeof(B.sc_layer_t) == 40 and ctypes.sizeof(B.sc_tuning_t) == 17 * 4
 
 
 def _expect(status, fn, *a, **k):

@@ -1208,3 +1208,42 @@ def test_forward_captured_in_a_hip_graph_replays_correctly():
             G.check(l, G.to_host(y), ref, f"graph replay {rep} {dtype} {tuning}")
         del g
         plan.destroy()
+
+
+def test_interleaved_samples_staged_by_rows():
+    """tuning.stage_rows = 1 (fp32, pack = 3): rows of 16- and 8-byte loads, strides of one and two, tiles
+    at the top and bottom edge of the plane, several chunks with a short last one, sample groups,
+    split-K, batches that end inside a word; refused where rows are no whole 8-byte loads, where the
+    tile is narrower than the plane, for other types and without interleaved samples."""
+    cases = ((wl.Layer("rows16", 40, 24, 9, 8, 3, 3, 1, 1, 1, 1, N=7, sparsity=0.7, dtype="f32", seed=111),
+              [dict(tile_p=3, chunk_c=8), dict(tile_p=9, chunk_c=16, tile_d=8), dict(tile_p=1, chunk_c=7, wg_threads=768),
+               dict(tile_p=2, chunk_c=8, split_n=3), dict(tile_p=4, chunk_c=12, sub_batch=1)]),
+             (wl.Layer("rows8", 24, 20, 6, 6, 3, 3, 1, 1, 1, 1, N=21, sparsity=0.6, dtype="f32", seed=112),
+              [dict(tile_p=2, chunk_c=8, sub_batch=3), dict(tile_p=6, chunk_c=24), dict(tile_p=3, chunk_c=5, split_n=4, tile_d=16)]),
+             (wl.Layer("rows_s2", 32, 20, 14, 12, 3, 3, 2, 2, 1, 1, N=5, sparsity=0.6, dtype="f32", seed=113),
+              [dict(tile_p=7, chunk_c=8), dict(tile_p=2, chunk_c=4, tile_d=8), dict(tile_p=3, chunk_c=16, split_n=2)]),
+             (wl.Layer("rows_5x5", 16, 12, 10, 12, 5, 5, 1, 1, 2, 2, N=3, sparsity=0.8, dtype="f32", seed=114),
+              [dict(tile_p=4, chunk_c=8)]))
+    for l, tunings in cases:
+        data = wl.prepare(l, ragged=True)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        for extra in tunings:
+            kw = dict(variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, stage_rows=1, wg_threads=256)
+            kw.update(extra)
+            plan.set_tuning(B.sc_tuning_t(), **kw)
+            t = plan.get_tuning().as_dict()
+            assert t["stage_rows"] == 1 and t["pack"] == 3
+            print("case", l.name, t, flush=True)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} {t}")
+        with pytest.raises(B.SparseConvError):          # without interleaved samples
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, stage_rows=1, chunk_c=8, tile_p=2)
+        with pytest.raises(B.SparseConvError):          # GATHER
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_GATHER, stage_rows=1)
+        plan.destroy()
+    for l in (wl.Layer("rows_odd", 16, 12, 9, 7, 3, 3, 1, 1, 1, 1, N=3, sparsity=0.5, dtype="f32", seed=115),     # rows of 28 bytes
+              wl.Layer("rows_f16", 16, 12, 8, 8, 3, 3, 1, 1, 1, 1, N=9, sparsity=0.5, dtype="f16", seed=116)):
+        plan = G.make_plan(l, wl.prepare(l))
+        with pytest.raises(B.SparseConvError):
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, stage_rows=1, chunk_c=8, tile_p=2)
+        plan.destroy()
