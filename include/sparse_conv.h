@@ -135,8 +135,15 @@ typedef struct {
                            no dedicated waves: every wave issues its share of the copy of tile i+1 and
                            then multiplies its rows of tile i (contiguous row ranges, one barrier per
                            tile); needs wsrc = 1 and at least one stored weight per row; with chunk_c > 0 at
-                           most 4 positions per lane and 8 rows per wave.  0 = one tile per workgroup */
-    int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4) */
+                           most 4 positions per lane and 8 rows per wave.  0 = one tile per workgroup.
+                           DENSE: 1 = the chunks of input channels are staged by `producers` waves of their
+                           own into two LDS buffers, one chunk ahead of the multiplying waves (which run
+                           over the steps of all chunks without draining their weights in flight);
+                           chunk_c then defaults to two channel blocks.  Same results as with 0 for four
+                           multiplying waves; with eight, the two groups split the steps of the whole
+                           contraction instead of each chunk's (another fixed summation order) */
+    int32_t producers;  /* SLAB with pipeline = 1: waves of the workgroup that only copy tiles (1, 2 or 4);
+                           DENSE with pipeline = 1: staging waves behind the multiplying ones (1 .. 4, 0 = 2) */
     int32_t chunk_c;    /* SLAB: input channels per LDS buffer (0 = all of them); with pipeline = 0 for any
                            layer shape (wsrc = 1 or 3, at most 4 positions per lane and 8 rows per wave), with
                            pipeline = 1 or 2 for pointwise layers (wsrc = 1).  With

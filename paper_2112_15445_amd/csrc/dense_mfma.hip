@@ -103,7 +103,7 @@ sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream)
 // ------------------------------------------------------------------------------------------------
 // Geometry of one (plan, tuning) pair, derived on the host.
 // ------------------------------------------------------------------------------------------------
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG)
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG, int PW)
 {
     const sc_layer_t& L = p.L;
     MfmaGeom g{};
@@ -136,9 +136,13 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     if (nw > 8) return false;
     g.NW = nw <= 1 ? 1 : (nw <= 2 ? 2 : (nw <= 4 ? 4 : 8));
     if (g.NW == 8 && g.MW == 4) return false;     // 32 accumulator blocks per wave: not instantiated
-    int64_t lds = (int64_t)g.npos_s * g.pitch;
     if (KG != 1 && KG != 2) return false;
     g.KG = KG;
+    if (PW < 0 || PW > 4) return false;
+    g.PW = PW;
+    // the pipelined form keeps two chunk buffers (one if the layer is a single chunk)
+    g.bufsz = (int)(((int64_t)g.npos_s * g.pitch + 15) / 16 * 16);
+    int64_t lds = (int64_t)g.bufsz * (PW > 0 && g.nchunks > 1 ? 2 : 1);
     // pooling windows must not straddle tiles
     if (has_epilogue(p) && p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
     if ((has_epilogue(p) && p.epi.pool) || KG == 2) {
@@ -169,6 +173,14 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     a.C = p.L.C; a.D = p.L.D; a.N = N; a.H = p.L.H; a.W = p.L.W; a.P = p.P; a.Q = p.Q;
     a.S = p.L.S; a.RS = p.L.R * p.L.S; a.s_h = p.L.stride_h; a.s_w = p.L.stride_w; a.pad_h = p.L.pad_h; a.pad_w = p.L.pad_w;
     a.TP = g.TP; a.NS = g.NS; a.tiles_p = g.tiles_p; a.Hs = g.Hs; a.Ws = g.Ws; a.npos_s = g.npos_s; a.npos = g.npos;
+    a.bufsz = g.bufsz;
+    {
+        const int ccb = g.CC / mfma_chan_block(p.dtype);
+        a.cbs_last = g.NCB - (g.nchunks - 1) * ccb;
+        a.inv_spc = 1.0f / (float)(p.L.R * p.L.S * ccb); a.inv_ccb = 1.0f / (float)ccb;
+        a.inv_cbs_last = 1.0f / (float)a.cbs_last; a.inv_S = 1.0f / (float)p.L.S;
+        if (g.PW && (mfma_weight_bytes(p) >= (1ull << 31) || (int64_t)p.L.R * p.L.S * g.NCB >= (1 << 18))) return SC_ERR_UNSUPPORTED;
+    }
     a.CC = g.CC; a.nchunks = g.nchunks; a.NCB = g.NCB; a.pitch = g.pitch; a.DB = g.DB; a.ndb = g.ndb;
     a.epi = has_epilogue(p) ? 1 : 0; a.epi_relu = p.epi.relu; a.epi_pool = p.epi.pool; a.epi_pitch = g.epi_pitch;
     a.Po = p.Po; a.Qo = p.Qo; a.requant = p.epi.requant ? p.d_requant : nullptr;
@@ -185,9 +197,9 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     switch (p.dtype) {
         // (the codebook variants were decoded when the weights were densified: same arithmetic)
         case SC_F16:
-        case SC_CB4_F16: return launch_mfma_f16(p, a, x, y, (int)grid, stream);
+        case SC_CB4_F16: return g.PW ? launch_mfma_pipe_f16(p, a, x, y, (int)grid, stream) : launch_mfma_f16(p, a, x, y, (int)grid, stream);
         case SC_I8:
-        case SC_CB4_I8: return launch_mfma_i8(p, a, x, y, (int)grid, stream);
+        case SC_CB4_I8: return g.PW ? launch_mfma_pipe_i8(p, a, x, y, (int)grid, stream) : launch_mfma_i8(p, a, x, y, (int)grid, stream);
         default: return SC_ERR_UNSUPPORTED;
     }
 }

@@ -29,6 +29,10 @@ template <sc_dtype_t DT> constexpr int kChanVec = kIntActs<DT> ? 16 : 8;
 struct MfmaArgs {
     int C, D, N, H, W, P, Q, S, RS, s_h, s_w, pad_h, pad_w;
     int TP, NS, tiles_p, Hs, Ws, npos_s, npos, CC, nchunks, NCB, pitch, DB, ndb, epv;
+    // pipelined form: bytes of one of the two chunk buffers; channel blocks of the last chunk; reciprocals
+    // of the steps per full chunk, of the channel blocks per chunk (full, last) and of S
+    int bufsz, cbs_last;
+    float inv_spc, inv_ccb, inv_cbs_last, inv_S;
     float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q;
     // fused epilogue (epi = 0: none): ReLU, 2 x 2 max-pooling, requantisation multipliers (or NULL),
     // row pitch of the LDS exchange, extents of y
@@ -38,6 +42,8 @@ struct MfmaArgs {
 
 sc_status_t launch_mfma_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_pipe_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_pipe_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 
 // floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
 // product at least 1/(2d) away from every integer, well above the two float roundings)
@@ -60,12 +66,36 @@ struct StageArgs {
     int wcols;             // input columns that are staged: [0, wcols)
 };
 
-template <typename X, int CV, int EPV, int NT>
-__device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned char* lds, int tid, int cgroups, int cleft,
+// blocks a thread has in flight per round: the multiplying waves keep this small (their registers
+// hold accumulators); waves that only stage (the pipelined kernel) take about 64 registers' worth
+template <int EPV> constexpr int kStageVB = EPV >= 8 ? 1 : (EPV >= 2 ? 2 : 4);
+template <typename X, int CV, int EPV>
+constexpr int stage_vb_wide()
+{
+    const int words = EPV * (int)sizeof(X) >= 4 ? EPV * (int)sizeof(X) / 4 : 1;   // registers per load
+    const int v = 64 / (CV * words);
+    return v > 8 ? 8 : (v < 1 ? 1 : v);
+}
+
+// padding: staged positions outside the input or past the batch are zeros
+__device__ __forceinline__ void stage_pad(unsigned char* lds, int tid, int NT, int cgroups, const StageArgs& sa, const MfmaArgs& a)
+{
+    for (int pos = tid; pos < a.npos_s; pos += NT) {
+        const int sm = fdiv19(pos, a.inv_HsWs);
+        const int rem = pos - sm * (a.Hs * a.Ws);
+        const int i = fdiv19(rem, a.inv_Ws);
+        const int w = rem - i * a.Ws;
+        const bool inside = sm < sa.nsv && i >= sa.ilo && i < sa.ilo + sa.nrows && w >= a.pad_w && w < a.pad_w + sa.wcols;
+        if (!inside)
+            for (int cg = 0; cg < cgroups; ++cg) *reinterpret_cast<uint4w*>(lds + pos * a.pitch + cg * 16) = uint4w{0u, 0u, 0u, 0u};
+    }
+}
+
+template <typename X, int CV, int EPV, int VB>
+__device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned char* lds, int tid, int NT, int cgroups, int cleft,
                                             const StageArgs& sa, const MfmaArgs& a, int plane)
 {
     struct alignas(EPV * sizeof(X)) Vec { X e[EPV]; };
-    constexpr int VB = EPV >= 8 ? 1 : (EPV >= 2 ? 2 : 4);
     const int G = (sa.wcols + EPV - 1) / EPV;
     const int rowsG = sa.nrows * G, per_cg = sa.nsv * rowsG;
     const int nblocks = cgroups * per_cg;
@@ -107,16 +137,23 @@ __device__ __forceinline__ void stage_chunk(const X* __restrict__ xc, unsigned c
             }
         }
     }
-    // padding: staged positions outside the input or past the batch
-    for (int pos = tid; pos < a.npos_s; pos += NT) {
-        const int sm = fdiv19(pos, a.inv_HsWs);
-        const int rem = pos - sm * (a.Hs * a.Ws);
-        const int i = fdiv19(rem, a.inv_Ws);
-        const int w = rem - i * a.Ws;
-        const bool inside = sm < sa.nsv && i >= sa.ilo && i < sa.ilo + sa.nrows && w >= a.pad_w && w < a.pad_w + sa.wcols;
-        if (!inside)
-            for (int cg = 0; cg < cgroups; ++cg) *reinterpret_cast<uint4w*>(lds + pos * a.pitch + cg * 16) = uint4w{0u, 0u, 0u, 0u};
+}
+
+// the same for the load width the launch found (elements per load: the widest power of two, up to
+// 16 bytes, that divides the row length and the caller's pointer)
+template <typename X, int CV, bool WIDE>
+__device__ __forceinline__ void stage_chunk_epv(int epv, const X* __restrict__ xc, unsigned char* lds, int tid, int NT, int cgroups,
+                                                int cleft, const StageArgs& sa, const MfmaArgs& a, int plane)
+{
+#define SC_STAGE(E) stage_chunk<X, CV, E, WIDE ? stage_vb_wide<X, CV, E>() : kStageVB<E>>(xc, lds, tid, NT, cgroups, cleft, sa, a, plane)
+    switch (epv) {
+        case 16: if constexpr (sizeof(X) == 1) { SC_STAGE(16); } break;
+        case 8: SC_STAGE(8); break;
+        case 4: SC_STAGE(4); break;
+        case 2: SC_STAGE(2); break;
+        default: SC_STAGE(1); break;
     }
+#undef SC_STAGE
 }
 
 // One step of the contraction = one filter tap x one block of CB input channels of the resident
@@ -140,172 +177,17 @@ struct StepCursor {
     }
 };
 
-// KG = 2: eight waves.  The two groups of four waves own the same outputs and take the even and the odd
-// steps of the contraction; their accumulators meet through LDS at the end (a fixed order: the
-// result does not depend on timing).  Two waves then share a SIMD, which is what the matrix
-// instructions need to issue back to back, at no more traffic: every operand is still fetched once.
-template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
-__global__ void __launch_bounds__(256 * KG)
-mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
-                 const uint4w* __restrict__ wfrag, const MfmaArgs a)
+// ------------------------------------------------------------------------------------------------
+// What follows the contraction, shared by the kernels below: the step groups add up their
+// accumulators (KG = 2), then the outputs are stored, with the fused epilogue if the plan has one.
+// Called by the 256 * KG multiplying threads of the workgroup (tid = 0 .. 256 * KG - 1), all of them.
+// ------------------------------------------------------------------------------------------------
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, typename Acc>
+__device__ __forceinline__ void mfma_finish(Acc (&acc)[MW][NW], const MfmaArgs& a, unsigned char* lds,
+                                            typename Types<DT>::Y* __restrict__ y, int tid, int kgrp, int wm, int wn, int kg,
+                                            int n16, int mblk0, const int64_t (&yoff)[NW], int b0, int p0, int db, int PQ)
 {
-    using X = typename Types<DT>::X;
-    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
-    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
-    constexpr int WN = 4 / WM;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-
     constexpr int NT = 256 * KG;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kgrp = KG > 1 ? wave8 >> 2 : 0;               // which steps of the contraction this wave takes
-    const int wave = wave8 & 3;
-    const int wm = wave % WM, wn = wave / WM;
-    const int n16 = lane & 15, kg = lane >> 4;
-
-    // workgroup -> (sample group, row tile, output-channel block); the blocks of one tile are
-    // neighbours so that they find the tile in the L2 their siblings loaded.  Workgroups are dealt
-    // round-robin to the 8 XCDs: number them so that each XCD gets a contiguous run.
-    const int grid = gridDim.x;
-    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int bt = fdiv19(wg, a.inv_ndb);
-    const int db = wg - bt * a.ndb;
-    const int bg = fdiv19(bt, a.inv_tiles_p);
-    const int tpi = bt - bg * a.tiles_p;
-    const int b0 = bg * a.NS, p0 = tpi * a.TP;
-    const int row0 = p0 * a.s_h - a.pad_h;
-    const int plane = a.H * a.W, PQ = a.P * a.Q;
-
-    // positions of this lane's NW column blocks: byte offset of the staged position in LDS (plus
-    // the lane's k group) and element offset of the output inside y, or -1
-    int bbase[NW];
-    int64_t yoff[NW];
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const int f = ((wn * NW + i) * 16 + n16);
-        const int sm = fdiv19(f, a.inv_TPQ);
-        const int rem = f - sm * (a.TP * a.Q);
-        const int tp = fdiv19(rem, a.inv_Q);
-        const int tq = rem - tp * a.Q;
-        const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
-        bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
-        yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
-    }
-
-    Acc acc[MW][NW];
-#pragma unroll
-    for (int m = 0; m < MW; ++m)
-#pragma unroll
-        for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
-
-    const int mblk0 = db * (a.DB >> 4) + wm * MW;            // first 16-row block of this wave
-    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
-
-    StageArgs sa;
-    sa.nsv = min(a.NS, a.N - b0);
-    sa.ilo = max(0, -row0);
-    sa.nrows = max(0, min(a.Hs, a.H - row0) - sa.ilo);
-    sa.rlo = row0 + sa.ilo;
-    sa.wcols = min(a.W, a.Ws - a.pad_w);
-    const X* xb = x + (int64_t)b0 * a.C * plane;
-    // the weights of row block m of this wave: a wave-uniform base, the lane adds its 16 bytes
-    const int wrow = a.RS * a.NCB * 64;                      // 16-byte words per 16-row block
-
-    auto multiply = [&](const uint4w (&av)[MW], const uint4w (&bv)[NW]) {
-#pragma unroll
-        for (int m = 0; m < MW; ++m)
-#pragma unroll
-            for (int i = 0; i < NW; ++i) {
-                if constexpr (kIntActs<DT>)
-                    acc[m][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av[m]),
-                                                                      __builtin_bit_cast(int4v_, bv[i]), acc[m][i], 0, 0, 0);
-                else
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av[m]),
-                                                                       __builtin_bit_cast(half8v, bv[i]), acc[m][i], 0, 0, 0);
-            }
-    };
-
-    for (int ch = 0; ch < a.nchunks; ++ch) {
-        const int c0 = ch * a.CC;
-        const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
-        const int gcb0 = c0 / CB;
-        const int ksteps_all = a.RS * cbs;
-        // this wave's steps: kgrp, kgrp + KG, ... (local index 0 .. ksteps - 1)
-        const int ksteps = KG > 1 ? (ksteps_all - kgrp + KG - 1) / KG : ksteps_all;
-        const int last = ksteps - 1;
-        // The weights come from L2 (several hundred clocks away, against 32 clocks per MFMA): the
-        // operands of the next PF steps are kept in flight in a ring of registers.  The ring is
-        // filled before the chunk is staged, so that its latency hides behind the copy.
-        constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
-        uint4w aq[PF][MW], bq[2][NW];
-        StepCursor wc{0, 0, 0, 0}, xc_{0, 0, 0, 0};
-        if (KG > 1 && kgrp) { wc.advance(cbs, a.S, ksteps > 0); xc_.advance(cbs, a.S, ksteps > 0); }
-        int wk = 0;                                          // step the weight cursor stands on
-        auto fetch_w = [&](uint4w (&av)[MW]) {
-            const uint4w* wu = wfrag + ((int64_t)mblk0 * wrow + (wc.tap * a.NCB + gcb0 + wc.cb) * 64);
-#pragma unroll
-            for (int m = 0; m < MW; ++m) av[m] = wu[m * wrow + lane];
-            wc.template advance<KG>(cbs, a.S, wk < last);
-            wk += wk < last ? 1 : 0;
-        };
-        int xk = 0;
-        auto fetch_x = [&](uint4w (&bv)[NW]) {
-            const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
-#pragma unroll
-            for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
-            xc_.template advance<KG>(cbs, a.S, xk < last);
-            xk += xk < last ? 1 : 0;
-        };
-        // (a wave without steps in this chunk -- the second group of a one-step chunk -- fetches nothing)
-        if (KG == 1 || ksteps > 0) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
-        }
-        if (ch > 0) __syncthreads();     // the previous chunk has been multiplied
-        // ------------------------------------------------------------ stage the chunk, transposed
-        {
-            const X* xc = xb + (int64_t)c0 * plane;
-            const int cleft = a.C - c0;                      // channels of the layer from c0 on
-            switch (a.epv) {
-                case 16: if constexpr (sizeof(X) == 1) { stage_chunk<X, CV, 16, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); } break;
-                case 8: stage_chunk<X, CV, 8, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                case 4: stage_chunk<X, CV, 4, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                case 2: stage_chunk<X, CV, 2, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-                default: stage_chunk<X, CV, 1, NT>(xc, lds, tid, cgroups, cleft, sa, a, plane); break;
-            }
-        }
-        __syncthreads();
-        // ------------------------------------------------------------ multiply
-        if (KG == 1 || ksteps > 0) fetch_x(bq[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        const int main_steps = ksteps / PF * PF;
-        for (int ks = 0; ks < main_steps; ks += PF) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                // Step ks + u: request the tile operands of the next step (from LDS), multiply,
-                // then refill this step's slot of the weight ring with the weights of step
-                // ks + u + PF -- after the MFMAs that read the slot, so that the slot keeps its
-                // registers from one round of the ring to the next.  The scheduling barriers keep
-                // the compiler from sinking the loads of later steps down to their first use, which
-                // would put the L2 latency back on the critical path.
-                fetch_x(bq[(u + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(aq[u], bq[u & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch_w(aq[u]);
-            }
-        }
-        // the last ksteps % PF steps: their weights are in the first slots of the ring (the cursor
-        // stopped at the last step), their tile operands alternate as before
-#pragma unroll
-        for (int u = 0; u < PF - 1; ++u) {
-            if (main_steps + u < ksteps) {
-                fetch_x(bq[(u + 1) & 1]);
-                multiply(aq[u], bq[u & 1]);
-            }
-        }
-    }
     if constexpr (KG > 1) {
         // ------------------------------------------------------------ the two step groups meet: the
         // second puts its accumulator blocks into LDS (the tile has been consumed), the first adds them
@@ -444,12 +326,382 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     }
 }
 
+// KG = 2: eight waves.  The two groups of four waves own the same outputs and take the even and the odd
+// steps of the contraction; their accumulators meet through LDS at the end (a fixed order: the
+// result does not depend on timing).  Two waves then share a SIMD, which is what the matrix
+// instructions need to issue back to back, at no more traffic: every operand is still fetched once.
 template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+__global__ void __launch_bounds__(256 * KG)
+mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                 const uint4w* __restrict__ wfrag, const MfmaArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
+    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    constexpr int NT = 256 * KG;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kgrp = KG > 1 ? wave8 >> 2 : 0;               // which steps of the contraction this wave takes
+    const int wave = wave8 & 3;
+    const int wm = wave % WM, wn = wave / WM;
+    const int n16 = lane & 15, kg = lane >> 4;
+
+    // workgroup -> (sample group, row tile, output-channel block); the blocks of one tile are
+    // neighbours so that they find the tile in the L2 their siblings loaded.  Workgroups are dealt
+    // round-robin to the 8 XCDs: number them so that each XCD gets a contiguous run.
+    const int grid = gridDim.x;
+    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int bt = fdiv19(wg, a.inv_ndb);
+    const int db = wg - bt * a.ndb;
+    const int bg = fdiv19(bt, a.inv_tiles_p);
+    const int tpi = bt - bg * a.tiles_p;
+    const int b0 = bg * a.NS, p0 = tpi * a.TP;
+    const int row0 = p0 * a.s_h - a.pad_h;
+    const int plane = a.H * a.W, PQ = a.P * a.Q;
+
+    int bbase[NW];
+    int64_t yoff[NW];
+    Acc acc[MW][NW];
+    auto decode_positions = [&] {
+        // positions of this lane's NW column blocks: byte offset of the staged position in LDS (plus
+        // the lane's k group) and element offset of the output inside y, or -1
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int f = ((wn * NW + i) * 16 + n16);
+            const int sm = fdiv19(f, a.inv_TPQ);
+            const int rem = f - sm * (a.TP * a.Q);
+            const int tp = fdiv19(rem, a.inv_Q);
+            const int tq = rem - tp * a.Q;
+            const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
+            bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+            yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
+        }
+
+#pragma unroll
+        for (int m = 0; m < MW; ++m)
+#pragma unroll
+            for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
+    };
+
+    decode_positions();
+    const int mblk0 = db * (a.DB >> 4) + wm * MW;            // first 16-row block of this wave
+    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
+
+    StageArgs sa;
+    sa.nsv = min(a.NS, a.N - b0);
+    sa.ilo = max(0, -row0);
+    sa.nrows = max(0, min(a.Hs, a.H - row0) - sa.ilo);
+    sa.rlo = row0 + sa.ilo;
+    sa.wcols = min(a.W, a.Ws - a.pad_w);
+    const X* xb = x + (int64_t)b0 * a.C * plane;
+    // the weights of row block m of this wave: a wave-uniform base, the lane adds its 16 bytes
+    const int wrow = a.RS * a.NCB * 64;                      // 16-byte words per 16-row block
+
+    auto multiply = [&](const uint4w (&av)[MW], const uint4w (&bv)[NW]) {
+#pragma unroll
+        for (int m = 0; m < MW; ++m)
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                if constexpr (kIntActs<DT>)
+                    acc[m][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av[m]),
+                                                                      __builtin_bit_cast(int4v_, bv[i]), acc[m][i], 0, 0, 0);
+                else
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av[m]),
+                                                                       __builtin_bit_cast(half8v, bv[i]), acc[m][i], 0, 0, 0);
+            }
+    };
+
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const int c0 = ch * a.CC;
+        const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
+        const int gcb0 = c0 / CB;
+        const int ksteps_all = a.RS * cbs;
+        // this wave's steps: kgrp, kgrp + KG, ... (local index 0 .. ksteps - 1)
+        const int ksteps = KG > 1 ? (ksteps_all - kgrp + KG - 1) / KG : ksteps_all;
+        const int last = ksteps - 1;
+        // The weights come from L2 (several hundred clocks away, against 32 clocks per MFMA): the
+        // operands of the next PF steps are kept in flight in a ring of registers.  The ring is
+        // filled before the chunk is staged, so that its latency hides behind the copy.
+        constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
+        uint4w aq[PF][MW], bq[2][NW];
+        StepCursor wc{0, 0, 0, 0}, xc_{0, 0, 0, 0};
+        if (KG > 1 && kgrp) { wc.advance(cbs, a.S, ksteps > 0); xc_.advance(cbs, a.S, ksteps > 0); }
+        int wk = 0;                                          // step the weight cursor stands on
+        auto fetch_w = [&](uint4w (&av)[MW]) {
+            const uint4w* wu = wfrag + ((int64_t)mblk0 * wrow + (wc.tap * a.NCB + gcb0 + wc.cb) * 64);
+#pragma unroll
+            for (int m = 0; m < MW; ++m) av[m] = wu[m * wrow + lane];
+            wc.template advance<KG>(cbs, a.S, wk < last);
+            wk += wk < last ? 1 : 0;
+        };
+        int xk = 0;
+        auto fetch_x = [&](uint4w (&bv)[NW]) {
+            const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
+#pragma unroll
+            for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+            xc_.template advance<KG>(cbs, a.S, xk < last);
+            xk += xk < last ? 1 : 0;
+        };
+        // (a wave without steps in this chunk -- the second group of a one-step chunk -- fetches nothing)
+        if (KG == 1 || ksteps > 0) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
+        }
+        if (ch > 0) __syncthreads();     // the previous chunk has been multiplied
+        // ------------------------------------------------------------ stage the chunk, transposed
+        {
+            const X* xc = xb + (int64_t)c0 * plane;
+            const int cleft = a.C - c0;                      // channels of the layer from c0 on
+            stage_chunk_epv<X, CV, false>(a.epv, xc, lds, tid, NT, cgroups, cleft, sa, a, plane);
+            stage_pad(lds, tid, NT, cgroups, sa, a);
+        }
+        __syncthreads();
+        // ------------------------------------------------------------ multiply
+        if (KG == 1 || ksteps > 0) fetch_x(bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int main_steps = ksteps / PF * PF;
+        for (int ks = 0; ks < main_steps; ks += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                // Step ks + u: request the tile operands of the next step (from LDS), multiply,
+                // then refill this step's slot of the weight ring with the weights of step
+                // ks + u + PF -- after the MFMAs that read the slot, so that the slot keeps its
+                // registers from one round of the ring to the next.  The scheduling barriers keep
+                // the compiler from sinking the loads of later steps down to their first use, which
+                // would put the L2 latency back on the critical path.
+                fetch_x(bq[(u + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(aq[u], bq[u & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_w(aq[u]);
+            }
+        }
+        // the last ksteps % PF steps: their weights are in the first slots of the ring (the cursor
+        // stopped at the last step), their tile operands alternate as before
+#pragma unroll
+        for (int u = 0; u < PF - 1; ++u) {
+            if (main_steps + u < ksteps) {
+                fetch_x(bq[(u + 1) & 1]);
+                multiply(aq[u], bq[u & 1]);
+            }
+        }
+    }
+    mfma_finish<DT, MW, NW, WM, KG>(acc, a, lds, y, tid, kgrp, wm, wn, kg, n16, mblk0, yoff, b0, p0, db, PQ);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The pipelined form (tuning.pipeline = 1): the same tile, contraction and weight layout, but the
+// chunks of input channels are staged by waves of their own (tuning.producers of them, behind the
+// 4 * KG multiplying waves) into two LDS buffers, one chunk ahead of the multiplication.  The
+// multiplying waves run over the steps of all chunks in one loop -- the ring of weights in flight
+// never drains -- and meet the staging waves at one barrier per chunk: barrier k says "chunk k is
+// staged" and, with it, "chunk k - 1 has been multiplied" (so its buffer may take chunk k + 1).
+// The barriers wait for LDS traffic only (s_waitcnt lgkmcnt(0)): the weights a wave has in flight
+// from L2 stay in flight across them.  With KG = 2 the two groups take the even and the odd steps
+// of that one sequence.  Small chunks are the point: only the first is staged before any
+// multiplication starts, and the two buffers of a small chunk leave LDS for more workgroups.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+__global__ void __launch_bounds__(256 * KG + 256)
+mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                 const uint4w* __restrict__ wfrag, const MfmaArgs a)
+{
+    using X = typename Types<DT>::X;
+    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
+    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
+    constexpr int NTC = 256 * KG;                            // multiplying threads
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = wave8 >= 4 * KG;
+
+    const int grid = gridDim.x;
+    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int bt = fdiv19(wg, a.inv_ndb);
+    const int db = wg - bt * a.ndb;
+    const int bg = fdiv19(bt, a.inv_tiles_p);
+    const int tpi = bt - bg * a.tiles_p;
+    const int b0 = bg * a.NS, p0 = tpi * a.TP;
+    const int row0 = p0 * a.s_h - a.pad_h;
+    const int plane = a.H * a.W, PQ = a.P * a.Q;
+    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
+    const int CCB = a.CC / CB;                               // channel blocks per chunk (the last may have fewer)
+
+    StageArgs sa;
+    sa.nsv = min(a.NS, a.N - b0);
+    sa.ilo = max(0, -row0);
+    sa.nrows = max(0, min(a.Hs, a.H - row0) - sa.ilo);
+    sa.rlo = row0 + sa.ilo;
+    sa.wcols = min(a.W, a.Ws - a.pad_w);
+    const X* xb = x + (int64_t)b0 * a.C * plane;
+
+    if (producer) {
+        const int ptid = tid - NTC, pn = (int)blockDim.x - NTC;
+        for (int k = 0; k < a.nchunks; ++k) {
+            const int c0 = k * a.CC;
+            stage_chunk_epv<X, CV, true>(a.epv, xb + (int64_t)c0 * plane, lds + (k & 1) * a.bufsz, ptid, pn, cgroups, a.C - c0, sa, a, plane);
+            lds_barrier();                                   // barrier k
+        }
+        return;
+    }
+
+    const int kgrp = KG > 1 ? wave8 >> 2 : 0;
+    const int wave = wave8 & 3;
+    const int wm = wave % WM, wn = wave / WM;
+    const int n16 = lane & 15, kg = lane >> 4;
+
+    int bbase[NW];                                           // (filled in below, once the first loads are out)
+    int64_t yoff[NW];
+    Acc acc[MW][NW];
+    const int mblk0 = db * (a.DB >> 4) + wm * MW;
+    const int wrow = a.RS * a.NCB * 64;
+
+    // The steps of all chunks in one sequence: chunk, then filter tap, then channel block of the
+    // chunk.  What a step needs -- the byte offset of its tile operands in LDS, of its weights in
+    // the weight array, and its chunk -- is computed 64 steps at a time, one step per lane, and
+    // read back with v_readlane: the loop itself carries no cursor arithmetic and no branches
+    // but the barrier test.  Steps past the wave's last repeat the last (operands are prefetched
+    // without a test).
+    const int total = a.RS * a.NCB;
+    const int nsteps = KG > 1 ? (total - kgrp + KG - 1) / KG : total;    // this wave's steps
+    const int last = max(nsteps - 1, 0);
+    const int SPC = a.RS * CCB;                              // steps of a full chunk
+    auto table = [&](int base, int& vt, int& vw, int& vc) {
+        const int g = kgrp + KG * min(base + lane, last);
+        const int ch = fdiv19(g, a.inv_spc);
+        const int rem = g - ch * SPC;
+        const bool tail = ch == a.nchunks - 1;
+        const int cbs = tail ? a.cbs_last : CCB;
+        const int tap = fdiv19(rem, tail ? a.inv_cbs_last : a.inv_ccb);
+        const int cb = rem - tap * cbs;
+        const int r = fdiv19(tap, a.inv_S);
+        const int sx = tap - r * a.S;
+        vt = (ch & 1) * a.bufsz + (r * a.Ws + sx) * a.pitch + cb * (CB * (int)sizeof(X));
+        vw = (tap * a.NCB + ch * CCB + cb) * 1024;           // (64 lanes x 16 bytes per operand block)
+        vc = ch;
+    };
+    constexpr int PF = MW >= 4 ? 4 : 6;                      // steps of weights in flight
+    uint4w aq[PF][MW], bq[2][NW];
+    int wtab, xtab, ctab, unused0, unused1;
+    table(0, xtab, wtab, ctab);
+    int wi = 0, wbase = 0, xi = 0, xbase = 0, nbar = 0;
+    // the weights of this wave's row blocks: a wave-uniform base (per step) plus a per-lane offset
+    const unsigned char* wrows = reinterpret_cast<const unsigned char*>(wfrag) + (int64_t)mblk0 * wrow * 16;
+    unsigned woffm[MW];
+#pragma unroll
+    for (int m = 0; m < MW; ++m) woffm[m] = (unsigned)(m * wrow + lane) * 16u;
+    const unsigned char* wstep = wrows;
+    auto next_w = [&]() {                                    // the weight cursor moves on one step
+        if (wi == 64) { wbase += 64; wi = 0; table(wbase, unused0, wtab, unused1); }
+        wstep = wrows + __builtin_amdgcn_readlane(wtab, wi);
+        ++wi;
+    };
+    auto fetch_w1 = [&](uint4w& av, int m) { av = *reinterpret_cast<const uint4w*>(wstep + woffm[m]); };
+    auto fetch_x = [&](uint4w (&bv)[NW]) {
+        if (xi == 64) { xbase += 64; xi = 0; table(xbase, xtab, unused0, ctab); }
+        const int toff = __builtin_amdgcn_readlane(xtab, xi);
+        const int ch = __builtin_amdgcn_readlane(ctab, xi);
+        ++xi;
+        while (nbar <= ch) { lds_barrier(); ++nbar; }        // the chunk of this step is staged
+#pragma unroll
+        for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+    };
+    auto mfma1 = [&](Acc& c, const uint4w& av, const uint4w& bv) {
+        if constexpr (kIntActs<DT>)
+            c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av), __builtin_bit_cast(int4v_, bv), c, 0, 0, 0);
+        else
+            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av), __builtin_bit_cast(half8v, bv), c, 0, 0, 0);
+    };
+    if (nsteps > 0) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            next_w();
+#pragma unroll
+            for (int m = 0; m < MW; ++m) fetch_w1(aq[u][m], m);
+        }
+    }
+    // The padding of both buffers is written once, here, while the first chunk and the first
+    // weights are on their way (the staging waves went straight to their loads): staging never
+    // touches it, and the first barrier orders it before any read.
+    __builtin_amdgcn_sched_barrier(0);
+    stage_pad(lds, tid, NTC, cgroups, sa, a);
+    if (a.nchunks > 1) stage_pad(lds + a.bufsz, tid, NTC, cgroups, sa, a);
+
+    // positions of this lane's NW column blocks (as in the one-shot kernel), and the accumulators
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int f = ((wn * NW + i) * 16 + n16);
+        const int sm = fdiv19(f, a.inv_TPQ);
+        const int rem = f - sm * (a.TP * a.Q);
+        const int tp = fdiv19(rem, a.inv_Q);
+        const int tq = rem - tp * a.Q;
+        const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
+        bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+        yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
+    }
+
+#pragma unroll
+    for (int m = 0; m < MW; ++m)
+#pragma unroll
+        for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
+
+    if (nsteps > 0) {
+        fetch_x(bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int main_steps = nsteps / PF * PF;
+        for (int ks = 0; ks < main_steps; ks += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                // Step ks + u.  The tile operands of the next step are requested first; a row of
+                // weights is requested again (for step ks + u + PF) as soon as the matrix
+                // instructions that read it have been issued, so that the address arithmetic and
+                // the loads issue while the matrix pipe works.  The barrier at the end keeps the
+                // compiler from moving loads from one step into another.
+                fetch_x(bq[(u + 1) & 1]);
+                next_w();
+#pragma unroll
+                for (int m = 0; m < MW; ++m) {
+#pragma unroll
+                    for (int i = 0; i < NW; ++i) mfma1(acc[m][i], aq[u][m], bq[u & 1][i]);
+                    fetch_w1(aq[u][m], m);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < PF - 1; ++u) {
+            if (main_steps + u < nsteps) {
+                fetch_x(bq[(u + 1) & 1]);
+#pragma unroll
+                for (int m = 0; m < MW; ++m)
+#pragma unroll
+                    for (int i = 0; i < NW; ++i) mfma1(acc[m][i], aq[u][m], bq[u & 1][i]);
+            }
+        }
+    }
+    while (nbar < a.nchunks) { lds_barrier(); ++nbar; }      // (a wave without steps in the last chunks)
+    mfma_finish<DT, MW, NW, WM, KG>(acc, a, lds, y, tid, kgrp, wm, wn, kg, n16, mblk0, yoff, b0, p0, db, PQ);
+}
+
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, bool PIPE>
 static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
-    auto kernel = mfma_conv_kernel<DT, MW, NW, WM, KG>;
+    auto kernel = [] {
+        if constexpr (PIPE) return &mfma_pipe_kernel<DT, MW, NW, WM, KG>;
+        else return &mfma_conv_kernel<DT, MW, NW, WM, KG>;
+    }();
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -457,45 +709,45 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     });
     if (attr_err != hipSuccess) return SC_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG), p.mg.lds_bytes, stream, static_cast<const X*>(x),
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG + (PIPE ? 64 * p.mg.PW : 0)), p.mg.lds_bytes, stream, static_cast<const X*>(x),
                        static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
-template <sc_dtype_t DT, int MW, int NW, int WM>
+template <sc_dtype_t DT, int MW, int NW, int WM, bool PIPE>
 static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
-    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2>(p, a, x, y, grid, stream)
-                        : launch_mfma_kg<DT, MW, NW, WM, 1>(p, a, x, y, grid, stream);
+    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2, PIPE>(p, a, x, y, grid, stream)
+                        : launch_mfma_kg<DT, MW, NW, WM, 1, PIPE>(p, a, x, y, grid, stream);
 }
 
-template <sc_dtype_t DT, int MW, int WM>
+template <sc_dtype_t DT, int MW, int WM, bool PIPE>
 static sc_status_t launch_mfma_nw(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     switch (p.mg.NW) {
-        case 1: return launch_mfma_one<DT, MW, 1, WM>(p, a, x, y, grid, stream);
-        case 2: return launch_mfma_one<DT, MW, 2, WM>(p, a, x, y, grid, stream);
-        case 4: return launch_mfma_one<DT, MW, 4, WM>(p, a, x, y, grid, stream);
+        case 1: return launch_mfma_one<DT, MW, 1, WM, PIPE>(p, a, x, y, grid, stream);
+        case 2: return launch_mfma_one<DT, MW, 2, WM, PIPE>(p, a, x, y, grid, stream);
+        case 4: return launch_mfma_one<DT, MW, 4, WM, PIPE>(p, a, x, y, grid, stream);
         case 8:
-            if constexpr (MW <= 2) return launch_mfma_one<DT, MW, 8, WM>(p, a, x, y, grid, stream);
+            if constexpr (MW <= 2) return launch_mfma_one<DT, MW, 8, WM, PIPE>(p, a, x, y, grid, stream);
             break;
     }
     return SC_ERR_UNSUPPORTED;
 }
 
-template <sc_dtype_t DT>
+template <sc_dtype_t DT, bool PIPE>
 static sc_status_t launch_mfma_typed(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     const int key = p.mg.WM * 10 + p.mg.MW;
     switch (key) {
-        case 11: return launch_mfma_nw<DT, 1, 1>(p, a, x, y, grid, stream);
-        case 12: return launch_mfma_nw<DT, 2, 1>(p, a, x, y, grid, stream);
-        case 14: return launch_mfma_nw<DT, 4, 1>(p, a, x, y, grid, stream);
-        case 21: return launch_mfma_nw<DT, 1, 2>(p, a, x, y, grid, stream);
-        case 22: return launch_mfma_nw<DT, 2, 2>(p, a, x, y, grid, stream);
-        case 24: return launch_mfma_nw<DT, 4, 2>(p, a, x, y, grid, stream);
-        case 41: return launch_mfma_nw<DT, 1, 4>(p, a, x, y, grid, stream);
-        case 42: return launch_mfma_nw<DT, 2, 4>(p, a, x, y, grid, stream);
+        case 11: return launch_mfma_nw<DT, 1, 1, PIPE>(p, a, x, y, grid, stream);
+        case 12: return launch_mfma_nw<DT, 2, 1, PIPE>(p, a, x, y, grid, stream);
+        case 14: return launch_mfma_nw<DT, 4, 1, PIPE>(p, a, x, y, grid, stream);
+        case 21: return launch_mfma_nw<DT, 1, 2, PIPE>(p, a, x, y, grid, stream);
+        case 22: return launch_mfma_nw<DT, 2, 2, PIPE>(p, a, x, y, grid, stream);
+        case 24: return launch_mfma_nw<DT, 4, 2, PIPE>(p, a, x, y, grid, stream);
+        case 41: return launch_mfma_nw<DT, 1, 4, PIPE>(p, a, x, y, grid, stream);
+        case 42: return launch_mfma_nw<DT, 2, 4, PIPE>(p, a, x, y, grid, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }

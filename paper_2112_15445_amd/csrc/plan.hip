@@ -252,7 +252,11 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu == 0) t.wg_per_cu = 2;
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc || t.split_n || t.pipeline || t.producers || t.ragged || t.pack || t.tile_q || t.buffers || t.stage_rows) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.split_n || t.ragged || t.pack || t.tile_q || t.buffers || t.stage_rows) return SC_ERR_UNSUPPORTED;
+    // pipeline = 1: the chunks are staged by `producers` waves of their own (1 .. 4, default 2), one chunk ahead
+    if (t.pipeline != 0 && t.pipeline != 1) return SC_ERR_UNSUPPORTED;
+    if (t.producers < 0 || t.producers > 4 || (t.producers && !t.pipeline)) return SC_ERR_UNSUPPORTED;
+    const int PW = t.pipeline ? (t.producers ? t.producers : 2) : 0;
     const int budget = kMaxLdsBytes / t.wg_per_cu;
     const int CB = mfma_chan_block(p.dtype);
     // 256 threads: four waves; 512: two groups of four that split the steps of the contraction
@@ -280,9 +284,11 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     MfmaGeom g{};
     for (;;) {
         bool ok = false;
-        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG);
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG, PW);
         else
-            for (int cc = (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB) ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG);
+            // (one-shot: the largest chunk that fits; pipelined: small chunks are the point -- two blocks)
+            for (int cc = PW ? std::min(2 * CB, (L.C + CB - 1) / CB * CB) : (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB)
+                ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG, PW);
         if (ok) break;
         if (fixed_tile) return SC_ERR_UNSUPPORTED;
         // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
@@ -299,6 +305,8 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     r.tile_d = g.DB;
     r.waves_m = g.WM;
     r.wg_per_cu = t.wg_per_cu;
+    r.pipeline = PW ? 1 : 0;
+    r.producers = PW;
     *out = r;
     *mgeom = g;
     return SC_OK;
@@ -1028,6 +1036,22 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 }
                 for (int ns : {1, 2, 4, 8, 16}) {
                     sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
+                }
+                // the pipelined form (staging waves, chunks of one or two channel blocks): filters
+                // with several taps, where a chunk is multiplied for longer than it takes to stage
+                if (thr == 256 && wpc <= 2 && p.L.R * p.L.S > 1) {
+                    const int cb = mfma_chan_block(p.dtype);
+                    for (int cc : {cb, 2 * cb}) {
+                        if (cc >= p.L.C) continue;
+                        for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
+                            sc_tuning_t t = base(); t.pipeline = 1; t.producers = 4; t.chunk_c = cc;
+                            t.tile_p = std::min(tp, p.P);
+                            push(t);
+                        }
+                        for (int ns : {2, 4}) {
+                            sc_tuning_t t = base(); t.pipeline = 1; t.producers = 4; t.chunk_c = cc; t.tile_p = p.P; t.sub_batch = ns; push(t);
+                        }
+                    }
                 }
             }
         }

@@ -838,26 +838,34 @@ def test_dense_variant_on_the_matrix_cores(dtype):
         data = wl.prepare(l)
         ref = G.oracle_out(l, data)
         plan = G.make_plan(l, data)
-        ran = 0
+        ran = piped = 0
         for extra in ({}, {"tile_d": 16}, {"tile_d": 32, "tile_p": 1}, {"tile_d": 64, "tile_p": 2, "chunk_c": 64},
                       {"tile_d": 128, "wg_per_cu": 1}, {"tile_d": 64, "tile_p": 1000, "sub_batch": 4},
                       {"tile_d": 128, "waves_m": 2, "tile_p": 2}, {"tile_d": 128, "waves_m": 4}, {"tile_d": 64, "waves_m": 1, "tile_p": 3},
                       {"tile_d": 64, "waves_m": 2, "chunk_c": 64},
                       {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
                       {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
-            # four waves, and eight (two groups that split the steps of the contraction and meet in LDS)
+            # four waves, and eight (two groups that split the steps of the contraction and meet in LDS);
+            # one-shot staging, and the pipelined form (staging waves of their own, two chunk buffers)
+            cb = 64 if dtype in ("i8", "cb4") else 32
             for threads in (256, 512):
-                try:
-                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, **extra)
-                except B.SparseConvError as e:
-                    assert e.status == 4
-                    continue
-                t = plan.get_tuning()
-                assert t.variant == B.SC_VARIANT_DENSE and t.wg_threads == threads
-                print("case dense", name, dtype, t.as_dict(), flush=True)
-                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense {extra} {threads}")
-                ran += 1
-        assert ran >= 6, (name, ran)
+                for pipe in ({}, {"pipeline": 1}, {"pipeline": 1, "producers": 4, "chunk_c": cb}, {"pipeline": 1, "producers": 1, "chunk_c": 3 * cb}):
+                    if pipe and "chunk_c" in extra and "chunk_c" in pipe:
+                        continue
+                    kw = {**extra, **pipe}
+                    try:
+                        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, **kw)
+                    except B.SparseConvError as e:
+                        assert e.status == 4
+                        continue
+                    t = plan.get_tuning()
+                    assert t.variant == B.SC_VARIANT_DENSE and t.wg_threads == threads and t.pipeline == pipe.get("pipeline", 0)
+                    assert t.producers == (pipe.get("producers", 2) if pipe else 0)
+                    print("case dense", name, dtype, t.as_dict(), flush=True)
+                    G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense {kw} {threads}")
+                    ran += 1
+                    piped += 1 if pipe else 0
+        assert ran >= 6 and piped >= 6, (name, ran, piped)
         plan.destroy()
 
 
