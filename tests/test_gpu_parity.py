@@ -1004,7 +1004,11 @@ def test_fused_epilogue_relu_pool_requantise(dtype):
                                    (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2}),
                                    (B.SC_VARIANT_DENSE, {"tile_d": 128, "tile_p": 4, "waves_m": 4, "chunk_c": 64}),
                                    (B.SC_VARIANT_DENSE, {"wg_threads": 512}), (B.SC_VARIANT_DENSE, {"tile_d": 32, "tile_p": 2, "wg_threads": 512}),
-                                   (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2, "wg_threads": 512})):
+                                   (B.SC_VARIANT_DENSE, {"tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2, "wg_threads": 512}),
+                                   # the pipelined form: its staging waves are gone when the epilogue's barriers are met
+                                   (B.SC_VARIANT_DENSE, {"pipeline": 1}), (B.SC_VARIANT_DENSE, {"pipeline": 1, "tile_d": 32, "tile_p": 2, "producers": 1}),
+                                   (B.SC_VARIANT_DENSE, {"pipeline": 1, "tile_d": 64, "tile_p": 1000, "sub_batch": 3, "waves_m": 2, "wg_threads": 512, "producers": 4}),
+                                   (B.SC_VARIANT_DENSE, {"pipeline": 1, "wg_threads": 512, "tile_p": 2, "producers": 3})):
                 try:
                     plan.set_tuning(B.sc_tuning_t(), variant=variant, **extra)
                 except B.SparseConvError as e:
@@ -1187,7 +1191,8 @@ def test_forward_captured_in_a_hip_graph_replays_correctly():
     cases = (("f32", dict(variant=B.SC_VARIANT_GATHER, sub_batch=2)),
              ("f32", dict(variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, chunk_c=8, split_n=3, tile_p=3, wg_threads=256)),
              ("i8", dict(variant=B.SC_VARIANT_SLAB, wsrc=1, chunk_c=8, split_n=2, tile_p=3, wg_threads=256)),
-             ("f16", dict(variant=B.SC_VARIANT_DENSE, wg_threads=512)))
+             ("f16", dict(variant=B.SC_VARIANT_DENSE, wg_threads=512)),
+             ("i8", dict(variant=B.SC_VARIANT_DENSE, pipeline=1, producers=4, tile_p=3)))
     for dtype, tuning in cases:
         l = wl.Layer("graph", 40, 24, 9, 7, 3, 3, 1, 1, 1, 1, N=6, sparsity=0.7, dtype=dtype, seed=101)
         data = wl.prepare(l)
