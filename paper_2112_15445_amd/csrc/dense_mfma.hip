@@ -22,7 +22,11 @@
 //   * the weights are densified once per plan into MFMA-operand order, so a wave fetches an operand
 //     with one coalesced 1 KB load from global memory (L2-resident, shared by all workgroups);
 //   * every wave keeps MW x NW blocks of 16 x 16 accumulators in registers; several workgroups per
-//     CU overlap the staging of one with the multiplication of another.
+//     CU overlap the staging of one with the multiplication of another;
+//   * two kernels share this tile and the epilogue: the one-shot form (a chunk of input channels
+//     is staged by all waves, then multiplied; four waves, or eight that split the steps) and the
+//     pipelined form (waves of their own stage the chunks into two LDS buffers, one chunk ahead of
+//     the multiplying waves).
 // Integer results are exact (bit-identical to the gather kernels); f16 results differ from them in
 // summation order only.
 #include "dense_mfma_kernel.h"

@@ -503,6 +503,9 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
 // from L2 stay in flight across them.  With KG = 2 the two groups take the even and the odd steps
 // of that one sequence.  Small chunks are the point: only the first is staged before any
 // multiplication starts, and the two buffers of a small chunk leave LDS for more workgroups.
+// The staging waves end when the last chunk is staged; the barriers of the epilogue are then met
+// by the multiplying waves alone (a barrier waits only for the waves of a workgroup that have
+// not ended).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void lds_barrier()
 {

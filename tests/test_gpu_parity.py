@@ -1260,3 +1260,30 @@ def test_interleaved_samples_staged_by_rows():
         with pytest.raises(B.SparseConvError):
             plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_SLAB, wsrc=1, pack=3, stage_rows=1, chunk_c=8, tile_p=2)
         plan.destroy()
+
+
+def test_random_candidates_on_seeded_random_layers():
+    """Eighteen seeded layers of random geometry (filters 1x1 .. 5x5, strides, paddings, planes of 2 .. 20,
+    3 .. 130 channels, batches 1 .. 9, every type, unified and ragged tables), and on each about forty
+    of the autotuner's candidates drawn at random: each gives the oracle's result."""
+    for seed in range(18):
+        rng = np.random.default_rng(1000 + seed)
+        dtype = ["f32", "f16", "i8", "cb4", "cb4h", "f32"][seed % 6]
+        R, S = [(1, 1), (3, 3), (1, 3), (5, 5), (2, 2), (3, 1)][int(rng.integers(6))]
+        sh, sw = (int(rng.integers(1, 3)), int(rng.integers(1, 3))) if R * S > 1 else (1, 1)
+        ph, pw = int(rng.integers(0, R // 2 + 1)), int(rng.integers(0, S // 2 + 1))
+        H, W = int(rng.integers(max(R, 2), 21)), int(rng.integers(max(S, 2), 21))
+        C, D, N = int(rng.integers(3, 131)), int(rng.integers(3, 91)), int(rng.integers(1, 10))
+        sp = float(rng.uniform(0.3, 0.95))
+        l = wl.Layer(f"rand{seed}", C, D, H, W, R, S, sh, sw, ph, pw, N=N, sparsity=sp, dtype=dtype, seed=500 + seed)
+        data = wl.prepare(l, ragged=bool(seed & 1))
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        nc = plan.num_candidates()
+        pick = sorted(set(int(i) for i in rng.integers(0, nc, size=44)))
+        print(f"case rand{seed}: {dtype} C{C} D{D} {H}x{W} {R}x{S} s{sh},{sw} p{ph},{pw} N{N} sp{sp:.2f}: {nc} candidates, {len(pick)} drawn", flush=True)
+        for i in pick:
+            t = plan.candidate(i)
+            plan.set_tuning(t)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} candidate {i} { {k: v for k, v in t.as_dict().items() if v} }")
+        plan.destroy()
