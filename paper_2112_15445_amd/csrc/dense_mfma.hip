@@ -107,7 +107,7 @@ sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream)
 // ------------------------------------------------------------------------------------------------
 // Geometry of one (plan, tuning) pair, derived on the host.
 // ------------------------------------------------------------------------------------------------
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG, int PW)
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG, int PW, int nat)
 {
     const sc_layer_t& L = p.L;
     MfmaGeom g{};
@@ -125,6 +125,7 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     g.CC = std::min(CC, g.NCB * CB);
     g.nchunks = (g.NCB * CB + g.CC - 1) / g.CC;
     g.pitch = g.CC * p.ex + 16;                   // bytes per staged position: a multiple of 16, odd in units of 16
+    g.nat = nat;
     g.DB = DB;
     g.ndb = (L.D + DB - 1) / DB;
     // the four waves: WM along the output channels (MW 16-row blocks each), 4 / WM along the
@@ -144,8 +145,14 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     g.KG = KG;
     if (PW < 0 || PW > 4) return false;
     g.PW = PW;
+    if (nat) {
+        // natural layout: pointwise layers only, the one-shot form; a row of LDS per channel, as many
+        // columns as the waves' blocks cover, pitch a multiple of 64 bytes plus 32
+        if (nat != 1 || PW || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h || L.pad_w) return false;
+        g.pitch = (WN * g.NW * 16 * p.ex + 63) / 64 * 64 + 32;
+    }
     // the pipelined form keeps two chunk buffers (one if the layer is a single chunk)
-    g.bufsz = (int)(((int64_t)g.npos_s * g.pitch + 15) / 16 * 16);
+    g.bufsz = nat ? g.CC * g.pitch : (int)(((int64_t)g.npos_s * g.pitch + 15) / 16 * 16);
     int64_t lds = (int64_t)g.bufsz * (PW > 0 && g.nchunks > 1 ? 2 : 1);
     // pooling windows must not straddle tiles
     if (has_epilogue(p) && p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
@@ -192,8 +199,13 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     // elements per staging load: the widest power of two (up to 16 bytes) that divides the row length
     // and the caller's pointer
     a.epv = 1;
-    for (int e = 16 / p.ex; e > 1; e >>= 1)
-        if (p.L.W % e == 0 && reinterpret_cast<uintptr_t>(x) % (uintptr_t)(e * p.ex) == 0) { a.epv = e; break; }
+    a.TPQ = g.TP * p.Q;
+    for (int e = 16 / p.ex; e > 1; e >>= 1) {
+        // (natural layout: a run of the tile starts at a multiple of TP * Q inside its plane and is whole loads long)
+        const bool fits = g.nat ? (p.L.H * p.L.W) % e == 0 && (g.TP * p.Q) % e == 0 : p.L.W % e == 0;
+        if (fits && reinterpret_cast<uintptr_t>(x) % (uintptr_t)(e * p.ex) == 0) { a.epv = e; break; }
+    }
+    if (g.nat && (int64_t)g.CC * g.NS * g.TP * p.Q >= (1 << 19)) return SC_ERR_UNSUPPORTED;     // fdiv19() range of the copy
     a.inv_ndb = 1.0f / (float)g.ndb; a.inv_tiles_p = 1.0f / (float)g.tiles_p;
     a.inv_HsWs = 1.0f / (float)(g.Hs * g.Ws); a.inv_Ws = 1.0f / (float)g.Ws;
     a.inv_TPQ = 1.0f / (float)(g.TP * p.Q); a.inv_Q = 1.0f / (float)p.Q;
@@ -201,9 +213,13 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     switch (p.dtype) {
         // (the codebook variants were decoded when the weights were densified: same arithmetic)
         case SC_F16:
-        case SC_CB4_F16: return g.PW ? launch_mfma_pipe_f16(p, a, x, y, (int)grid, stream) : launch_mfma_f16(p, a, x, y, (int)grid, stream);
+        case SC_CB4_F16:
+            return g.nat ? launch_mfma_nat_f16(p, a, x, y, (int)grid, stream)
+                         : (g.PW ? launch_mfma_pipe_f16(p, a, x, y, (int)grid, stream) : launch_mfma_f16(p, a, x, y, (int)grid, stream));
         case SC_I8:
-        case SC_CB4_I8: return g.PW ? launch_mfma_pipe_i8(p, a, x, y, (int)grid, stream) : launch_mfma_i8(p, a, x, y, (int)grid, stream);
+        case SC_CB4_I8:
+            return g.nat ? launch_mfma_nat_i8(p, a, x, y, (int)grid, stream)
+                         : (g.PW ? launch_mfma_pipe_i8(p, a, x, y, (int)grid, stream) : launch_mfma_i8(p, a, x, y, (int)grid, stream));
         default: return SC_ERR_UNSUPPORTED;
     }
 }

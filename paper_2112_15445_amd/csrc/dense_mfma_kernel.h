@@ -32,6 +32,7 @@ struct MfmaArgs {
     // pipelined form: bytes of one of the two chunk buffers; channel blocks of the last chunk; reciprocals
     // of the steps per full chunk, of the channel blocks per chunk (full, last) and of S
     int bufsz, cbs_last;
+    int TPQ;                 // natural layout: positions of one sample in the tile (TP * Q)
     float inv_spc, inv_ccb, inv_cbs_last, inv_S;
     float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q;
     // fused epilogue (epi = 0: none): ReLU, 2 x 2 max-pooling, requantisation multipliers (or NULL),
@@ -44,6 +45,8 @@ sc_status_t launch_mfma_f16(const Plan& p, const MfmaArgs& a, const void* x, voi
 sc_status_t launch_mfma_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_pipe_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_pipe_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_nat_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_nat_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 
 // floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
 // product at least 1/(2d) away from every integer, well above the two float roundings)
@@ -176,6 +179,77 @@ struct StepCursor {
         }
     }
 };
+
+// ------------------------------------------------------------------------------------------------
+// Pointwise layers (1 x 1, unit stride, no padding), tuning.stage_rows = 1: the tile is staged in
+// its natural layout, [channel][position] -- the positions of a tile are one contiguous run per
+// (sample, channel) in NCHW, so staging is a plain copy with the widest loads the run lengths and
+// the pointer allow and no transposition in registers -- and the MFMA operands are read with
+// gfx950's transposing LDS reads.  ds_read_b64_tr_b16: in every group of 16 lanes, lane i receives
+// element i % 4 of the 8-byte words that lanes 4 j + i / 4 addressed, j = 0 .. 3; when lanes
+// 4 j .. 4 j + 3 address 16 consecutive positions of channel row j, lane i holds 4 channels of
+// position i -- half of a 16-bit operand (two reads).  ds_read_b64_tr_b8 is the same with 8 rows
+// of 16 one-byte positions (lanes 2 j, 2 j + 1 address row j): 8 channels per read.  Row pitch:
+// a multiple of 64 bytes plus 32, so that the rows of a group fall into different banks.
+// Columns past the tile's positions hold whatever LDS held (their outputs are not stored, and a
+// column only feeds its own output); channel rows past the layer's last are written as zeros.
+// ------------------------------------------------------------------------------------------------
+#define SC_LDS_AS __attribute__((address_space(3)))
+template <typename X>
+__device__ __forceinline__ uint4w read_operand_tr(const unsigned char* lds, int off, int pitch)
+{
+    uint4w r;
+    if constexpr (sizeof(X) == 2) {
+        typedef __attribute__((__vector_size__(4 * sizeof(__fp16)))) __fp16 h4;
+        const h4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4f16((SC_LDS_AS h4*)((SC_LDS_AS unsigned char*)lds + off));
+        const h4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4f16((SC_LDS_AS h4*)((SC_LDS_AS unsigned char*)lds + off + 4 * pitch));
+        __builtin_memcpy(&r, &lo, 8);
+        __builtin_memcpy(reinterpret_cast<unsigned char*>(&r) + 8, &hi, 8);
+    } else {
+        typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i2;
+        const i2 lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((SC_LDS_AS i2*)((SC_LDS_AS unsigned char*)lds + off));
+        const i2 hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((SC_LDS_AS i2*)((SC_LDS_AS unsigned char*)lds + off + 8 * pitch));
+        __builtin_memcpy(&r, &lo, 8);
+        __builtin_memcpy(reinterpret_cast<unsigned char*>(&r) + 8, &hi, 8);
+    }
+    return r;
+}
+#undef SC_LDS_AS
+
+// copy of one chunk: `rows` channel rows (the first min(rows, cleft) from memory, the rest zeros),
+// each nsv runs of cnt elements (cnt a multiple of EPV), run (sm, c) to columns sm * a.TPQ ...
+template <typename X, int EPV>
+__device__ __forceinline__ void stage_rows_nat(const X* __restrict__ xc, unsigned char* lds, int tid, int NT, int rows, int cleft,
+                                               int nsv, int cnt, const MfmaArgs& a, int plane)
+{
+    struct alignas(EPV * sizeof(X)) Vec { X e[EPV]; };
+    constexpr int VB = 8;                                  // loads in flight per thread
+    const int G = cnt / EPV, per_c = nsv * G;
+    const int live = min(rows, cleft);
+    const int nblocks = live * per_c;
+    const float inv_per_c = 1.0f / (float)max(per_c, 1), inv_G = 1.0f / (float)max(G, 1);
+    for (int v0 = tid; v0 < nblocks; v0 += NT * VB) {
+        Vec val[VB];
+        int dst[VB];
+#pragma unroll
+        for (int u = 0; u < VB; ++u) {
+            const int v = v0 + u * NT;
+            const int vv = v < nblocks ? v : 0;            // (past the end: block 0 again, not written)
+            const int c = fdiv19(vv, inv_per_c);
+            const int rem = vv - c * per_c;
+            const int sm = fdiv19(rem, inv_G);
+            const int g = rem - sm * G;
+            dst[u] = v < nblocks ? c * a.pitch + (sm * a.TPQ + g * EPV) * (int)sizeof(X) : -1;
+            val[u] = *reinterpret_cast<const Vec*>(xc + (int64_t)(sm * a.C + c) * plane + g * EPV);
+        }
+#pragma unroll
+        for (int u = 0; u < VB; ++u)
+            if (dst[u] >= 0) *reinterpret_cast<Vec*>(lds + dst[u]) = val[u];
+    }
+    const int w16 = a.pitch >> 4;                          // 16-byte words per row
+    for (int i = tid; i < (rows - live) * w16; i += NT)
+        *reinterpret_cast<uint4w*>(lds + live * a.pitch + i * 16) = uint4w{0u, 0u, 0u, 0u};
+}
 
 // ------------------------------------------------------------------------------------------------
 // What follows the contraction, shared by the kernels below: the step groups add up their
@@ -330,7 +404,7 @@ __device__ __forceinline__ void mfma_finish(Acc (&acc)[MW][NW], const MfmaArgs& 
 // steps of the contraction; their accumulators meet through LDS at the end (a fixed order: the
 // result does not depend on timing).  Two waves then share a SIMD, which is what the matrix
 // instructions need to issue back to back, at no more traffic: every operand is still fetched once.
-template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, bool NAT>
 __global__ void __launch_bounds__(256 * KG)
 mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                  const uint4w* __restrict__ wfrag, const MfmaArgs a)
@@ -376,7 +450,14 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
             const int tp = fdiv19(rem, a.inv_Q);
             const int tq = rem - tp * a.Q;
             const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
-            bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+            if constexpr (NAT) {
+                // the lane's part in the transposing reads of block i: row kg * 8 + n16 / 4 (16-bit) or
+                // kg * 16 + n16 / 2 (8-bit) of the channel block, the 8 bytes at position n16 % 4 * 4 (% 2 * 8)
+                constexpr int LPR = sizeof(X) == 2 ? 4 : 2;    // lanes per row of a group
+                bbase[i] = (kg * CV + n16 / LPR) * a.pitch + (wn * NW + i) * 16 * (int)sizeof(X) + (n16 % LPR) * 8;
+            } else {
+                bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+            }
             yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
         }
 
@@ -439,9 +520,15 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         };
         int xk = 0;
         auto fetch_x = [&](uint4w (&bv)[NW]) {
-            const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
+            if constexpr (NAT) {
+                const int toff = xc_.cb * CB * a.pitch;
 #pragma unroll
-            for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+                for (int i = 0; i < NW; ++i) bv[i] = read_operand_tr<X>(lds, bbase[i] + toff, a.pitch);
+            } else {
+                const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
+#pragma unroll
+                for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+            }
             xc_.template advance<KG>(cbs, a.S, xk < last);
             xk += xk < last ? 1 : 0;
         };
@@ -455,8 +542,20 @@ mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         {
             const X* xc = xb + (int64_t)c0 * plane;
             const int cleft = a.C - c0;                      // channels of the layer from c0 on
-            stage_chunk_epv<X, CV, false>(a.epv, xc, lds, tid, NT, cgroups, cleft, sa, a, plane);
-            stage_pad(lds, tid, NT, cgroups, sa, a);
+            if constexpr (NAT) {
+                const X* xt = xc + p0 * a.Q;                               // the tile's run of every (sample, channel)
+                const int cnt = min(a.TP, a.P - p0) * a.Q;                   // its length
+                switch (a.epv) {
+                    case 16: if constexpr (sizeof(X) == 1) { stage_rows_nat<X, 16>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); } break;
+                    case 8: stage_rows_nat<X, 8>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
+                    case 4: stage_rows_nat<X, 4>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
+                    case 2: stage_rows_nat<X, 2>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
+                    default: stage_rows_nat<X, 1>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
+                }
+            } else {
+                stage_chunk_epv<X, CV, false>(a.epv, xc, lds, tid, NT, cgroups, cleft, sa, a, plane);
+                stage_pad(lds, tid, NT, cgroups, sa, a);
+            }
         }
         __syncthreads();
         // ------------------------------------------------------------ multiply
@@ -696,14 +795,14 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     mfma_finish<DT, MW, NW, WM, KG>(acc, a, lds, y, tid, kgrp, wm, wn, kg, n16, mblk0, yoff, b0, p0, db, PQ);
 }
 
-template <sc_dtype_t DT, int MW, int NW, int WM, int KG, bool PIPE>
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, int MODE>
 static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
     auto kernel = [] {
-        if constexpr (PIPE) return &mfma_pipe_kernel<DT, MW, NW, WM, KG>;
-        else return &mfma_conv_kernel<DT, MW, NW, WM, KG>;
+        if constexpr (MODE == 1) return &mfma_pipe_kernel<DT, MW, NW, WM, KG>;
+        else return &mfma_conv_kernel<DT, MW, NW, WM, KG, MODE == 2>;
     }();
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -712,45 +811,45 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     });
     if (attr_err != hipSuccess) return SC_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG + (PIPE ? 64 * p.mg.PW : 0)), p.mg.lds_bytes, stream, static_cast<const X*>(x),
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG + (MODE == 1 ? 64 * p.mg.PW : 0)), p.mg.lds_bytes, stream, static_cast<const X*>(x),
                        static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }
 
-template <sc_dtype_t DT, int MW, int NW, int WM, bool PIPE>
+template <sc_dtype_t DT, int MW, int NW, int WM, int MODE>
 static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
-    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2, PIPE>(p, a, x, y, grid, stream)
-                        : launch_mfma_kg<DT, MW, NW, WM, 1, PIPE>(p, a, x, y, grid, stream);
+    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2, MODE>(p, a, x, y, grid, stream)
+                        : launch_mfma_kg<DT, MW, NW, WM, 1, MODE>(p, a, x, y, grid, stream);
 }
 
-template <sc_dtype_t DT, int MW, int WM, bool PIPE>
+template <sc_dtype_t DT, int MW, int WM, int MODE>
 static sc_status_t launch_mfma_nw(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     switch (p.mg.NW) {
-        case 1: return launch_mfma_one<DT, MW, 1, WM, PIPE>(p, a, x, y, grid, stream);
-        case 2: return launch_mfma_one<DT, MW, 2, WM, PIPE>(p, a, x, y, grid, stream);
-        case 4: return launch_mfma_one<DT, MW, 4, WM, PIPE>(p, a, x, y, grid, stream);
+        case 1: return launch_mfma_one<DT, MW, 1, WM, MODE>(p, a, x, y, grid, stream);
+        case 2: return launch_mfma_one<DT, MW, 2, WM, MODE>(p, a, x, y, grid, stream);
+        case 4: return launch_mfma_one<DT, MW, 4, WM, MODE>(p, a, x, y, grid, stream);
         case 8:
-            if constexpr (MW <= 2) return launch_mfma_one<DT, MW, 8, WM, PIPE>(p, a, x, y, grid, stream);
+            if constexpr (MW <= 2) return launch_mfma_one<DT, MW, 8, WM, MODE>(p, a, x, y, grid, stream);
             break;
     }
     return SC_ERR_UNSUPPORTED;
 }
 
-template <sc_dtype_t DT, bool PIPE>
+template <sc_dtype_t DT, int MODE>
 static sc_status_t launch_mfma_typed(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
     const int key = p.mg.WM * 10 + p.mg.MW;
     switch (key) {
-        case 11: return launch_mfma_nw<DT, 1, 1, PIPE>(p, a, x, y, grid, stream);
-        case 12: return launch_mfma_nw<DT, 2, 1, PIPE>(p, a, x, y, grid, stream);
-        case 14: return launch_mfma_nw<DT, 4, 1, PIPE>(p, a, x, y, grid, stream);
-        case 21: return launch_mfma_nw<DT, 1, 2, PIPE>(p, a, x, y, grid, stream);
-        case 22: return launch_mfma_nw<DT, 2, 2, PIPE>(p, a, x, y, grid, stream);
-        case 24: return launch_mfma_nw<DT, 4, 2, PIPE>(p, a, x, y, grid, stream);
-        case 41: return launch_mfma_nw<DT, 1, 4, PIPE>(p, a, x, y, grid, stream);
-        case 42: return launch_mfma_nw<DT, 2, 4, PIPE>(p, a, x, y, grid, stream);
+        case 11: return launch_mfma_nw<DT, 1, 1, MODE>(p, a, x, y, grid, stream);
+        case 12: return launch_mfma_nw<DT, 2, 1, MODE>(p, a, x, y, grid, stream);
+        case 14: return launch_mfma_nw<DT, 4, 1, MODE>(p, a, x, y, grid, stream);
+        case 21: return launch_mfma_nw<DT, 1, 2, MODE>(p, a, x, y, grid, stream);
+        case 22: return launch_mfma_nw<DT, 2, 2, MODE>(p, a, x, y, grid, stream);
+        case 24: return launch_mfma_nw<DT, 4, 2, MODE>(p, a, x, y, grid, stream);
+        case 41: return launch_mfma_nw<DT, 1, 4, MODE>(p, a, x, y, grid, stream);
+        case 42: return launch_mfma_nw<DT, 2, 4, MODE>(p, a, x, y, grid, stream);
     }
     return SC_ERR_UNSUPPORTED;
 }

@@ -4,6 +4,6 @@
 namespace sc {
 sc_status_t launch_mfma_pipe_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
-    return launch_mfma_typed<SC_F16, true>(p, a, x, y, grid, stream);
+    return launch_mfma_typed<SC_F16, 1>(p, a, x, y, grid, stream);
 }
 }  // namespace sc

@@ -4,6 +4,6 @@
 namespace sc {
 sc_status_t launch_mfma_pipe_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
-    return launch_mfma_typed<SC_I8, true>(p, a, x, y, grid, stream);
+    return launch_mfma_typed<SC_I8, 1>(p, a, x, y, grid, stream);
 }
 }  // namespace sc

@@ -252,7 +252,11 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu == 0) t.wg_per_cu = 2;
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc || t.split_n || t.ragged || t.pack || t.tile_q || t.buffers || t.stage_rows) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.split_n || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
+    // stage_rows = 1: pointwise layers staged in their natural layout (the one-shot form only)
+    if (t.stage_rows != 0 && t.stage_rows != 1) return SC_ERR_UNSUPPORTED;
+    if (t.stage_rows && (t.pipeline || !is_pointwise(L))) return SC_ERR_UNSUPPORTED;
+    const int nat = t.stage_rows;
     // pipeline = 1: the chunks are staged by `producers` waves of their own (1 .. 4, default 2), one chunk ahead
     if (t.pipeline != 0 && t.pipeline != 1) return SC_ERR_UNSUPPORTED;
     if (t.producers < 0 || t.producers > 4 || (t.producers && !t.pipeline)) return SC_ERR_UNSUPPORTED;
@@ -284,11 +288,11 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     MfmaGeom g{};
     for (;;) {
         bool ok = false;
-        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG, PW);
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG, PW, nat);
         else
             // (one-shot: the largest chunk that fits; pipelined: small chunks are the point -- two blocks)
             for (int cc = PW ? std::min(2 * CB, (L.C + CB - 1) / CB * CB) : (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB)
-                ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG, PW);
+                ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG, PW, nat);
         if (ok) break;
         if (fixed_tile) return SC_ERR_UNSUPPORTED;
         // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
@@ -307,6 +311,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     r.wg_per_cu = t.wg_per_cu;
     r.pipeline = PW ? 1 : 0;
     r.producers = PW;
+    r.stage_rows = nat;
     *out = r;
     *mgeom = g;
     return SC_OK;
@@ -1036,6 +1041,17 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                 }
                 for (int ns : {1, 2, 4, 8, 16}) {
                     sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
+                }
+                // pointwise layers whose planes are whole 8-byte loads: the same shapes on the natural layout
+                if (is_pointwise(p.L) && (p.L.H * p.L.W * p.ex) % 8 == 0) {
+                    { sc_tuning_t t = base(); t.stage_rows = 1; push(t); }
+                    for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
+                        if (tp >= p.P) continue;
+                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = tp; push(t);
+                    }
+                    for (int ns : {1, 2, 4}) {
+                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = p.P; t.sub_batch = ns; push(t);
+                    }
                 }
                 // the pipelined form (staging waves, chunks of one or two channel blocks): filters
                 // with several taps, where a chunk is multiplied for longer than it takes to stage

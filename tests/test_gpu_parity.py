@@ -1287,3 +1287,47 @@ def test_random_candidates_on_seeded_random_layers():
             plan.set_tuning(t)
             G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} candidate {i} { {k: v for k, v in t.as_dict().items() if v} }")
         plan.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8", "cb4", "cb4h"])
+def test_dense_variant_on_pointwise_layers_in_their_natural_layout(dtype):
+    """tuning.stage_rows = 1 on the matrix-core tile (pointwise layers): the tile is copied to LDS as
+    [channel][position] and read with the transposing LDS reads.  Planes whose runs are whole 16-,
+    8-, 4-, 2-byte loads and odd ones, several chunks with a last one that is not full, channels
+    that do not fill a block, tiles of rows and whole planes of several samples, batches that do
+    not fill the last group, four and eight waves; refused for filters with taps and with the
+    pipelined form."""
+    shapes = [("pw16", 150, 70, 8, 8, 7, 0.7), ("pw28", 64, 40, 28, 28, 3, 0.5), ("pw14", 200, 37, 14, 14, 5, 0.8),
+              ("pw7", 96, 48, 7, 7, 19, 0.9), ("pw5x6", 40, 130, 5, 6, 9, 0.6), ("pw_one_block", 24, 40, 9, 8, 3, 0.5)]
+    cb = 64 if dtype in ("i8", "cb4") else 32
+    for name, C, D, H, W, N, sp in shapes:
+        l = wl.Layer(name, C, D, H, W, 1, 1, 1, 1, 0, 0, N=N, sparsity=sp, dtype=dtype, seed=888)
+        data = wl.prepare(l)
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        ran = 0
+        for extra in ({}, {"tile_d": 16}, {"tile_d": 32, "tile_p": 1}, {"tile_d": 64, "tile_p": 2, "chunk_c": cb},
+                      {"tile_d": 128, "wg_per_cu": 1}, {"tile_d": 64, "tile_p": 1000, "sub_batch": 4, "chunk_c": 2 * cb},
+                      {"tile_d": 128, "waves_m": 2, "tile_p": 2}, {"tile_d": 64, "waves_m": 1, "tile_p": 3},
+                      {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
+                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
+            for threads in (256, 512):
+                try:
+                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, stage_rows=1, **extra)
+                except B.SparseConvError as e:
+                    assert e.status == 4
+                    continue
+                t = plan.get_tuning()
+                assert t.variant == B.SC_VARIANT_DENSE and t.stage_rows == 1 and t.wg_threads == threads
+                print("case dense natural", name, dtype, t.as_dict(), flush=True)
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense natural {extra} {threads}")
+                ran += 1
+        assert ran >= 6, (name, ran)
+        with pytest.raises(B.SparseConvError):
+            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, stage_rows=1, pipeline=1)
+        plan.destroy()
+    l = wl.Layer("taps", 32, 16, 8, 8, 3, 3, 1, 1, 1, 1, N=2, sparsity=0.5, dtype=dtype, seed=889)
+    plan = G.make_plan(l, wl.prepare(l))
+    with pytest.raises(B.SparseConvError):
+        plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, stage_rows=1)
+    plan.destroy()
