@@ -186,10 +186,12 @@ typedef struct {
                            word.  For unit strides (or strides of two) with tiles as wide as the plane
                            and rows that are whole 16- or 8-byte loads; a caller whose x is not 16-byte
                            aligned is served by the table form.  0 = by table.
-                           DENSE, pointwise layers (1 x 1, unit stride, no padding), one-shot form: 1 = the tile
+                           DENSE, pointwise layers (1 x 1, unit stride, no padding): 1 = the tile
                            is copied to LDS in its natural layout ([channel][position], plain wide loads, no
                            transposition in registers) and the matrix operands are read with gfx950's
-                           transposing LDS reads; same results as with 0 */
+                           transposing LDS reads; same results as with 0.  With pipeline = 1 the staging waves
+                           copy the chunks with direct-to-LDS loads: one sample per workgroup, runs and planes
+                           of whole 16-byte words, x 16-byte aligned (SC_ERR_UNSUPPORTED at launch otherwise) */
 } sc_tuning_t;
 
 typedef struct {

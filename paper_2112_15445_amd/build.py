@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparseconv.so")
-SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "dense_mfma_pipe_f16.hip", "dense_mfma_pipe_i8.hip", "dense_mfma_nat_f16.hip", "dense_mfma_nat_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip", "dense_library.hip"]
+SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "dense_mfma_pipe_f16.hip", "dense_mfma_pipe_i8.hip", "dense_mfma_nat_f16.hip", "dense_mfma_nat_i8.hip", "dense_mfma_pipe_nat_f16.hip", "dense_mfma_pipe_nat_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip", "dense_library.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -148,11 +148,19 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
     if (nat) {
         // natural layout: pointwise layers only, the one-shot form; a row of LDS per channel, as many
         // columns as the waves' blocks cover, pitch a multiple of 64 bytes plus 32
-        if (nat != 1 || PW || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h || L.pad_w) return false;
+        if (nat != 1 || L.R != 1 || L.S != 1 || L.stride_h != 1 || L.stride_w != 1 || L.pad_h || L.pad_w) return false;
         g.pitch = (WN * g.NW * 16 * p.ex + 63) / 64 * 64 + 32;
+        if (PW) {
+            // pipelined: the buffers are what the direct-to-LDS loads write -- rows back to back, one
+            // sample per workgroup, runs and planes whole 16-byte words
+            if (g.NS != 1 || (g.TP * p.Q * p.ex) % 16 || (L.H * L.W * p.ex) % 16) return false;
+            g.pitch = g.TP * p.Q * p.ex;
+        }
     }
     // the pipelined form keeps two chunk buffers (one if the layer is a single chunk)
     g.bufsz = nat ? g.CC * g.pitch : (int)(((int64_t)g.npos_s * g.pitch + 15) / 16 * 16);
+    // (unpadded rows: the blocks of the waves may reach past the end of the last row)
+    if (nat && PW) g.bufsz += (std::max(0, WN * g.NW * 16 * p.ex - g.pitch) + 15) / 16 * 16;
     int64_t lds = (int64_t)g.bufsz * (PW > 0 && g.nchunks > 1 ? 2 : 1);
     // pooling windows must not straddle tiles
     if (has_epilogue(p) && p.epi.pool && g.TP < p.P && (g.TP & 1)) return false;
@@ -206,6 +214,8 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
         if (fits && reinterpret_cast<uintptr_t>(x) % (uintptr_t)(e * p.ex) == 0) { a.epv = e; break; }
     }
     if (g.nat && (int64_t)g.CC * g.NS * g.TP * p.Q >= (1 << 19)) return SC_ERR_UNSUPPORTED;     // fdiv19() range of the copy
+    // (the direct-to-LDS copies of the pipelined natural-layout form move 16-byte words)
+    if (g.nat && g.PW && reinterpret_cast<uintptr_t>(x) % 16 != 0) return SC_ERR_UNSUPPORTED;
     a.inv_ndb = 1.0f / (float)g.ndb; a.inv_tiles_p = 1.0f / (float)g.tiles_p;
     a.inv_HsWs = 1.0f / (float)(g.Hs * g.Ws); a.inv_Ws = 1.0f / (float)g.Ws;
     a.inv_TPQ = 1.0f / (float)(g.TP * p.Q); a.inv_Q = 1.0f / (float)p.Q;
@@ -214,11 +224,11 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
         // (the codebook variants were decoded when the weights were densified: same arithmetic)
         case SC_F16:
         case SC_CB4_F16:
-            return g.nat ? launch_mfma_nat_f16(p, a, x, y, (int)grid, stream)
+            return g.nat ? (g.PW ? launch_mfma_pipe_nat_f16(p, a, x, y, (int)grid, stream) : launch_mfma_nat_f16(p, a, x, y, (int)grid, stream))
                          : (g.PW ? launch_mfma_pipe_f16(p, a, x, y, (int)grid, stream) : launch_mfma_f16(p, a, x, y, (int)grid, stream));
         case SC_I8:
         case SC_CB4_I8:
-            return g.nat ? launch_mfma_nat_i8(p, a, x, y, (int)grid, stream)
+            return g.nat ? (g.PW ? launch_mfma_pipe_nat_i8(p, a, x, y, (int)grid, stream) : launch_mfma_nat_i8(p, a, x, y, (int)grid, stream))
                          : (g.PW ? launch_mfma_pipe_i8(p, a, x, y, (int)grid, stream) : launch_mfma_i8(p, a, x, y, (int)grid, stream));
         default: return SC_ERR_UNSUPPORTED;
     }

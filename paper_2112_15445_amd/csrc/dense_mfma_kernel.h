@@ -7,6 +7,7 @@
 #include <type_traits>
 
 #include "sc_device.h"
+#include "sc_dma.h"
 #include "sc_internal.h"
 
 namespace sc {
@@ -47,6 +48,8 @@ sc_status_t launch_mfma_pipe_f16(const Plan& p, const MfmaArgs& a, const void* x
 sc_status_t launch_mfma_pipe_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_nat_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_nat_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_pipe_nat_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_pipe_nat_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 
 // floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
 // product at least 1/(2d) away from every integer, well above the two float roundings)
@@ -611,7 +614,11 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <sc_dtype_t DT, int MW, int NW, int WM, int KG>
+// NAT (pointwise layers, tuning.stage_rows = 1): the chunk buffers hold the tile in its natural
+// layout, [channel][position] with no padding between the rows -- the image the direct-to-LDS
+// loads of gfx950 write, so the staging waves copy a chunk without touching a register -- and the
+// operands are read with the transposing LDS reads (see above).  One sample per workgroup.
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, bool NAT>
 __global__ void __launch_bounds__(256 * KG + 256)
 mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                  const uint4w* __restrict__ wfrag, const MfmaArgs a)
@@ -651,7 +658,17 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const int ptid = tid - NTC, pn = (int)blockDim.x - NTC;
         for (int k = 0; k < a.nchunks; ++k) {
             const int c0 = k * a.CC;
-            stage_chunk_epv<X, CV, true>(a.epv, xb + (int64_t)c0 * plane, lds + (k & 1) * a.bufsz, ptid, pn, cgroups, a.C - c0, sa, a, plane);
+            if constexpr (NAT) {
+                // rows of this chunk (whole channel blocks), those of them that exist in the layer
+                const int rows = min(CCB, a.NCB - k * CCB) * CB, live = min(rows, a.C - c0);
+                unsigned char* buf = lds + (k & 1) * a.bufsz;
+                dma_tile<X>(xb + (int64_t)c0 * plane + p0 * a.Q, buf, live, a.TPQ, plane, p0 * a.Q, ptid >> 6, pn >> 6, lane, a.inv_TPQ);
+                for (int i = ptid; i < (rows - live) * a.pitch / 16; i += pn)
+                    *reinterpret_cast<uint4w*>(buf + live * a.pitch + i * 16) = uint4w{0u, 0u, 0u, 0u};
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies of this wave have landed
+            } else {
+                stage_chunk_epv<X, CV, true>(a.epv, xb + (int64_t)c0 * plane, lds + (k & 1) * a.bufsz, ptid, pn, cgroups, a.C - c0, sa, a, plane);
+            }
             lds_barrier();                                   // barrier k
         }
         return;
@@ -688,7 +705,8 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const int cb = rem - tap * cbs;
         const int r = fdiv19(tap, a.inv_S);
         const int sx = tap - r * a.S;
-        vt = (ch & 1) * a.bufsz + (r * a.Ws + sx) * a.pitch + cb * (CB * (int)sizeof(X));
+        vt = NAT ? (ch & 1) * a.bufsz + cb * CB * a.pitch
+                 : (ch & 1) * a.bufsz + (r * a.Ws + sx) * a.pitch + cb * (CB * (int)sizeof(X));
         vw = (tap * a.NCB + ch * CCB + cb) * 1024;           // (64 lanes x 16 bytes per operand block)
         vc = ch;
     };
@@ -716,7 +734,10 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         ++xi;
         while (nbar <= ch) { lds_barrier(); ++nbar; }        // the chunk of this step is staged
 #pragma unroll
-        for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+        for (int i = 0; i < NW; ++i) {
+            if constexpr (NAT) bv[i] = read_operand_tr<X>(lds, bbase[i] + toff, a.pitch);
+            else bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
+        }
     };
     auto mfma1 = [&](Acc& c, const uint4w& av, const uint4w& bv) {
         if constexpr (kIntActs<DT>)
@@ -736,8 +757,10 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
     // weights are on their way (the staging waves went straight to their loads): staging never
     // touches it, and the first barrier orders it before any read.
     __builtin_amdgcn_sched_barrier(0);
-    stage_pad(lds, tid, NTC, cgroups, sa, a);
-    if (a.nchunks > 1) stage_pad(lds + a.bufsz, tid, NTC, cgroups, sa, a);
+    if constexpr (!NAT) {
+        stage_pad(lds, tid, NTC, cgroups, sa, a);
+        if (a.nchunks > 1) stage_pad(lds + a.bufsz, tid, NTC, cgroups, sa, a);
+    }
 
     // positions of this lane's NW column blocks (as in the one-shot kernel), and the accumulators
 #pragma unroll
@@ -748,7 +771,12 @@ mfma_pipe_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>
         const int tp = fdiv19(rem, a.inv_Q);
         const int tq = rem - tp * a.Q;
         const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
-        bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+        if constexpr (NAT) {
+            constexpr int LPR = sizeof(X) == 2 ? 4 : 2;        // lanes per row of a group of the transposing read
+            bbase[i] = (kg * CV + n16 / LPR) * a.pitch + (wn * NW + i) * 16 * (int)sizeof(X) + (n16 % LPR) * 8;
+        } else {
+            bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
+        }
         yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
     }
 
@@ -801,7 +829,7 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
     using X = typename Types<DT>::X;
     using Y = typename Types<DT>::Y;
     auto kernel = [] {
-        if constexpr (MODE == 1) return &mfma_pipe_kernel<DT, MW, NW, WM, KG>;
+        if constexpr (MODE == 1 || MODE == 3) return &mfma_pipe_kernel<DT, MW, NW, WM, KG, MODE == 3>;
         else return &mfma_conv_kernel<DT, MW, NW, WM, KG, MODE == 2>;
     }();
     static std::once_flag once;
@@ -811,7 +839,7 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     });
     if (attr_err != hipSuccess) return SC_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG + (MODE == 1 ? 64 * p.mg.PW : 0)), p.mg.lds_bytes, stream, static_cast<const X*>(x),
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * KG + (MODE == 1 || MODE == 3 ? 64 * p.mg.PW : 0)), p.mg.lds_bytes, stream, static_cast<const X*>(x),
                        static_cast<Y*>(y), reinterpret_cast<const uint4w*>(p.d_wfrag), a);
     return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_HIP;
 }

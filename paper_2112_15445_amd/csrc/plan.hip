@@ -253,9 +253,9 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
     if (t.wsrc || t.split_n || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
-    // stage_rows = 1: pointwise layers staged in their natural layout (the one-shot form only)
+    // stage_rows = 1: pointwise layers staged in their natural layout (pipelined: by direct-to-LDS copies)
     if (t.stage_rows != 0 && t.stage_rows != 1) return SC_ERR_UNSUPPORTED;
-    if (t.stage_rows && (t.pipeline || !is_pointwise(L))) return SC_ERR_UNSUPPORTED;
+    if (t.stage_rows && !is_pointwise(L)) return SC_ERR_UNSUPPORTED;
     const int nat = t.stage_rows;
     // pipeline = 1: the chunks are staged by `producers` waves of their own (1 .. 4, default 2), one chunk ahead
     if (t.pipeline != 0 && t.pipeline != 1) return SC_ERR_UNSUPPORTED;
@@ -1051,6 +1051,18 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
                     }
                     for (int ns : {1, 2, 4}) {
                         sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = p.P; t.sub_batch = ns; push(t);
+                    }
+                    // ... and pipelined, the chunks copied by direct-to-LDS loads
+                    if (wpc <= 2) {
+                        const int cb = mfma_chan_block(p.dtype);
+                        for (int cc : {cb, 2 * cb, 4 * cb}) for (int np_ : {1, 2}) {
+                            if (cc >= p.L.C) continue;
+                            for (int tp : {1, 2, 4, 7, 8, 14, 16, 28}) {
+                                sc_tuning_t t = base(); t.stage_rows = 1; t.pipeline = 1; t.producers = np_; t.chunk_c = cc;
+                                t.tile_p = std::min(tp, p.P);
+                                push(t);
+                            }
+                        }
                     }
                 }
                 // the pipelined form (staging waves, chunks of one or two channel blocks): filters

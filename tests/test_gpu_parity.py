@@ -1323,8 +1323,24 @@ def test_dense_variant_on_pointwise_layers_in_their_natural_layout(dtype):
                 G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense natural {extra} {threads}")
                 ran += 1
         assert ran >= 6, (name, ran)
-        with pytest.raises(B.SparseConvError):
-            plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, stage_rows=1, pipeline=1)
+        # pipelined: the chunks are copied by direct-to-LDS loads (runs and planes of whole 16-byte words, one
+        # sample per workgroup); refused otherwise
+        piped = 0
+        for extra in ({}, {"tile_p": 1, "chunk_c": cb, "producers": 1}, {"tile_p": 2, "tile_d": 32, "producers": 4},
+                      {"tile_p": 4, "tile_d": 64, "waves_m": 1, "chunk_c": 3 * cb}, {"tile_p": 1000, "tile_d": 128, "chunk_c": cb}):
+            for threads in (256, 512):
+                try:
+                    plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, stage_rows=1, pipeline=1, **extra)
+                except B.SparseConvError as e:
+                    assert e.status == 4
+                    continue
+                t = plan.get_tuning()
+                assert t.stage_rows == 1 and t.pipeline == 1 and t.sub_batch == 1
+                print("case dense natural pipelined", name, dtype, t.as_dict(), flush=True)
+                G.check(l, G.run_gpu(plan, data["x"]), ref, f"{name} dense natural pipelined {extra} {threads}")
+                piped += 1
+        whole_words = (H * W * (1 if dtype in ("i8", "cb4") else 2)) % 16 == 0
+        assert (piped >= 2) == whole_words, (name, piped)
         plan.destroy()
     l = wl.Layer("taps", 32, 16, 8, 8, 3, 3, 1, 1, 1, 1, N=2, sparsity=0.5, dtype=dtype, seed=889)
     plan = G.make_plan(l, wl.prepare(l))
