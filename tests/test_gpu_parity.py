@@ -1347,3 +1347,33 @@ def test_dense_variant_on_pointwise_layers_in_their_natural_layout(dtype):
     with pytest.raises(B.SparseConvError):
         plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, stage_rows=1)
     plan.destroy()
+
+
+def test_natural_layout_candidates_on_seeded_random_pointwise_layers():
+    """Twelve seeded pointwise layers (planes of whole 16-byte words and odd ones, 3 .. 300 channels, batches
+    1 .. 11, the four 16- and 8-bit types) and on each up to thirty of the autotuner's natural-layout
+    candidates of the matrix-core tile (register copy and direct-to-LDS copy) drawn at random."""
+    ran = 0
+    for seed in range(12):
+        rng = np.random.default_rng(7000 + seed)
+        dtype = ["f16", "i8", "cb4h", "cb4"][seed % 4]
+        H, W = int(rng.integers(1, 9)) * 4, int(rng.integers(1, 9)) * 4
+        if seed % 3 == 0:
+            H, W = int(rng.integers(2, 30)), int(rng.integers(2, 30))
+        C, D, N = int(rng.integers(3, 300)), int(rng.integers(3, 200)), int(rng.integers(1, 12))
+        sp = float(rng.uniform(0.3, 0.95))
+        l = wl.Layer(f"rnat{seed}", C, D, H, W, 1, 1, 1, 1, 0, 0, N=N, sparsity=sp, dtype=dtype, seed=900 + seed)
+        data = wl.prepare(l, ragged=bool(seed & 1))
+        ref = G.oracle_out(l, data)
+        plan = G.make_plan(l, data)
+        nat = [i for i in range(plan.num_candidates())
+               if plan.candidate(i).stage_rows and plan.candidate(i).variant == B.SC_VARIANT_DENSE]
+        pick = [nat[int(i)] for i in sorted(set(rng.integers(0, len(nat), size=30)))] if nat else []
+        print(f"case rnat{seed}: {dtype} C{C} D{D} {H}x{W} N{N} sp{sp:.2f}: {len(nat)} natural-layout candidates, {len(pick)} drawn", flush=True)
+        for i in pick:
+            t = plan.candidate(i)
+            plan.set_tuning(t)
+            G.check(l, G.run_gpu(plan, data["x"]), ref, f"{l.name} candidate {i} { {k: v for k, v in t.as_dict().items() if v} }")
+            ran += 1
+        plan.destroy()
+    assert ran >= 150, ran
