@@ -413,7 +413,8 @@ def short_shape(t):
     if t.get("variant") == 3:
         return (f"mfma tp{t.get('tile_p', 0)} ns{t.get('sub_batch', 1)} cc{t.get('chunk_c', 0)} td{t.get('tile_d', 0)} "
                 f"wm{t.get('waves_m', 0)} wpc{t.get('wg_per_cu', 1)}" + (f" thr{t['wg_threads']}" if t.get("wg_threads", 256) > 256 else "")
-                + (f" pl1 np{t.get('producers', 0)}" if t.get("pipeline") else "") + (" nat" if t.get("stage_rows") else ""))
+                + (f" pl1 np{t.get('producers', 0)}" if t.get("pipeline") else "") + (" nat" if t.get("stage_rows") else "")
+                + (f" dl{t['split_n']}" if t.get("split_n") else ""))
     sh = "slab"
     if t.get("pipeline"):
         sh += f" pl{t['pipeline']}"

@@ -128,7 +128,11 @@ typedef struct {
                            partial sums into y with atomic adds (y is cleared by a small kernel first) -- for
                            layers with fewer tiles than CUs; at most as many as there are chunks.  fp32
                            results of such a shape depend on the order in which the workgroups arrive
-                           (last bits, within the tolerance of the type); int8 results do not */
+                           (last bits, within the tolerance of the type); int8 results do not.
+                           DENSE, one-shot form with four waves and the whole contraction in one chunk: 2..16 =
+                           a workgroup walks over that many blocks of tile_d output channels, one after the
+                           other, with its tile staged once and resident in LDS (for layers with few input
+                           and many output channels); same results as with 0 */
     int32_t pipeline;   /* SLAB, pointwise layers: 1 = persistent workgroups that stream tile i+1 into a
                            second LDS buffer (direct-to-LDS loads issued by dedicated waves) while
                            tile i is multiplied; needs wsrc != 0.  2 = the same double buffering with

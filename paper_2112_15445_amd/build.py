@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparseconv.so")
-SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "dense_mfma_pipe_f16.hip", "dense_mfma_pipe_i8.hip", "dense_mfma_nat_f16.hip", "dense_mfma_nat_i8.hip", "dense_mfma_pipe_nat_f16.hip", "dense_mfma_pipe_nat_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip", "dense_library.hip"]
+SOURCES = ["slab.hip", "dense_mfma_f16.hip", "dense_mfma_i8.hip", "dense_mfma_pipe_f16.hip", "dense_mfma_pipe_i8.hip", "dense_mfma_nat_f16.hip", "dense_mfma_nat_i8.hip", "dense_mfma_pipe_nat_f16.hip", "dense_mfma_pipe_nat_i8.hip", "dense_mfma_dl_f16.hip", "dense_mfma_dl_i8.hip", "plan.hip", "gather.hip", "dense_mfma.hip", "dense_library.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -27,7 +27,7 @@ def build(verbose: bool = False, jobs: int = 8, incremental: bool = False) -> st
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
         if incremental and os.path.exists(obj):
-            deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
+            deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith((".h", ".inc"))]
             deps.append(os.path.join(ROOT, "include", "sparse_conv.h"))
             if all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in deps):
                 continue

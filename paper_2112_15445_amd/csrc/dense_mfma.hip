@@ -107,7 +107,7 @@ sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream)
 // ------------------------------------------------------------------------------------------------
 // Geometry of one (plan, tuning) pair, derived on the host.
 // ------------------------------------------------------------------------------------------------
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG, int PW, int nat)
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG, int PW, int nat, int DL)
 {
     const sc_layer_t& L = p.L;
     MfmaGeom g{};
@@ -169,6 +169,10 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
         g.epi_pitch = (4 / g.WM) * g.NW * 16 + 1;
         lds = std::max<int64_t>(lds, (int64_t)g.DB * g.epi_pitch * 4);
     }
+    // several output-channel blocks per workgroup: the tile stays in LDS, so one chunk, no exchange through LDS
+    if (DL < 1 || DL > 16) return false;
+    g.DL = std::min(DL, g.ndb);
+    if (g.DL > 1 && (g.nchunks != 1 || KG != 1 || PW || (has_epilogue(p) && p.epi.pool))) return false;
     if (lds > lds_budget || lds > kMaxLdsBytes) return false;
     g.lds_bytes = (int)((lds + 15) / 16 * 16);
     *out = g;
@@ -178,14 +182,15 @@ bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int ld
 int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N)
 {
     (void)p;
-    return ((N + g.NS - 1) / g.NS) * g.tiles_p * g.ndb;
+    return ((N + g.NS - 1) / g.NS) * g.tiles_p * ((g.ndb + g.DL - 1) / g.DL);
 }
 
 sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream)
 {
     const MfmaGeom& g = p.mg;
     if (!p.d_wfrag) return SC_ERR_UNSUPPORTED;
-    const int64_t grid = (int64_t)((N + g.NS - 1) / g.NS) * g.tiles_p * g.ndb;
+    const int ndbg = (g.ndb + g.DL - 1) / g.DL;
+    const int64_t grid = (int64_t)((N + g.NS - 1) / g.NS) * g.tiles_p * ndbg;
     if (grid >= (1 << 19)) return SC_ERR_UNSUPPORTED;                       // fdiv19() range
     if ((int64_t)g.NS * p.L.C * p.L.H * p.L.W >= (1ll << 31)) return SC_ERR_UNSUPPORTED;
     MfmaArgs a{};
@@ -193,6 +198,7 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
     a.S = p.L.S; a.RS = p.L.R * p.L.S; a.s_h = p.L.stride_h; a.s_w = p.L.stride_w; a.pad_h = p.L.pad_h; a.pad_w = p.L.pad_w;
     a.TP = g.TP; a.NS = g.NS; a.tiles_p = g.tiles_p; a.Hs = g.Hs; a.Ws = g.Ws; a.npos_s = g.npos_s; a.npos = g.npos;
     a.bufsz = g.bufsz;
+    a.DL = g.DL; a.ndbg = ndbg; a.inv_ndbg = 1.0f / (float)ndbg;
     {
         const int ccb = g.CC / mfma_chan_block(p.dtype);
         a.cbs_last = g.NCB - (g.nchunks - 1) * ccb;
@@ -224,10 +230,12 @@ sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_
         // (the codebook variants were decoded when the weights were densified: same arithmetic)
         case SC_F16:
         case SC_CB4_F16:
+            if (g.DL > 1) return launch_mfma_dl_f16(p, a, x, y, (int)grid, stream);
             return g.nat ? (g.PW ? launch_mfma_pipe_nat_f16(p, a, x, y, (int)grid, stream) : launch_mfma_nat_f16(p, a, x, y, (int)grid, stream))
                          : (g.PW ? launch_mfma_pipe_f16(p, a, x, y, (int)grid, stream) : launch_mfma_f16(p, a, x, y, (int)grid, stream));
         case SC_I8:
         case SC_CB4_I8:
+            if (g.DL > 1) return launch_mfma_dl_i8(p, a, x, y, (int)grid, stream);
             return g.nat ? (g.PW ? launch_mfma_pipe_nat_i8(p, a, x, y, (int)grid, stream) : launch_mfma_nat_i8(p, a, x, y, (int)grid, stream))
                          : (g.PW ? launch_mfma_pipe_i8(p, a, x, y, (int)grid, stream) : launch_mfma_i8(p, a, x, y, (int)grid, stream));
         default: return SC_ERR_UNSUPPORTED;

@@ -34,6 +34,8 @@ struct MfmaArgs {
     // of the steps per full chunk, of the channel blocks per chunk (full, last) and of S
     int bufsz, cbs_last;
     int TPQ;                 // natural layout: positions of one sample in the tile (TP * Q)
+    int DL, ndbg;            // one-shot form: output-channel blocks per workgroup, groups of them (ndb / DL, rounded up)
+    float inv_ndbg;
     float inv_spc, inv_ccb, inv_cbs_last, inv_S;
     float inv_ndb, inv_tiles_p, inv_HsWs, inv_Ws, inv_TPQ, inv_Q;
     // fused epilogue (epi = 0: none): ReLU, 2 x 2 max-pooling, requantisation multipliers (or NULL),
@@ -50,6 +52,8 @@ sc_status_t launch_mfma_nat_f16(const Plan& p, const MfmaArgs& a, const void* x,
 sc_status_t launch_mfma_nat_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_pipe_nat_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 sc_status_t launch_mfma_pipe_nat_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_dl_f16(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
+sc_status_t launch_mfma_dl_i8(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream);
 
 // floor(e / d) for 0 <= e < 2^19 given inv = 1.0f / d (exact: the half-integer bias keeps the
 // product at least 1/(2d) away from every integer, well above the two float roundings)
@@ -412,186 +416,48 @@ __global__ void __launch_bounds__(256 * KG)
 mfma_conv_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
                  const uint4w* __restrict__ wfrag, const MfmaArgs a)
 {
-    using X = typename Types<DT>::X;
-    using Acc = typename std::conditional<kIntActs<DT>, int4v_, float4v>::type;
-    constexpr int CB = kChanBlock<DT>, CV = kChanVec<DT>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+#define SC_DL_DECODE const int bt = fdiv19(wg, a.inv_ndb); const int db = wg - bt * a.ndb;
+#define SC_DL_MBLK0 const int mblk0 = db * (a.DB >> 4) + wm * MW;            /* first 16-row block of this wave */
+#define SC_DL_BEGIN
+#define SC_DL_IF_FIRST
+#define SC_DL_END
+#include "dense_mfma_conv_body.inc"
+#undef SC_DL_DECODE
+#undef SC_DL_MBLK0
+#undef SC_DL_BEGIN
+#undef SC_DL_IF_FIRST
+#undef SC_DL_END
+}
 
-    constexpr int NT = 256 * KG;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kgrp = KG > 1 ? wave8 >> 2 : 0;               // which steps of the contraction this wave takes
-    const int wave = wave8 & 3;
-    const int wm = wave % WM, wn = wave / WM;
-    const int n16 = lane & 15, kg = lane >> 4;
-
-    // workgroup -> (sample group, row tile, output-channel block); the blocks of one tile are
-    // neighbours so that they find the tile in the L2 their siblings loaded.  Workgroups are dealt
-    // round-robin to the 8 XCDs: number them so that each XCD gets a contiguous run.
-    const int grid = gridDim.x;
-    const int wg = (grid & 7) == 0 ? (int)(blockIdx.x & 7) * (grid >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int bt = fdiv19(wg, a.inv_ndb);
-    const int db = wg - bt * a.ndb;
-    const int bg = fdiv19(bt, a.inv_tiles_p);
-    const int tpi = bt - bg * a.tiles_p;
-    const int b0 = bg * a.NS, p0 = tpi * a.TP;
-    const int row0 = p0 * a.s_h - a.pad_h;
-    const int plane = a.H * a.W, PQ = a.P * a.Q;
-
-    int bbase[NW];
-    int64_t yoff[NW];
-    Acc acc[MW][NW];
-    auto decode_positions = [&] {
-        // positions of this lane's NW column blocks: byte offset of the staged position in LDS (plus
-        // the lane's k group) and element offset of the output inside y, or -1
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const int f = ((wn * NW + i) * 16 + n16);
-            const int sm = fdiv19(f, a.inv_TPQ);
-            const int rem = f - sm * (a.TP * a.Q);
-            const int tp = fdiv19(rem, a.inv_Q);
-            const int tq = rem - tp * a.Q;
-            const bool ok = f < a.npos && b0 + sm < a.N && p0 + tp < a.P;
-            if constexpr (NAT) {
-                // the lane's part in the transposing reads of block i: row kg * 8 + n16 / 4 (16-bit) or
-                // kg * 16 + n16 / 2 (8-bit) of the channel block, the 8 bytes at position n16 % 4 * 4 (% 2 * 8)
-                constexpr int LPR = sizeof(X) == 2 ? 4 : 2;    // lanes per row of a group
-                bbase[i] = (kg * CV + n16 / LPR) * a.pitch + (wn * NW + i) * 16 * (int)sizeof(X) + (n16 % LPR) * 8;
-            } else {
-                bbase[i] = (ok ? ((sm * a.Hs + tp * a.s_h) * a.Ws + tq * a.s_w) * a.pitch : 0) + kg * 16;
-            }
-            yoff[i] = ok ? ((int64_t)(b0 + sm) * a.D) * PQ + (p0 + tp) * a.Q + tq : -1;
+// The same with tuning.split_n blocks of tile_d output channels per workgroup, one after the other: the
+// tile is staged once (a single chunk) and stays in LDS, and the stores of one block drain while the
+// next is multiplied -- for layers with few input and many output channels, where a workgroup per
+// block would spend its time starting, staging and draining.  Four waves, no exchange through LDS
+// (no pooling).
+template <sc_dtype_t DT, int MW, int NW, int WM, int KG, bool NAT>
+__global__ void __launch_bounds__(256 * KG)
+mfma_conv_dl_kernel(const typename Types<DT>::X* __restrict__ x, typename Types<DT>::Y* __restrict__ y,
+                    const uint4w* __restrict__ wfrag, const MfmaArgs a)
+{
+#define SC_DL_DECODE const int bt = fdiv19(wg, a.inv_ndbg); const int db0 = (wg - bt * a.ndbg) * a.DL;
+#define SC_DL_MBLK0
+#define SC_DL_BEGIN                                                                           \
+    for (int it = 0; it < a.DL; ++it) {                                                       \
+        const int db = db0 + it;                                                              \
+        if (db >= a.ndb) break;                                                               \
+        const int mblk0 = db * (a.DB >> 4) + wm * MW;                                         \
+        if (it > 0) {                                                                         \
+            _Pragma("unroll") for (int m = 0; m < MW; ++m)                                    \
+                _Pragma("unroll") for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};   \
         }
-
-#pragma unroll
-        for (int m = 0; m < MW; ++m)
-#pragma unroll
-            for (int i = 0; i < NW; ++i) acc[m][i] = Acc{0, 0, 0, 0};
-    };
-
-    decode_positions();
-    const int mblk0 = db * (a.DB >> 4) + wm * MW;            // first 16-row block of this wave
-    const int cgroups = a.CC / CV;                           // 16-byte channel groups per staged position
-
-    StageArgs sa;
-    sa.nsv = min(a.NS, a.N - b0);
-    sa.ilo = max(0, -row0);
-    sa.nrows = max(0, min(a.Hs, a.H - row0) - sa.ilo);
-    sa.rlo = row0 + sa.ilo;
-    sa.wcols = min(a.W, a.Ws - a.pad_w);
-    const X* xb = x + (int64_t)b0 * a.C * plane;
-    // the weights of row block m of this wave: a wave-uniform base, the lane adds its 16 bytes
-    const int wrow = a.RS * a.NCB * 64;                      // 16-byte words per 16-row block
-
-    auto multiply = [&](const uint4w (&av)[MW], const uint4w (&bv)[NW]) {
-#pragma unroll
-        for (int m = 0; m < MW; ++m)
-#pragma unroll
-            for (int i = 0; i < NW; ++i) {
-                if constexpr (kIntActs<DT>)
-                    acc[m][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v_, av[m]),
-                                                                      __builtin_bit_cast(int4v_, bv[i]), acc[m][i], 0, 0, 0);
-                else
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, av[m]),
-                                                                       __builtin_bit_cast(half8v, bv[i]), acc[m][i], 0, 0, 0);
-            }
-    };
-
-    for (int ch = 0; ch < a.nchunks; ++ch) {
-        const int c0 = ch * a.CC;
-        const int cbs = min(a.CC, a.NCB * CB - c0) / CB;     // channel blocks in this chunk
-        const int gcb0 = c0 / CB;
-        const int ksteps_all = a.RS * cbs;
-        // this wave's steps: kgrp, kgrp + KG, ... (local index 0 .. ksteps - 1)
-        const int ksteps = KG > 1 ? (ksteps_all - kgrp + KG - 1) / KG : ksteps_all;
-        const int last = ksteps - 1;
-        // The weights come from L2 (several hundred clocks away, against 32 clocks per MFMA): the
-        // operands of the next PF steps are kept in flight in a ring of registers.  The ring is
-        // filled before the chunk is staged, so that its latency hides behind the copy.
-        constexpr int PF = MW >= 4 ? 4 : 6;                  // steps of weights in flight (even)
-        uint4w aq[PF][MW], bq[2][NW];
-        StepCursor wc{0, 0, 0, 0}, xc_{0, 0, 0, 0};
-        if (KG > 1 && kgrp) { wc.advance(cbs, a.S, ksteps > 0); xc_.advance(cbs, a.S, ksteps > 0); }
-        int wk = 0;                                          // step the weight cursor stands on
-        auto fetch_w = [&](uint4w (&av)[MW]) {
-            const uint4w* wu = wfrag + ((int64_t)mblk0 * wrow + (wc.tap * a.NCB + gcb0 + wc.cb) * 64);
-#pragma unroll
-            for (int m = 0; m < MW; ++m) av[m] = wu[m * wrow + lane];
-            wc.template advance<KG>(cbs, a.S, wk < last);
-            wk += wk < last ? 1 : 0;
-        };
-        int xk = 0;
-        auto fetch_x = [&](uint4w (&bv)[NW]) {
-            if constexpr (NAT) {
-                const int toff = xc_.cb * CB * a.pitch;
-#pragma unroll
-                for (int i = 0; i < NW; ++i) bv[i] = read_operand_tr<X>(lds, bbase[i] + toff, a.pitch);
-            } else {
-                const int toff = (xc_.r * a.Ws + xc_.s) * a.pitch + xc_.cb * (CB * (int)sizeof(X));
-#pragma unroll
-                for (int i = 0; i < NW; ++i) bv[i] = *reinterpret_cast<const uint4w*>(lds + bbase[i] + toff);
-            }
-            xc_.template advance<KG>(cbs, a.S, xk < last);
-            xk += xk < last ? 1 : 0;
-        };
-        // (a wave without steps in this chunk -- the second group of a one-step chunk -- fetches nothing)
-        if (KG == 1 || ksteps > 0) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) fetch_w(aq[u]);
-        }
-        if (ch > 0) __syncthreads();     // the previous chunk has been multiplied
-        // ------------------------------------------------------------ stage the chunk, transposed
-        {
-            const X* xc = xb + (int64_t)c0 * plane;
-            const int cleft = a.C - c0;                      // channels of the layer from c0 on
-            if constexpr (NAT) {
-                const X* xt = xc + p0 * a.Q;                               // the tile's run of every (sample, channel)
-                const int cnt = min(a.TP, a.P - p0) * a.Q;                   // its length
-                switch (a.epv) {
-                    case 16: if constexpr (sizeof(X) == 1) { stage_rows_nat<X, 16>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); } break;
-                    case 8: stage_rows_nat<X, 8>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
-                    case 4: stage_rows_nat<X, 4>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
-                    case 2: stage_rows_nat<X, 2>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
-                    default: stage_rows_nat<X, 1>(xt, lds, tid, NT, cbs * CB, cleft, sa.nsv, cnt, a, plane); break;
-                }
-            } else {
-                stage_chunk_epv<X, CV, false>(a.epv, xc, lds, tid, NT, cgroups, cleft, sa, a, plane);
-                stage_pad(lds, tid, NT, cgroups, sa, a);
-            }
-        }
-        __syncthreads();
-        // ------------------------------------------------------------ multiply
-        if (KG == 1 || ksteps > 0) fetch_x(bq[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        const int main_steps = ksteps / PF * PF;
-        for (int ks = 0; ks < main_steps; ks += PF) {
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                // Step ks + u: request the tile operands of the next step (from LDS), multiply,
-                // then refill this step's slot of the weight ring with the weights of step
-                // ks + u + PF -- after the MFMAs that read the slot, so that the slot keeps its
-                // registers from one round of the ring to the next.  The scheduling barriers keep
-                // the compiler from sinking the loads of later steps down to their first use, which
-                // would put the L2 latency back on the critical path.
-                fetch_x(bq[(u + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(aq[u], bq[u & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch_w(aq[u]);
-            }
-        }
-        // the last ksteps % PF steps: their weights are in the first slots of the ring (the cursor
-        // stopped at the last step), their tile operands alternate as before
-#pragma unroll
-        for (int u = 0; u < PF - 1; ++u) {
-            if (main_steps + u < ksteps) {
-                fetch_x(bq[(u + 1) & 1]);
-                multiply(aq[u], bq[u & 1]);
-            }
-        }
-    }
-    mfma_finish<DT, MW, NW, WM, KG>(acc, a, lds, y, tid, kgrp, wm, wn, kg, n16, mblk0, yoff, b0, p0, db, PQ);
+#define SC_DL_IF_FIRST if (it == 0)
+#define SC_DL_END }
+#include "dense_mfma_conv_body.inc"
+#undef SC_DL_DECODE
+#undef SC_DL_MBLK0
+#undef SC_DL_BEGIN
+#undef SC_DL_IF_FIRST
+#undef SC_DL_END
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -830,6 +696,7 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
     using Y = typename Types<DT>::Y;
     auto kernel = [] {
         if constexpr (MODE == 1 || MODE == 3) return &mfma_pipe_kernel<DT, MW, NW, WM, KG, MODE == 3>;
+        else if constexpr (MODE == 4 || MODE == 5) return &mfma_conv_dl_kernel<DT, MW, NW, WM, KG, MODE == 5>;
         else return &mfma_conv_kernel<DT, MW, NW, WM, KG, MODE == 2>;
     }();
     static std::once_flag once;
@@ -847,8 +714,12 @@ static sc_status_t launch_mfma_kg(const Plan& p, const MfmaArgs& a, const void* 
 template <sc_dtype_t DT, int MW, int NW, int WM, int MODE>
 static sc_status_t launch_mfma_one(const Plan& p, const MfmaArgs& a, const void* x, void* y, int grid, hipStream_t stream)
 {
-    return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2, MODE>(p, a, x, y, grid, stream)
-                        : launch_mfma_kg<DT, MW, NW, WM, 1, MODE>(p, a, x, y, grid, stream);
+    if constexpr (MODE == 4 || MODE == 5) {               // (several output-channel blocks per workgroup: four waves)
+        return p.mg.KG == 1 ? launch_mfma_kg<DT, MW, NW, WM, 1, MODE>(p, a, x, y, grid, stream) : SC_ERR_UNSUPPORTED;
+    } else {
+        return p.mg.KG == 2 ? launch_mfma_kg<DT, MW, NW, WM, 2, MODE>(p, a, x, y, grid, stream)
+                            : launch_mfma_kg<DT, MW, NW, WM, 1, MODE>(p, a, x, y, grid, stream);
+    }
 }
 
 template <sc_dtype_t DT, int MW, int WM, int MODE>

@@ -252,7 +252,10 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     if (t.wg_per_cu == 0) t.wg_per_cu = 2;
     if (t.wg_per_cu < 1 || t.wg_per_cu > 8) return SC_ERR_UNSUPPORTED;
     if (t.tile_p < 0 || t.sub_batch < 0 || t.chunk_c < 0 || t.tile_d < 0) return SC_ERR_UNSUPPORTED;
-    if (t.wsrc || t.split_n || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
+    if (t.wsrc || t.ragged || t.pack || t.tile_q || t.buffers) return SC_ERR_UNSUPPORTED;
+    // split_n = 2 .. 16: the workgroup walks over that many blocks of tile_d output channels, the tile resident in LDS
+    if (t.split_n < 0 || t.split_n > 16) return SC_ERR_UNSUPPORTED;
+    const int DL = std::max(1, t.split_n);
     // stage_rows = 1: pointwise layers staged in their natural layout (pipelined: by direct-to-LDS copies)
     if (t.stage_rows != 0 && t.stage_rows != 1) return SC_ERR_UNSUPPORTED;
     if (t.stage_rows && !is_pointwise(L)) return SC_ERR_UNSUPPORTED;
@@ -288,11 +291,11 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     MfmaGeom g{};
     for (;;) {
         bool ok = false;
-        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG, PW, nat);
+        if (t.chunk_c) ok = mfma_geometry(p, TP, NS, t.chunk_c, DB, WM, budget, &g, KG, PW, nat, DL);
         else
             // (one-shot: the largest chunk that fits; pipelined: small chunks are the point -- two blocks)
             for (int cc = PW ? std::min(2 * CB, (L.C + CB - 1) / CB * CB) : (L.C + CB - 1) / CB * CB; cc >= CB && !ok; cc -= CB)
-                ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG, PW, nat);
+                ok = mfma_geometry(p, TP, NS, cc, DB, WM, budget, &g, KG, PW, nat, DL);
         if (ok) break;
         if (fixed_tile) return SC_ERR_UNSUPPORTED;
         // heuristic tile too large for LDS or for the waves: fewer samples, then fewer rows
@@ -312,6 +315,7 @@ static sc_status_t resolve_dense(const Plan& p, sc_tuning_t t, sc_tuning_t* out,
     r.pipeline = PW ? 1 : 0;
     r.producers = PW;
     r.stage_rows = nat;
+    r.split_n = g.DL > 1 ? g.DL : 0;
     *out = r;
     *mgeom = g;
     return SC_OK;
@@ -1034,23 +1038,30 @@ static void build_candidates(const Plan& p, std::vector<sc_tuning_t>* out)
             if (db % (16 * wm) || db / (16 * wm) > 4 || (db > 32 && db >= 2 * p.L.D)) continue;
             for (int thr : {256, 512}) {
                 auto base = [&]() { sc_tuning_t t{}; t.variant = SC_VARIANT_DENSE; t.tile_d = db; t.waves_m = wm; t.wg_per_cu = wpc; t.wg_threads = thr; return t; };
-                push(base());
+                // (with several blocks of output channels in the layer: also 2, 4 or 8 of them per workgroup,
+                // one after the other on the resident tile)
+                auto pushd = [&](sc_tuning_t t) {
+                    push(t);
+                    if (thr == 256 && db < p.L.D)
+                        for (int dl : {2, 4, 8}) { t.split_n = dl; push(t); }
+                };
+                pushd(base());
                 for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
                     if (tp >= p.P) continue;
-                    sc_tuning_t t = base(); t.tile_p = tp; push(t);
+                    sc_tuning_t t = base(); t.tile_p = tp; pushd(t);
                 }
                 for (int ns : {1, 2, 4, 8, 16}) {
-                    sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; push(t);
+                    sc_tuning_t t = base(); t.tile_p = p.P; t.sub_batch = ns; pushd(t);
                 }
                 // pointwise layers whose planes are whole 8-byte loads: the same shapes on the natural layout
                 if (is_pointwise(p.L) && (p.L.H * p.L.W * p.ex) % 8 == 0) {
-                    { sc_tuning_t t = base(); t.stage_rows = 1; push(t); }
+                    { sc_tuning_t t = base(); t.stage_rows = 1; pushd(t); }
                     for (int tp : {1, 2, 4, 7, 8, 14, 16}) {
                         if (tp >= p.P) continue;
-                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = tp; push(t);
+                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = tp; pushd(t);
                     }
                     for (int ns : {1, 2, 4}) {
-                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = p.P; t.sub_batch = ns; push(t);
+                        sc_tuning_t t = base(); t.stage_rows = 1; t.tile_p = p.P; t.sub_batch = ns; pushd(t);
                     }
                     // ... and pipelined, the chunks copied by direct-to-LDS loads
                     if (wpc <= 2) {

@@ -72,6 +72,7 @@ struct MfmaGeom {
     int PW;                // pipelined form: waves that stage the chunks (0 = the one-shot form)
     int bufsz;             // bytes of one chunk buffer
     int nat;               // 1 = pointwise layer staged in its natural layout ([channel][position])
+    int DL;                // one-shot form: blocks of DB output channels a workgroup walks over (1 = one)
     int lds_bytes;
     int epi_pitch;         // elements per output-channel row of the LDS exchange of the fused epilogue
 };
@@ -150,7 +151,7 @@ void library_conv_destroy(LibraryConv* c);
 int mfma_chan_block(sc_dtype_t dt);
 size_t mfma_weight_bytes(const Plan& p);
 sc_status_t mfma_densify(const Plan& p, unsigned char* out, hipStream_t stream);
-bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG = 1, int PW = 0, int nat = 0);
+bool mfma_geometry(const Plan& p, int TP, int NS, int CC, int DB, int WM, int lds_budget, MfmaGeom* out, int KG = 1, int PW = 0, int nat = 0, int DL = 1);
 inline bool has_epilogue(const Plan& p) { return p.epi.relu || p.epi.pool || p.epi.requant; }
 int mfma_grid_size(const Plan& p, const MfmaGeom& g, int N);
 sc_status_t launch_mfma(const Plan& p, const void* x, void* y, int N, hipStream_t stream);

@@ -844,7 +844,10 @@ def test_dense_variant_on_the_matrix_cores(dtype):
                       {"tile_d": 128, "waves_m": 2, "tile_p": 2}, {"tile_d": 128, "waves_m": 4}, {"tile_d": 64, "waves_m": 1, "tile_p": 3},
                       {"tile_d": 64, "waves_m": 2, "chunk_c": 64},
                       {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
-                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
+                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1},
+                      # several blocks of output channels per workgroup, one after the other on the resident tile
+                      {"tile_d": 16, "split_n": 2}, {"tile_d": 32, "tile_p": 2, "split_n": 3}, {"tile_d": 16, "tile_p": 1, "split_n": 16},
+                      {"tile_d": 64, "waves_m": 2, "split_n": 2, "tile_p": 1000, "sub_batch": 2}):
             # four waves, and eight (two groups that split the steps of the contraction and meet in LDS);
             # one-shot staging, and the pipelined form (staging waves of their own, two chunk buffers)
             cb = 64 if dtype in ("i8", "cb4") else 32
@@ -1310,7 +1313,8 @@ def test_dense_variant_on_pointwise_layers_in_their_natural_layout(dtype):
                       {"tile_d": 128, "wg_per_cu": 1}, {"tile_d": 64, "tile_p": 1000, "sub_batch": 4, "chunk_c": 2 * cb},
                       {"tile_d": 128, "waves_m": 2, "tile_p": 2}, {"tile_d": 64, "waves_m": 1, "tile_p": 3},
                       {"tile_d": 32, "waves_m": 2, "tile_p": 1000, "sub_batch": 3},
-                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1}):
+                      {"tile_d": 32, "tile_p": 1000, "sub_batch": 16, "chunk_c": 128, "wg_per_cu": 1},
+                      {"tile_d": 16, "split_n": 2}, {"tile_d": 32, "tile_p": 2, "split_n": 3}, {"tile_d": 16, "tile_p": 1, "split_n": 16}):
             for threads in (256, 512):
                 try:
                     plan.set_tuning(B.sc_tuning_t(), variant=B.SC_VARIANT_DENSE, wg_threads=threads, stage_rows=1, **extra)
